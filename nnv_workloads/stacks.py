@@ -1,0 +1,148 @@
+"""Conv-layer shape lists for the five synthetic workloads.
+
+The paper evaluates whole trained CNNs (Table 4: MobileNetV2, ResNet-18,
+ResNet-50, ... at 224x224 input, batch 1).  Only the *shapes* of their
+convolution layers matter for the transform/execute trade-off (Section 3.1,
+Table 2), so each workload here is the list of conv layers of such a network;
+pooling, batch-norm, activations and residual adds are not modelled and every
+layer gets its own random input of the right shape.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List
+
+
+@dataclass(frozen=True)
+class ConvLayer:
+    """One 2-D convolution: x[n,c,h,w] (*) w[k,c/groups,r,s] -> y[n,k,p,q]."""
+    name: str
+    c: int
+    h: int
+    w: int
+    k: int
+    r: int
+    s: int
+    stride: int
+    pad: int
+    groups: int = 1
+    n: int = 1
+
+    @property
+    def p(self) -> int:
+        return (self.h + 2 * self.pad - self.r) // self.stride + 1
+
+    @property
+    def q(self) -> int:
+        return (self.w + 2 * self.pad - self.s) // self.stride + 1
+
+    @property
+    def cg(self) -> int:
+        """Input channels per group (second dim of the OIHW weight tensor)."""
+        return self.c // self.groups
+
+    @property
+    def params(self) -> int:
+        return self.k * self.cg * self.r * self.s
+
+    @property
+    def macs(self) -> int:
+        return self.n * self.k * self.p * self.q * self.cg * self.r * self.s
+
+    @property
+    def is_depthwise(self) -> bool:
+        return self.groups == self.c and self.groups == self.k and self.groups > 1
+
+    @property
+    def winograd_ok(self) -> bool:
+        return (self.r == 3 and self.s == 3 and self.stride == 1 and self.groups == 1)
+
+
+STACK_NAMES = ("single3x3", "resnet18", "mobilenetv2", "vgg16", "resnet50")
+
+
+def _single() -> List[ConvLayer]:
+    return [ConvLayer("conv3x3_16_32", 16, 32, 32, 16, 3, 3, 1, 1)]
+
+
+def _resnet18() -> List[ConvLayer]:
+    L = [ConvLayer("stem7x7", 3, 224, 224, 64, 7, 7, 2, 3)]
+    # after the stem's 3x3/2 max-pool the feature map is 56x56
+    for i in range(4):
+        L.append(ConvLayer(f"l1_conv{i}", 64, 56, 56, 64, 3, 3, 1, 1))
+    cin, hw = 64, 56
+    for stage, width in ((2, 128), (3, 256), (4, 512)):
+        L.append(ConvLayer(f"l{stage}_conv0_s2", cin, hw, hw, width, 3, 3, 2, 1))
+        L.append(ConvLayer(f"l{stage}_down1x1_s2", cin, hw, hw, width, 1, 1, 2, 0))
+        hw //= 2
+        for i in range(1, 4):
+            L.append(ConvLayer(f"l{stage}_conv{i}", width, hw, hw, width, 3, 3, 1, 1))
+        cin = width
+    return L
+
+
+def _mobilenetv2() -> List[ConvLayer]:
+    # (expansion t, output width c, repeats n, first stride s) of the published
+    # inverted-residual schedule; 3x3/2 stem to 32 channels, final 1x1 to 1280.
+    sched = ((1, 16, 1, 1), (6, 24, 2, 2), (6, 32, 3, 2), (6, 64, 4, 2),
+             (6, 96, 3, 1), (6, 160, 3, 2), (6, 320, 1, 1))
+    L = [ConvLayer("stem3x3_s2", 3, 224, 224, 32, 3, 3, 2, 1)]
+    cin, hw = 32, 112
+    b = 0
+    for t, cout, reps, s0 in sched:
+        for i in range(reps):
+            st = s0 if i == 0 else 1
+            hid = cin * t
+            if t != 1:
+                L.append(ConvLayer(f"b{b}_expand", cin, hw, hw, hid, 1, 1, 1, 0))
+            L.append(ConvLayer(f"b{b}_dw_s{st}", hid, hw, hw, hid, 3, 3, st, 1, groups=hid))
+            hw = (hw + 2 - 3) // st + 1
+            L.append(ConvLayer(f"b{b}_project", hid, hw, hw, cout, 1, 1, 1, 0))
+            cin = cout
+            b += 1
+    L.append(ConvLayer("head1x1", cin, hw, hw, 1280, 1, 1, 1, 0))
+    return L
+
+
+def _vgg16() -> List[ConvLayer]:
+    cfg = ((224, (64, 64)), (112, (128, 128)), (56, (256, 256, 256)),
+           (28, (512, 512, 512)), (14, (512, 512, 512)))
+    L, cin = [], 3
+    for hw, widths in cfg:
+        for i, wd in enumerate(widths):
+            L.append(ConvLayer(f"conv{hw}_{i}", cin, hw, hw, wd, 3, 3, 1, 1))
+            cin = wd
+    return L
+
+
+def _resnet50() -> List[ConvLayer]:
+    # Bottleneck blocks; the stride of a stage's first block sits on its first
+    # 1x1 conv, so every 3x3 conv has stride 1.
+    L = [ConvLayer("stem7x7", 3, 224, 224, 64, 7, 7, 2, 3)]
+    cin, hw = 64, 56
+    for stage, (width, blocks) in enumerate(((64, 3), (128, 4), (256, 6), (512, 3)), start=1):
+        for b in range(blocks):
+            st = 2 if (b == 0 and stage > 1) else 1
+            hout = hw // st
+            L.append(ConvLayer(f"s{stage}b{b}_reduce1x1", cin, hw, hw, width, 1, 1, st, 0))
+            L.append(ConvLayer(f"s{stage}b{b}_conv3x3", width, hout, hout, width, 3, 3, 1, 1))
+            L.append(ConvLayer(f"s{stage}b{b}_expand1x1", width, hout, hout, 4 * width, 1, 1, 1, 0))
+            if b == 0:
+                L.append(ConvLayer(f"s{stage}b{b}_down1x1", cin, hw, hw, 4 * width, 1, 1, st, 0))
+            cin, hw = 4 * width, hout
+    return L
+
+
+_BUILDERS = {"single3x3": _single, "resnet18": _resnet18, "mobilenetv2": _mobilenetv2,
+             "vgg16": _vgg16, "resnet50": _resnet50}
+
+
+def stack(name: str) -> List[ConvLayer]:
+    """Layer list of one workload; `name` is one of STACK_NAMES."""
+    return _BUILDERS[name]()
+
+
+def table2_layer(hw: int = 56) -> ConvLayer:
+    """A layer shaped like the one Table 2 times (3x3, stride 1, 64 -> 192
+    channels); the paper does not state its spatial size, so `hw` is a guess."""
+    return ConvLayer(f"table2_64to192_{hw}", 64, hw, hw, 192, 3, 3, 1, 1)
