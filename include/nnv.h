@@ -1,0 +1,152 @@
+/* nnv.h -- C ABI of the conv hot path behind NNV12-style cold inference on MI355X.
+ *
+ * The paper splits every operator of a cold inference into operations: reading
+ * the weights, transforming them into the layout a kernel wants (w_i) and
+ * executing the kernel (e_i); its scheduler chooses, per conv layer, which
+ * kernel alternative to use from the measured cost of those operations
+ * (Section 3.1.1 kernel selection, Table 2, Section 3.2, Algorithm 1's
+ * profiling input).  This library is the w_i and e_i of a convolution for five
+ * kernel alternatives, plus the per-operation timing the selection needs.
+ *
+ * All data pointers are DEVICE pointers unless a parameter says "host".  The
+ * caller owns every buffer; the library allocates no device memory and keeps
+ * no mutable global state.  Device buffers must be 16-byte aligned.  Work is
+ * enqueued on the given HIP stream (a hipStream_t passed as void*, NULL = the
+ * default stream) and the call returns without waiting, except nnv_time_layer.
+ * Every function returns NNV_OK (0) or a negative nnv_status; none aborts or
+ * throws.
+ *
+ * Tensors at the boundary: x is NCHW, y is NKPQ, raw weights are OIHW
+ * (K, C/groups, R, S) and ALWAYS float32.  desc.dtype is the storage type of x,
+ * y and the transformed weights; accumulation is float32 in both cases.
+ * Convolution means zero-padded cross-correlation, dilation 1,
+ * P = floor((H + 2*pad_h - R)/stride_h) + 1.
+ */
+#ifndef NNV_H
+#define NNV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Kernel alternatives of the conv operator (Section 3.1.1, Fig. 5, Table 2 name
+ * winograd, sgemm, direct and depthwise families). */
+typedef enum {
+    NNV_DIRECT = 0,      /* direct convolution from raw OIHW weights, no transformation       */
+    NNV_IM2COL_GEMM = 1, /* implicit im2col GEMM from matrix-instruction-ordered weight panels */
+    NNV_WINO_F2 = 2,     /* Winograd F(2x2,3x3): 4x4 tiles                                     */
+    NNV_WINO_F4 = 3,     /* Winograd F(4x4,3x3): 6x6 tiles                                     */
+    NNV_DEPTHWISE = 4,   /* 3x3 depthwise (groups = C = K) from channel-blocked tap-major weights */
+    NNV_KIND_COUNT = 5
+} nnv_kind;
+
+typedef enum { NNV_F32 = 0, NNV_F16 = 1 } nnv_dtype;
+
+typedef enum {
+    NNV_OK = 0,
+    NNV_E_NULL = -1,        /* a required pointer is NULL                                  */
+    NNV_E_BAD_DESC = -2,    /* non-positive size, empty output, groups not dividing C or K */
+    NNV_E_UNSUPPORTED = -3, /* this kind cannot run this layer (see nnv_kind_supported)     */
+    NNV_E_WORKSPACE = -4,   /* workspace smaller than nnv_workspace_bytes                   */
+    NNV_E_ALIGN = -5,       /* a device pointer is not 16-byte aligned                      */
+    NNV_E_HIP = -6,         /* a HIP call failed; text via nnv_last_hip_error               */
+    NNV_E_ARG = -7          /* bad count / reps / enum value                                */
+} nnv_status;
+
+typedef struct {
+    int32_t n, c, h, w;          /* input  N x C x H x W               */
+    int32_t k;                   /* output channels                    */
+    int32_t r, s;                /* filter height, width               */
+    int32_t stride_h, stride_w;
+    int32_t pad_h, pad_w;
+    int32_t groups;              /* 1, or any divisor of C and K       */
+    int32_t dtype;               /* nnv_dtype of x, y, transformed w   */
+} nnv_conv_desc;
+
+/* Result of nnv_time_layer: GPU time of the two operations of one (layer, kind)
+ * and the algorithmic traffic/work they stand for. */
+typedef struct {
+    double transform_ms;       /* median GPU time of the weight transformation           */
+    double forward_ms;         /* median GPU time of the convolution                      */
+    double transform_bytes;    /* raw weights read + transformed weights written          */
+    double forward_bytes;      /* x + transformed weights + y (workspace traffic excluded) */
+    double forward_flops;      /* flops executed (Winograd: 2*alpha^2*K*C*tiles)           */
+    double direct_equiv_flops; /* 2 * multiply-accumulates of the plain convolution        */
+} nnv_timing;
+
+/* Version of the transformed-weight layouts and of the Winograd matrix sets.
+ * Version 1: 16-row fragments (float32: 16x4, float16: 16x32); Winograd points
+ * {0,1,-1} (F2), {0,+-1,+-2} (F4 float32), {0,1,-1,2,-1/2} with G rows scaled by
+ * (4,4,4,16,4,1) (F4 float16). */
+int nnv_layout_version(void);
+
+/* Static text for a status code (never NULL). */
+const char *nnv_status_string(int status);
+
+/* Text of the last HIP error seen by the calling thread ("" if none). */
+const char *nnv_last_hip_error(void);
+
+/* 1 if `kind` can run the layer, 0 if not, NNV_E_* if the descriptor is invalid.
+ *   WINO_F2/F4   : R = S = 3, stride 1, groups 1
+ *   DEPTHWISE    : groups = C = K, R = S = 3, stride_h = stride_w in {1,2}
+ *   IM2COL_GEMM  : groups 1, R,S <= 32, R*S <= 128
+ *   DIRECT       : any groups dividing C and K
+ * (the paper's engine keys the usable kernels on filter size, stride and channel
+ * divisibility in the same way, Fig. 5). */
+int nnv_kind_supported(const nnv_conv_desc *desc, nnv_kind kind);
+
+/* Bytes of the transformed-weight buffer of `kind` (0 if unsupported/invalid).
+ * This is the size a post-transformed-weights cache would store and read back
+ * (Section 3.1.2): alpha^2/9 of the raw size for Winograd up to padding. */
+size_t nnv_transformed_bytes(const nnv_conv_desc *desc, nnv_kind kind);
+
+/* Bytes of scratch nnv_conv_forward needs for `kind` (may be 0). */
+size_t nnv_workspace_bytes(const nnv_conv_desc *desc, nnv_kind kind);
+
+/* Weight transformation w_i (Section 2 "weights transformation", Fig. 3, Table 2
+ * column "Weights Trans."): raw OIHW float32 -> the layout `kind` executes from.
+ *   w_raw : device, K*(C/groups)*R*S float32, read only
+ *   w_tx  : device, nnv_transformed_bytes(desc, kind) bytes, fully overwritten
+ *           (padding included).  For NNV_DIRECT the layout is the raw one: if
+ *           w_tx == w_raw nothing is done, else the weights are copied.
+ * Errors: NULL, BAD_DESC, UNSUPPORTED, ALIGN, HIP. */
+int nnv_transform_weights(const nnv_conv_desc *desc, nnv_kind kind, const float *w_raw,
+                          void *w_tx, void *hip_stream);
+
+/* The same for n_layers layers in as few launches as possible (a whole model's
+ * weights at cold start, Table 1 "weights transformation").  descs, kinds,
+ * w_raw and w_tx are HOST arrays of length n_layers holding descriptors, kinds
+ * and device pointers.  Layers are independent; outputs must not overlap. */
+int nnv_transform_weights_grouped(int n_layers, const nnv_conv_desc *descs, const nnv_kind *kinds,
+                                  const float *const *w_raw, void *const *w_tx, void *hip_stream);
+
+/* Kernel execution e_i (Table 2 column "Execution") from transformed weights.
+ *   x    : device, N*C*H*W elements of desc.dtype, read only
+ *   w_tx : device, output of nnv_transform_weights for the same desc and kind
+ *   bias : device, K float32, or NULL
+ *   y    : device, N*K*P*Q elements of desc.dtype, fully overwritten
+ *   workspace : device, >= nnv_workspace_bytes(desc, kind) bytes (may be NULL if 0)
+ * Errors: NULL, BAD_DESC, UNSUPPORTED, WORKSPACE, ALIGN, HIP. */
+int nnv_conv_forward(const nnv_conv_desc *desc, nnv_kind kind, const void *x, const void *w_tx,
+                     const float *bias, void *y, void *workspace, size_t workspace_bytes,
+                     void *hip_stream);
+
+/* Per-operation profiling (the latency table Algorithm 1 consumes; Section 3.3
+ * re-profiles operations while planning).  Runs `warmup` untimed and `reps`
+ * timed repetitions of the transformation and, separately, of the forward pass,
+ * each bracketed by HIP events on `hip_stream`, and reports the medians.  If
+ * flush is non-NULL, flush_bytes of it are overwritten before every timed
+ * repetition so that weights and activations are not cache-resident ("cold").
+ * Synchronises the stream.  `out` is a HOST pointer. */
+int nnv_time_layer(const nnv_conv_desc *desc, nnv_kind kind, const float *w_raw, void *w_tx,
+                   const void *x, void *y, void *workspace, size_t workspace_bytes,
+                   void *flush, size_t flush_bytes, int warmup, int reps, void *hip_stream,
+                   nnv_timing *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NNV_H */

@@ -17,7 +17,15 @@ The matrices come from oracle.cooktoom with the point sets and row scalings
 declared in VARIANTS.  The result equals the direct convolution exactly in
 real arithmetic.
 
-Pins (tests/test_oracle_winograd.py): conv2d_winograd == oracle.direct to
+conv2d_winograd_stored() is the same five steps with U, V and y rounded to a
+storage type where the half-precision kernels round them (U after step 1, V
+after step 2, y after step 5; everything between in float32 or wider).  It
+states what the float16 Winograd variant computes, rounding included.
+
+Pins (tests/test_oracle_winograd.py): conv2d_winograd_stored with float64
+storage equals conv2d_winograd; with float16 storage it stays within the
+half-precision bound of the direct convolution on the workload shapes.
+conv2d_winograd == oracle.direct to
 1e-12 relative on random layers including ragged tile edges; U for the
 centre-delta and the all-ones filter against the closed forms
 G[:,1] G[:,1]^T and (G 1)(G 1)^T typed from the printed matrices.
@@ -103,3 +111,23 @@ def conv2d_winograd(x, w, variant: str, pad: int = 1, bias=None):
     if bias is not None:
         y = y + np.asarray(bias, dtype=np.float64).reshape(1, K, 1, 1)
     return np.ascontiguousarray(y)
+
+
+def conv2d_winograd_stored(x, w, variant: str, pad: int = 1, bias=None, store=np.float16):
+    """Steps 1-5 with U, V and y rounded (to nearest even) to `store`; U and V are
+    formed in float32 before that rounding, the contraction accumulates in float32."""
+    m = tile_m(variant)
+    AT, _, _ = matrices(variant)
+    xs = np.asarray(x).astype(store).astype(np.float64)
+    N, C, H, W = xs.shape
+    K = w.shape[0]
+    P, Q = H + 2 * pad - 2, W + 2 * pad - 2
+    U = transform_weights(np.asarray(w, dtype=np.float64), variant).astype(np.float32).astype(store).astype(np.float64)
+    V = transform_input(xs, variant, pad).astype(np.float32).astype(store).astype(np.float64)
+    th, tw = V.shape[4], V.shape[5]
+    Mf = np.einsum("uvkc,uvncij->uvnkij", U, V).astype(np.float32).astype(np.float64)
+    Y = np.einsum("pu,uvnkij,qv->nkipjq", AT, Mf, AT).reshape(N, K, th * m, tw * m)
+    y = Y[:, :, :P, :Q]
+    if bias is not None:
+        y = y + np.asarray(bias, dtype=np.float64).reshape(1, K, 1, 1)
+    return np.ascontiguousarray(y.astype(np.float32).astype(store).astype(np.float64))

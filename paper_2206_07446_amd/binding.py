@@ -1,0 +1,162 @@
+"""ctypes binding of libnnv.so: the same entry points as include/nnv.h, argument
+marshalling only.  torch supplies device memory and the stream handle."""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import c_char_p, c_double, c_int, c_int32, c_size_t, c_void_p, POINTER, Structure, byref
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libnnv.so")
+
+DIRECT, IM2COL_GEMM, WINO_F2, WINO_F4, DEPTHWISE = range(5)
+KINDS = {"direct": DIRECT, "im2col_gemm": IM2COL_GEMM, "wino_f2": WINO_F2, "wino_f4": WINO_F4,
+         "depthwise": DEPTHWISE}
+F32, F16 = 0, 1
+
+EXPORTS = ("nnv_layout_version", "nnv_status_string", "nnv_last_hip_error", "nnv_kind_supported",
+           "nnv_transformed_bytes", "nnv_workspace_bytes", "nnv_transform_weights",
+           "nnv_transform_weights_grouped", "nnv_conv_forward", "nnv_time_layer")
+
+
+class NnvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        text = nnv_status_string(status)
+        if status == -6:
+            text += ": " + nnv_last_hip_error()
+        super().__init__(f"{where}: {text} ({status})")
+
+
+class ConvDesc(Structure):
+    _fields_ = [(n, c_int32) for n in ("n", "c", "h", "w", "k", "r", "s", "stride_h", "stride_w",
+                                       "pad_h", "pad_w", "groups", "dtype")]
+
+
+class Timing(Structure):
+    _fields_ = [(n, c_double) for n in ("transform_ms", "forward_ms", "transform_bytes", "forward_bytes",
+                                        "forward_flops", "direct_equiv_flops")]
+
+
+_lib = None
+
+
+def load():
+    """Load libnnv.so (building it first only if it does not exist).  torch is imported
+    before the library so that both share one HIP runtime."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    import torch  # noqa: F401  (loads the HIP runtime the library binds to)
+    if not os.path.exists(LIB_PATH):
+        from .build import build
+        build()
+    lib = ctypes.CDLL(LIB_PATH)
+    lib.nnv_layout_version.restype = c_int
+    lib.nnv_status_string.restype = c_char_p
+    lib.nnv_status_string.argtypes = [c_int]
+    lib.nnv_last_hip_error.restype = c_char_p
+    lib.nnv_kind_supported.restype = c_int
+    lib.nnv_kind_supported.argtypes = [POINTER(ConvDesc), c_int]
+    lib.nnv_transformed_bytes.restype = c_size_t
+    lib.nnv_transformed_bytes.argtypes = [POINTER(ConvDesc), c_int]
+    lib.nnv_workspace_bytes.restype = c_size_t
+    lib.nnv_workspace_bytes.argtypes = [POINTER(ConvDesc), c_int]
+    lib.nnv_transform_weights.restype = c_int
+    lib.nnv_transform_weights.argtypes = [POINTER(ConvDesc), c_int, c_void_p, c_void_p, c_void_p]
+    lib.nnv_transform_weights_grouped.restype = c_int
+    lib.nnv_transform_weights_grouped.argtypes = [c_int, POINTER(ConvDesc), POINTER(c_int), POINTER(c_void_p),
+                                                  POINTER(c_void_p), c_void_p]
+    lib.nnv_conv_forward.restype = c_int
+    lib.nnv_conv_forward.argtypes = [POINTER(ConvDesc), c_int, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                     c_size_t, c_void_p]
+    lib.nnv_time_layer.restype = c_int
+    lib.nnv_time_layer.argtypes = [POINTER(ConvDesc), c_int, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                   c_size_t, c_void_p, c_size_t, c_int, c_int, c_void_p, POINTER(Timing)]
+    _lib = lib
+    return lib
+
+
+def make_desc(layer, dtype: int = F32) -> ConvDesc:
+    """ConvDesc from any object with c,h,w,k,r,s,stride,pad,groups,n attributes."""
+    return ConvDesc(layer.n, layer.c, layer.h, layer.w, layer.k, layer.r, layer.s, layer.stride, layer.stride,
+                    layer.pad, layer.pad, layer.groups, dtype)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return c_void_p(t)
+    return c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    elif hasattr(stream, "cuda_stream"):
+        stream = stream.cuda_stream
+    return c_void_p(stream)
+
+
+def _check(rc: int, where: str):
+    if rc < 0:
+        raise NnvError(rc, where)
+    return rc
+
+
+def nnv_layout_version() -> int:
+    return load().nnv_layout_version()
+
+
+def nnv_status_string(status: int) -> str:
+    return load().nnv_status_string(status).decode()
+
+
+def nnv_last_hip_error() -> str:
+    return load().nnv_last_hip_error().decode()
+
+
+def nnv_kind_supported(desc: ConvDesc, kind: int) -> bool:
+    return bool(_check(load().nnv_kind_supported(byref(desc), kind), "nnv_kind_supported"))
+
+
+def nnv_transformed_bytes(desc: ConvDesc, kind: int) -> int:
+    return int(load().nnv_transformed_bytes(byref(desc), kind))
+
+
+def nnv_workspace_bytes(desc: ConvDesc, kind: int) -> int:
+    return int(load().nnv_workspace_bytes(byref(desc), kind))
+
+
+def nnv_transform_weights(desc: ConvDesc, kind: int, w_raw, w_tx, stream=None) -> None:
+    _check(load().nnv_transform_weights(byref(desc), kind, _ptr(w_raw), _ptr(w_tx), _stream(stream)),
+           "nnv_transform_weights")
+
+
+def nnv_transform_weights_grouped(descs, kinds, w_raw, w_tx, stream=None) -> None:
+    n = len(descs)
+    d = (ConvDesc * n)(*descs)
+    k = (c_int * n)(*kinds)
+    src = (c_void_p * n)(*[t if isinstance(t, int) else t.data_ptr() for t in w_raw])
+    dst = (c_void_p * n)(*[t if isinstance(t, int) else t.data_ptr() for t in w_tx])
+    _check(load().nnv_transform_weights_grouped(n, d, k, src, dst, _stream(stream)), "nnv_transform_weights_grouped")
+
+
+def nnv_conv_forward(desc: ConvDesc, kind: int, x, w_tx, bias, y, workspace, workspace_bytes=None, stream=None) -> None:
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().nnv_conv_forward(byref(desc), kind, _ptr(x), _ptr(w_tx), _ptr(bias), _ptr(y), _ptr(workspace),
+                                   workspace_bytes, _stream(stream)), "nnv_conv_forward")
+
+
+def nnv_time_layer(desc: ConvDesc, kind: int, w_raw, w_tx, x, y, workspace, flush=None, warmup=2, reps=10,
+                   stream=None) -> Timing:
+    out = Timing()
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    fl_bytes = 0 if flush is None else flush.numel() * flush.element_size()
+    _check(load().nnv_time_layer(byref(desc), kind, _ptr(w_raw), _ptr(w_tx), _ptr(x), _ptr(y), _ptr(workspace),
+                                 ws_bytes, _ptr(flush), fl_bytes, warmup, reps, _stream(stream), byref(out)),
+           "nnv_time_layer")
+    return out

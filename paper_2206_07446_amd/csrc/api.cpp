@@ -1,0 +1,288 @@
+// Host side of the C ABI declared in nnv.h: descriptor validation, size queries,
+// dispatch by kernel kind and the per-operation timing.
+#include <algorithm>
+#include <cstring>
+#include <string>
+#include <vector>
+#include "nnv_internal.h"
+
+using namespace nnv;
+
+namespace {
+
+thread_local std::string g_hip_error;
+
+int hip_fail(hipError_t e) {
+    g_hip_error = hipGetErrorString(e);
+    return NNV_E_HIP;
+}
+
+int make_geo(const nnv_conv_desc *d, Geo *g) {
+    if (!d) return NNV_E_NULL;
+    if (d->n <= 0 || d->c <= 0 || d->h <= 0 || d->w <= 0 || d->k <= 0 || d->r <= 0 || d->s <= 0) return NNV_E_BAD_DESC;
+    if (d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0 || d->groups <= 0) return NNV_E_BAD_DESC;
+    if (d->c % d->groups || d->k % d->groups) return NNV_E_BAD_DESC;
+    if (d->dtype != NNV_F32 && d->dtype != NNV_F16) return NNV_E_BAD_DESC;
+    if (d->h + 2 * d->pad_h < d->r || d->w + 2 * d->pad_w < d->s) return NNV_E_BAD_DESC;
+    if (d->n > 65535 || d->c > 65535 || d->k > 65535) return NNV_E_BAD_DESC;
+    g->n = d->n; g->c = d->c; g->h = d->h; g->w = d->w; g->k = d->k; g->r = d->r; g->s = d->s;
+    g->sh = d->stride_h; g->sw = d->stride_w; g->ph = d->pad_h; g->pw = d->pad_w;
+    g->groups = d->groups; g->dtype = d->dtype;
+    g->p = (d->h + 2 * d->pad_h - d->r) / d->stride_h + 1;
+    g->q = (d->w + 2 * d->pad_w - d->s) / d->stride_w + 1;
+    g->cg = d->c / d->groups;
+    g->kg = d->k / d->groups;
+    const int64_t lim = (int64_t)1 << 30;   // element counts are indexed with 32-bit ints
+    if ((int64_t)g->n * g->c * g->h * g->w >= lim || (int64_t)g->n * g->k * g->p * g->q >= lim) return NNV_E_BAD_DESC;
+    if ((int64_t)g->n * g->h * g->w * (ceil_div(g->c, 32) * 32) >= lim) return NNV_E_BAD_DESC;
+    if ((int64_t)g->k * g->cg * g->r * g->s >= lim) return NNV_E_BAD_DESC;
+    return NNV_OK;
+}
+
+bool supported(const Geo &g, int kind) {
+    switch (kind) {
+        case NNV_DIRECT: return true;
+        case NNV_IM2COL_GEMM: return g.groups == 1 && g.r <= 32 && g.s <= 32 && g.r * g.s <= 64;
+        case NNV_WINO_F2:
+        case NNV_WINO_F4: return g.groups == 1 && g.r == 3 && g.s == 3 && g.sh == 1 && g.sw == 1;
+        case NNV_DEPTHWISE:
+            return g.groups == g.c && g.c == g.k && g.r == 3 && g.s == 3 && g.sh == g.sw && (g.sh == 1 || g.sh == 2);
+        default: return false;
+    }
+}
+
+size_t tx_bytes(const Geo &g, int kind) {
+    const bool half = g.dtype == NNV_F16;
+    const size_t frag = half ? (size_t)ceil_div(g.cg, 32) * 512 * 2 : (size_t)ceil_div(g.cg, 4) * 64 * 4;
+    const size_t k16 = ceil_div(g.k, 16);
+    switch (kind) {
+        case NNV_DIRECT: return (size_t)g.k * g.cg * g.r * g.s * sizeof(float);
+        case NNV_IM2COL_GEMM: return k16 * frag * g.r * g.s;
+        case NNV_WINO_F2: return 16 * k16 * frag;
+        case NNV_WINO_F4: return 36 * k16 * frag;
+        case NNV_DEPTHWISE: return (size_t)ceil_div(g.c, 32) * 288 * (half ? 2 : 4);
+        default: return 0;
+    }
+}
+
+size_t ws_bytes(const Geo &g, int kind) {
+    switch (kind) {
+        case NNV_IM2COL_GEMM: return im2col_workspace_bytes(g);
+        case NNV_WINO_F2:
+        case NNV_WINO_F4: return wino_workspace_bytes(g, kind);
+        default: return 0;
+    }
+}
+
+inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; }
+
+int transform_many(int n, const nnv_conv_desc *descs, const nnv_kind *kinds, const float *const *w_raw,
+                   void *const *w_tx, hipStream_t st) {
+    if (n < 0) return NNV_E_ARG;
+    if (n == 0) return NNV_OK;
+    if (!descs || !kinds || !w_raw || !w_tx) return NNV_E_NULL;
+    std::vector<Geo> geos(n);
+    for (int i = 0; i < n; ++i) {
+        int rc = make_geo(&descs[i], &geos[i]);
+        if (rc) return rc;
+        if (kinds[i] < 0 || kinds[i] >= NNV_KIND_COUNT) return NNV_E_ARG;
+        if (!supported(geos[i], kinds[i])) return NNV_E_UNSUPPORTED;
+        if (!w_raw[i] || !w_tx[i]) return NNV_E_NULL;
+        if (misaligned(w_raw[i]) || misaligned(w_tx[i])) return NNV_E_ALIGN;
+    }
+    JobTable tbl;
+    tbl.njobs = 0;
+    int blocks = 0;
+    size_t lds = 0;
+    auto flush = [&]() -> hipError_t {
+        if (tbl.njobs == 0) return hipSuccess;
+        hipError_t e = launch_transform_jobs(tbl, blocks, lds, st);
+        tbl.njobs = 0; blocks = 0; lds = 0;
+        return e;
+    };
+    for (int i = 0; i < n; ++i) {
+        if (kinds[i] == NNV_DIRECT) {
+            if (static_cast<const void *>(w_raw[i]) != w_tx[i]) {
+                hipError_t e = launch_copy_f32(w_raw[i], static_cast<float *>(w_tx[i]),
+                                               (size_t)geos[i].k * geos[i].cg * geos[i].r * geos[i].s, st);
+                if (e != hipSuccess) return hip_fail(e);
+            }
+            continue;
+        }
+        TransformJob &job = tbl.job[tbl.njobs];
+        if (fill_transform_job(geos[i], kinds[i], w_raw[i], w_tx[i], &job)) return NNV_E_UNSUPPORTED;
+        job.block0 = blocks;
+        blocks += job.nblocks;
+        lds = std::max(lds, transform_job_lds_bytes(job));
+        if (++tbl.njobs == kMaxJobs) {
+            hipError_t e = flush();
+            if (e != hipSuccess) return hip_fail(e);
+        }
+    }
+    hipError_t e = flush();
+    if (e != hipSuccess) return hip_fail(e);
+    return NNV_OK;
+}
+
+int forward_checked(const Geo &g, int kind, const void *x, const void *w_tx, const float *bias, void *y, void *ws,
+                    hipStream_t st) {
+    hipError_t e = hipSuccess;
+    switch (kind) {
+        case NNV_DIRECT: e = launch_direct(g, x, static_cast<const float *>(w_tx), bias, y, st); break;
+        case NNV_IM2COL_GEMM: e = launch_im2col(g, x, w_tx, bias, y, ws, st); break;
+        case NNV_WINO_F2:
+        case NNV_WINO_F4: e = launch_wino(g, kind, x, w_tx, bias, y, ws, st); break;
+        case NNV_DEPTHWISE: e = launch_depthwise(g, x, w_tx, bias, y, st); break;
+        default: return NNV_E_ARG;
+    }
+    if (e != hipSuccess) return hip_fail(e);
+    return NNV_OK;
+}
+
+int forward_args(const nnv_conv_desc *desc, nnv_kind kind, const void *x, const void *w_tx, const float *bias,
+                 void *y, void *ws, size_t ws_size, Geo *g) {
+    int rc = make_geo(desc, g);
+    if (rc) return rc;
+    if (kind < 0 || kind >= NNV_KIND_COUNT) return NNV_E_ARG;
+    if (!supported(*g, kind)) return NNV_E_UNSUPPORTED;
+    if (!x || !w_tx || !y) return NNV_E_NULL;
+    const size_t need = ws_bytes(*g, kind);
+    if (need > 0 && !ws) return NNV_E_NULL;
+    if (ws_size < need) return NNV_E_WORKSPACE;
+    if (misaligned(x) || misaligned(w_tx) || misaligned(y) || (need && misaligned(ws)) || (bias && (reinterpret_cast<uintptr_t>(bias) & 3)))
+        return NNV_E_ALIGN;
+    return NNV_OK;
+}
+
+double median(std::vector<float> v) {
+    std::sort(v.begin(), v.end());
+    const size_t n = v.size();
+    return n % 2 ? v[n / 2] : 0.5 * (v[n / 2 - 1] + v[n / 2]);
+}
+
+}  // namespace
+
+extern "C" {
+
+int nnv_layout_version(void) { return 1; }
+
+const char *nnv_status_string(int status) {
+    switch (status) {
+        case NNV_OK: return "ok";
+        case NNV_E_NULL: return "a required pointer is NULL";
+        case NNV_E_BAD_DESC: return "invalid convolution descriptor";
+        case NNV_E_UNSUPPORTED: return "kernel kind does not support this layer";
+        case NNV_E_WORKSPACE: return "workspace too small";
+        case NNV_E_ALIGN: return "device pointer not 16-byte aligned";
+        case NNV_E_HIP: return "HIP runtime error";
+        case NNV_E_ARG: return "invalid argument";
+        default: return "unknown status";
+    }
+}
+
+const char *nnv_last_hip_error(void) { return g_hip_error.c_str(); }
+
+int nnv_kind_supported(const nnv_conv_desc *desc, nnv_kind kind) {
+    Geo g;
+    int rc = make_geo(desc, &g);
+    if (rc) return rc;
+    if (kind < 0 || kind >= NNV_KIND_COUNT) return NNV_E_ARG;
+    return supported(g, kind) ? 1 : 0;
+}
+
+size_t nnv_transformed_bytes(const nnv_conv_desc *desc, nnv_kind kind) {
+    Geo g;
+    if (make_geo(desc, &g) || kind < 0 || kind >= NNV_KIND_COUNT || !supported(g, kind)) return 0;
+    return tx_bytes(g, kind);
+}
+
+size_t nnv_workspace_bytes(const nnv_conv_desc *desc, nnv_kind kind) {
+    Geo g;
+    if (make_geo(desc, &g) || kind < 0 || kind >= NNV_KIND_COUNT || !supported(g, kind)) return 0;
+    return ws_bytes(g, kind);
+}
+
+int nnv_transform_weights(const nnv_conv_desc *desc, nnv_kind kind, const float *w_raw, void *w_tx, void *hip_stream) {
+    if (!desc) return NNV_E_NULL;
+    const float *src[1] = {w_raw};
+    void *dst[1] = {w_tx};
+    return transform_many(1, desc, &kind, src, dst, static_cast<hipStream_t>(hip_stream));
+}
+
+int nnv_transform_weights_grouped(int n_layers, const nnv_conv_desc *descs, const nnv_kind *kinds,
+                                  const float *const *w_raw, void *const *w_tx, void *hip_stream) {
+    return transform_many(n_layers, descs, kinds, w_raw, w_tx, static_cast<hipStream_t>(hip_stream));
+}
+
+int nnv_conv_forward(const nnv_conv_desc *desc, nnv_kind kind, const void *x, const void *w_tx, const float *bias,
+                     void *y, void *workspace, size_t workspace_bytes, void *hip_stream) {
+    Geo g;
+    int rc = forward_args(desc, kind, x, w_tx, bias, y, workspace, workspace_bytes, &g);
+    if (rc) return rc;
+    return forward_checked(g, kind, x, w_tx, bias, y, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+int nnv_time_layer(const nnv_conv_desc *desc, nnv_kind kind, const float *w_raw, void *w_tx, const void *x, void *y,
+                   void *workspace, size_t workspace_bytes, void *flush, size_t flush_bytes, int warmup, int reps,
+                   void *hip_stream, nnv_timing *out) {
+    if (!out || !w_raw) return NNV_E_NULL;
+    if (reps <= 0 || warmup < 0) return NNV_E_ARG;
+    Geo g;
+    int rc = forward_args(desc, kind, x, w_tx, nullptr, y, workspace, workspace_bytes, &g);
+    if (rc) return rc;
+    if (misaligned(w_raw) || (flush && misaligned(flush))) return NNV_E_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    hipEvent_t e0, e1;
+    hipError_t e = hipEventCreate(&e0);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipEventCreate(&e1);
+    if (e != hipSuccess) { (void)hipEventDestroy(e0); return hip_fail(e); }
+    std::vector<float> t_tx, t_fw;
+    const bool tx_is_noop = kind == NNV_DIRECT && static_cast<const void *>(w_raw) == w_tx;
+    rc = NNV_OK;
+    for (int it = 0; it < warmup + reps && rc == NNV_OK; ++it) {
+        for (int phase = 0; phase < 2 && rc == NNV_OK; ++phase) {
+            if (flush && flush_bytes >= 16) {
+                e = launch_fill_u32(static_cast<uint32_t *>(flush), flush_bytes / 4, (uint32_t)it, st);
+                if (e != hipSuccess) { rc = hip_fail(e); break; }
+            }
+            float ms = 0.f;
+            if (phase == 0 && tx_is_noop) {
+                // nothing to run: the raw layout is the execution layout
+            } else {
+                if ((e = hipEventRecord(e0, st)) != hipSuccess) { rc = hip_fail(e); break; }
+                if (phase == 0) rc = nnv_transform_weights(desc, kind, w_raw, w_tx, hip_stream);
+                else rc = forward_checked(g, kind, x, w_tx, nullptr, y, workspace, st);
+                if (rc) break;
+                if ((e = hipEventRecord(e1, st)) != hipSuccess) { rc = hip_fail(e); break; }
+                if ((e = hipEventSynchronize(e1)) != hipSuccess) { rc = hip_fail(e); break; }
+                if ((e = hipEventElapsedTime(&ms, e0, e1)) != hipSuccess) { rc = hip_fail(e); break; }
+            }
+            if (it >= warmup) (phase == 0 ? t_tx : t_fw).push_back(ms);
+        }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc) return rc;
+    e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return hip_fail(e);
+    const double esz = g.dtype == NNV_F16 ? 2.0 : 4.0;
+    const double raw_b = (double)g.k * g.cg * g.r * g.s * 4.0;
+    const double tx_b = (double)tx_bytes(g, kind);
+    out->transform_ms = median(t_tx);
+    out->forward_ms = median(t_fw);
+    out->transform_bytes = tx_is_noop ? 0.0 : raw_b + tx_b;
+    out->forward_bytes = esz * ((double)g.n * g.c * g.h * g.w + (double)g.n * g.k * g.p * g.q) + tx_b;
+    const double macs = (double)g.n * g.k * g.p * g.q * g.cg * g.r * g.s;
+    out->direct_equiv_flops = 2.0 * macs;
+    if (kind == NNV_WINO_F2 || kind == NNV_WINO_F4) {
+        const int m = kind == NNV_WINO_F2 ? 2 : 4;
+        const double tiles = (double)g.n * ceil_div(g.p, m) * ceil_div(g.q, m);
+        out->forward_flops = 2.0 * (m + 2) * (m + 2) * g.k * g.c * tiles;
+    } else {
+        out->forward_flops = 2.0 * macs;
+    }
+    return NNV_OK;
+}
+
+}  // extern "C"

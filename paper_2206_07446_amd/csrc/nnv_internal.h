@@ -1,0 +1,63 @@
+// Internal declarations shared by the host dispatch and the HIP kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "nnv.h"
+
+namespace nnv {
+
+// Validated geometry of one conv layer (host side).
+struct Geo {
+    int n, c, h, w, k, r, s, sh, sw, ph, pw, groups, dtype;
+    int p, q;      // output height / width
+    int cg, kg;    // channels per group (input / output)
+};
+
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Winograd matrix sets (see wino_consts.h)
+enum WinoSet { WS_F2 = 0, WS_F4 = 1, WS_F4H = 2 };
+static inline int wino_set(int kind, int dtype) {
+    if (kind == NNV_WINO_F2) return WS_F2;
+    return dtype == NNV_F16 ? WS_F4H : WS_F4;
+}
+
+// One weight-transformation job of a grouped launch.
+enum JobType { JOB_WINO = 0, JOB_GEMM = 1, JOB_DW = 2 };
+struct TransformJob {
+    const float *src;
+    void *dst;
+    int type;        // JobType
+    int wset;        // WinoSet (JOB_WINO)
+    int half;        // output float16
+    int K, C, RS;    // rows, channels per row, taps
+    int cchunk;      // channels handled by one block
+    int nchunks;     // blocks per 16-row group
+    int block0;      // first block of this job in the launch
+    int nblocks;
+};
+constexpr int kMaxJobs = 40;
+struct JobTable {
+    TransformJob job[kMaxJobs];
+    int njobs;
+};
+
+int fill_transform_job(const Geo &g, int kind, const float *src, void *dst, TransformJob *job);
+size_t transform_job_lds_bytes(const TransformJob &job);
+hipError_t launch_transform_jobs(const JobTable &tbl, int total_blocks, size_t lds, hipStream_t st);
+hipError_t launch_copy_f32(const float *src, float *dst, size_t n, hipStream_t st);
+hipError_t launch_fill_u32(uint32_t *dst, size_t n, uint32_t v, hipStream_t st);
+
+hipError_t launch_direct(const Geo &g, const void *x, const float *w, const float *bias, void *y, hipStream_t st);
+hipError_t launch_depthwise(const Geo &g, const void *x, const void *w, const float *bias, void *y, hipStream_t st);
+
+size_t im2col_workspace_bytes(const Geo &g);
+hipError_t launch_im2col(const Geo &g, const void *x, const void *w, const float *bias, void *y, void *ws, hipStream_t st);
+
+size_t wino_workspace_bytes(const Geo &g, int kind);
+hipError_t launch_wino(const Geo &g, int kind, const void *x, const void *w, const float *bias, void *y, void *ws, hipStream_t st);
+
+}  // namespace nnv

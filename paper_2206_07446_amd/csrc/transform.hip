@@ -1,0 +1,317 @@
+// Weight-transformation kernels: raw OIHW float32 -> the layout a kernel executes from
+// (the operation w_i of Section 3.2; Section 2 "weights transformation", Fig. 3).
+//
+// All of them are bandwidth-bound permutations (plus the tiny G g G^T product for
+// Winograd), so the design goal is full-width coalesced reads and writes:
+//   * a block owns 16 output channels (one fragment row group) and a chunk of input
+//     channels; it stages the 16 contiguous row segments of the raw tensor in LDS with
+//     coalesced (float4 when aligned) loads,
+//   * threads then read their filter taps from LDS with the k-index fastest, so every
+//     wavefront store is one contiguous 256 B .. 1 KB piece of the output fragment.
+// One launch can carry many layers (a job table passed by value as kernel argument),
+// because single layers of a batch-1 CNN are far too small to fill 256 CUs.
+#include "nnv_internal.h"
+#include "wino_consts.h"
+
+namespace nnv {
+
+static constexpr int kRows = 16;   // output channels per block / fragment
+
+__host__ __device__ static inline int lds_row_stride(int rowlen) {
+    // multiple of 64 plus 4: 16 rows x odd tap strides map to distinct LDS banks
+    return ((rowlen + 63) / 64) * 64 + 4;
+}
+
+// Stage rows k0..k0+15, columns [col0, col0+len_valid) of a (K x rowstride) float matrix
+// into lds[row * ROW + col], zero-filling up to len_fill and for rows >= K.
+__device__ static inline void stage_rows(const float *__restrict__ src, float *lds, int ROW, int k0, int K,
+                                         size_t rowstride, size_t col0, int len_valid, int len_fill) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const bool vec = ((rowstride & 3) == 0) && ((col0 & 3) == 0) && ((len_valid & 3) == 0);
+    const int fill4 = (len_fill + 3) >> 2;
+    for (int rr = 0; rr < kRows / 4; ++rr) {
+        const int row = wave * (kRows / 4) + rr;
+        const int k = k0 + row;
+        const float *rp = src + (size_t)k * rowstride + col0;
+        float *lp = lds + row * ROW;
+        if (vec) {
+            const int valid4 = (k < K) ? (len_valid >> 2) : 0;
+            for (int i = lane; i < fill4; i += 64) {
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (i < valid4) v = reinterpret_cast<const float4 *>(rp)[i];
+                reinterpret_cast<float4 *>(lp)[i] = v;
+            }
+        } else {
+            const int valid = (k < K) ? len_valid : 0;
+            for (int i = lane; i < fill4 * 4; i += 64) {
+                float v = 0.f;
+                if (i < valid) v = rp[i];
+                lp[i] = v;
+            }
+        }
+    }
+    __syncthreads();
+}
+
+// U = G g G^T for one 3x3 filter held in registers.
+template <int SET>
+__device__ static inline void wino_u(const float g[9], float u[WinoMat<SET>::A * WinoMat<SET>::A]) {
+    using W = WinoMat<SET>;
+    constexpr int A = W::A;
+    float t[A][3];
+#pragma unroll
+    for (int a = 0; a < A; ++a)
+#pragma unroll
+        for (int s = 0; s < 3; ++s) {
+            float acc = 0.f;
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+                if (W::G[a][r] != 0.f) acc += W::G[a][r] * g[r * 3 + s];
+            t[a][s] = acc;
+        }
+#pragma unroll
+    for (int a = 0; a < A; ++a)
+#pragma unroll
+        for (int b = 0; b < A; ++b) {
+            float acc = 0.f;
+#pragma unroll
+            for (int s = 0; s < 3; ++s)
+                if (W::G[b][s] != 0.f) acc += t[a][s] * W::G[b][s];
+            u[a * A + b] = acc;
+        }
+}
+
+__device__ static inline uint32_t pack_half2(float a, float b) {
+    __half2 h = __floats2half2_rn(a, b);
+    return *reinterpret_cast<uint32_t *>(&h);
+}
+
+// Winograd weight transformation of one block: 16 output channels x up to 64 channels.
+template <int SET, bool HALF>
+__device__ static inline void wino_block(const TransformJob &job, int local_block, float *lds) {
+    using W = WinoMat<SET>;
+    constexpr int AA = W::A * W::A;
+    const int kb = local_block / job.nchunks, chunk = local_block % job.nchunks;
+    const int K16 = (job.K + 15) / 16;
+    const int cpad = HALF ? ((job.C + 31) / 32) * 32 : ((job.C + 3) / 4) * 4;
+    const int c0 = chunk * 64;
+    const int cfill = min(64, cpad - c0);
+    const int cvalid = max(0, min(64, job.C - c0));
+    const int ROW = lds_row_stride(64 * 9);
+    stage_rows(job.src, lds, ROW, kb * 16, job.K, (size_t)job.C * 9, (size_t)c0 * 9, cvalid * 9, cfill * 9);
+    if (!HALF) {
+        float *dst = static_cast<float *>(job.dst);
+        const int k_in = threadIdx.x & 15, csub = threadIdx.x >> 4;
+#pragma unroll 1
+        for (int j = 0; j < 4; ++j) {
+            const int cl = j * 16 + csub;
+            if (cl >= cfill) break;
+            float g[9], u[AA];
+#pragma unroll
+            for (int i = 0; i < 9; ++i) g[i] = lds[k_in * ROW + cl * 9 + i];
+            wino_u<SET>(g, u);
+            float *o = dst + ((size_t)kb * cpad + c0 + cl) * 16 + k_in;
+            const size_t xi_stride = (size_t)K16 * cpad * 16;
+#pragma unroll
+            for (int xi = 0; xi < AA; ++xi) o[xi * xi_stride] = u[xi];
+        }
+    } else {
+        __half *dst = static_cast<__half *>(job.dst);
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        const int oct = wave * 2 + (lane >> 5), hq = lane & 1, k_in = (lane >> 1) & 15;
+        if (oct * 8 < cfill) {
+            uint32_t lo[AA], hi[AA];
+#pragma unroll
+            for (int pr = 0; pr < 2; ++pr) {
+                float g0[9], g1[9], u0[AA], u1[AA];
+                const int cl = oct * 8 + hq * 4 + pr * 2;
+#pragma unroll
+                for (int i = 0; i < 9; ++i) {
+                    g0[i] = lds[k_in * ROW + cl * 9 + i];
+                    g1[i] = lds[k_in * ROW + (cl + 1) * 9 + i];
+                }
+                wino_u<SET>(g0, u0);
+                wino_u<SET>(g1, u1);
+#pragma unroll
+                for (int xi = 0; xi < AA; ++xi) {
+                    const uint32_t v = pack_half2(u0[xi], u1[xi]);
+                    if (pr == 0) lo[xi] = v; else hi[xi] = v;
+                }
+            }
+            const int cabs = c0 + oct * 8;
+            const int c32n = cpad / 32;
+            __half *o = dst + ((size_t)kb * c32n + cabs / 32) * 512 + ((cabs % 32) / 8) * 128 + k_in * 8 + hq * 4;
+            const size_t xi_stride = (size_t)K16 * c32n * 512;
+#pragma unroll
+            for (int xi = 0; xi < AA; ++xi)
+                *reinterpret_cast<uint2 *>(o + xi * xi_stride) = make_uint2(lo[xi], hi[xi]);
+        }
+    }
+}
+
+// GEMM panel pack of one block: 16 output channels x job.cchunk channels x RS taps.
+template <bool HALF>
+__device__ static inline void gemm_block(const TransformJob &job, int local_block, float *lds) {
+    const int kb = local_block / job.nchunks, chunk = local_block % job.nchunks;
+    const int RS = job.RS;
+    const int cpad = HALF ? ((job.C + 31) / 32) * 32 : ((job.C + 3) / 4) * 4;
+    const int c0 = chunk * job.cchunk;
+    const int cfill = min(job.cchunk, cpad - c0);
+    const int cvalid = max(0, min(job.cchunk, job.C - c0));
+    const int ROW = lds_row_stride(min(job.cchunk, cpad) * RS);
+    stage_rows(job.src, lds, ROW, kb * 16, job.K, (size_t)job.C * RS, (size_t)c0 * RS, cvalid * RS, cfill * RS);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int k_in = lane & 15, grp = lane >> 4;
+    if (!HALF) {
+        float *dst = static_cast<float *>(job.dst) + ((size_t)kb * (cpad / 4) + c0 / 4) * RS * 64;
+        const int nfrag = (cfill / 4) * RS;
+        int cb = 0, rs = wave;
+        while (rs >= RS) { rs -= RS; ++cb; }
+        for (int f = wave; f < nfrag; f += 4) {
+            const float v = lds[k_in * ROW + (cb * 4 + grp) * RS + rs];
+            dst[(size_t)f * 64 + lane] = v;
+            rs += 4;
+            while (rs >= RS) { rs -= RS; ++cb; }
+        }
+    } else {
+        __half *dst = static_cast<__half *>(job.dst) + ((size_t)kb * (cpad / 32) + c0 / 32) * RS * 512;
+        const int nfrag = (cfill / 32) * RS;
+        int cb = 0, rs = wave;
+        while (rs >= RS) { rs -= RS; ++cb; }
+        for (int f = wave; f < nfrag; f += 4) {
+            const float *lp = lds + k_in * ROW + (cb * 32 + grp * 8) * RS + rs;
+            uint4 v;
+            v.x = pack_half2(lp[0], lp[RS]);
+            v.y = pack_half2(lp[2 * RS], lp[3 * RS]);
+            v.z = pack_half2(lp[4 * RS], lp[5 * RS]);
+            v.w = pack_half2(lp[6 * RS], lp[7 * RS]);
+            *reinterpret_cast<uint4 *>(dst + (size_t)f * 512 + lane * 8) = v;
+            rs += 4;
+            while (rs >= RS) { rs -= RS; ++cb; }
+        }
+    }
+}
+
+// Depthwise repack (C,1,3,3) -> [C/32][9 taps][32 channels]; 256 outputs per block.
+template <bool HALF>
+__device__ static inline void dw_block(const TransformJob &job, int local_block) {
+    const int total = ((job.C + 31) / 32) * 288;
+    const int o = local_block * 256 + threadIdx.x;
+    if (o >= total) return;
+    const int cb = o / 288, rem = o - cb * 288, tap = rem >> 5, ci = rem & 31;
+    const int c = cb * 32 + ci;
+    const float v = (c < job.C) ? job.src[(size_t)c * 9 + tap] : 0.f;
+    if (HALF) static_cast<__half *>(job.dst)[o] = __float2half_rn(v);
+    else static_cast<float *>(job.dst)[o] = v;
+}
+
+__global__ __launch_bounds__(256) void transform_kernel(const JobTable tbl) {
+    extern __shared__ __align__(16) float lds[];
+    const int b = blockIdx.x;
+    int j = 0;
+    while (j + 1 < tbl.njobs && tbl.job[j + 1].block0 <= b) ++j;
+    const TransformJob &job = tbl.job[j];
+    const int lb = b - job.block0;
+    if (job.type == JOB_WINO) {
+        if (job.wset == WS_F2) {
+            if (job.half) wino_block<0, true>(job, lb, lds); else wino_block<0, false>(job, lb, lds);
+        } else if (job.wset == WS_F4) {
+            wino_block<1, false>(job, lb, lds);
+        } else {
+            wino_block<2, true>(job, lb, lds);
+        }
+    } else if (job.type == JOB_GEMM) {
+        if (job.half) gemm_block<true>(job, lb, lds); else gemm_block<false>(job, lb, lds);
+    } else {
+        if (job.half) dw_block<true>(job, lb); else dw_block<false>(job, lb);
+    }
+}
+
+// ---------------------------------------------------------------- host side
+
+int fill_transform_job(const Geo &g, int kind, const float *src, void *dst, TransformJob *job) {
+    job->src = src;
+    job->dst = dst;
+    job->half = g.dtype == NNV_F16;
+    job->K = g.k;
+    job->C = g.cg;
+    job->RS = g.r * g.s;
+    job->wset = 0;
+    job->block0 = 0;
+    const int k16 = ceil_div(g.k, 16);
+    if (kind == NNV_WINO_F2 || kind == NNV_WINO_F4) {
+        job->type = JOB_WINO;
+        job->wset = wino_set(kind, g.dtype);
+        const int cpad = job->half ? ceil_div(g.cg, 32) * 32 : ceil_div(g.cg, 4) * 4;
+        job->cchunk = 64;
+        job->nchunks = ceil_div(cpad, 64);
+        job->nblocks = k16 * job->nchunks;
+    } else if (kind == NNV_IM2COL_GEMM) {
+        job->type = JOB_GEMM;
+        const int cpad = job->half ? ceil_div(g.cg, 32) * 32 : ceil_div(g.cg, 4) * 4;
+        int cc = (1024 / job->RS) / 32 * 32;
+        if (cc < 32) cc = 32;
+        job->cchunk = cc;
+        job->nchunks = ceil_div(cpad, cc);
+        job->nblocks = k16 * job->nchunks;
+    } else if (kind == NNV_DEPTHWISE) {
+        job->type = JOB_DW;
+        job->cchunk = 32;
+        job->nchunks = 1;
+        job->nblocks = ceil_div(ceil_div(g.c, 32) * 288, 256);
+        job->C = g.c;
+    } else {
+        return -1;
+    }
+    return 0;
+}
+
+size_t transform_job_lds_bytes(const TransformJob &job) {
+    if (job.type == JOB_WINO) return (size_t)kRows * lds_row_stride(64 * 9) * sizeof(float);
+    if (job.type == JOB_GEMM) {
+        const int cpad = job.half ? ceil_div(job.C, 32) * 32 : ceil_div(job.C, 4) * 4;
+        const int cc = job.cchunk < cpad ? job.cchunk : cpad;
+        return (size_t)kRows * lds_row_stride(cc * job.RS) * sizeof(float);
+    }
+    return 0;
+}
+
+hipError_t launch_transform_jobs(const JobTable &tbl, int total_blocks, size_t lds, hipStream_t st) {
+    if (total_blocks <= 0) return hipSuccess;
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(transform_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(transform_kernel, dim3(total_blocks), dim3(256), lds, st, tbl);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void copy_f32_kernel(const float *__restrict__ src, float *__restrict__ dst, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+hipError_t launch_copy_f32(const float *src, float *dst, size_t n, hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(copy_f32_kernel, dim3((unsigned)blocks), dim3(256), 0, st, src, dst, n);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void fill_u32_kernel(uint4 *__restrict__ dst, size_t n4, uint32_t v) {
+    const uint4 val = make_uint4(v, v, v, v);
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) dst[i] = val;
+}
+
+// Overwrite n 32-bit words (n rounded down to a multiple of 4): the cache flush of nnv_time_layer.
+hipError_t launch_fill_u32(uint32_t *dst, size_t n, uint32_t v, hipStream_t st) {
+    const size_t n4 = n / 4;
+    if (n4 == 0) return hipSuccess;
+    size_t blocks = (n4 + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)blocks), dim3(256), 0, st, reinterpret_cast<uint4 *>(dst), n4, v);
+    return hipGetLastError();
+}
+
+}  // namespace nnv

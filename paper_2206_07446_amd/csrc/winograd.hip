@@ -1,0 +1,310 @@
+// Winograd F(2x2,3x3) / F(4x4,3x3) convolution from transformed weights (the fastest
+// executing, most expensive to prepare kernel family of Table 2).  Three kernels:
+//   1. input transform   V[xi][tile block][c][16 tiles] = (B^T d B)[xi]   (vector ALU)
+//   2. batched tile GEMM M[xi] = U[xi] (K x C) * V[xi] (C x T), alpha^2 independent
+//      products on the matrix cores; U and V are stored as ready-made 16-row operand
+//      fragments, so both are read with one coalesced load per fragment and no LDS
+//   3. output transform  Y = A^T M A, clipped to P x Q, plus bias        (vector ALU)
+// V and M live in the caller's workspace.  float16 storage keeps U, V and y in half
+// precision; the transforms and the accumulation are float32.
+#include <type_traits>
+#include "nnv_internal.h"
+#include "wino_consts.h"
+
+namespace nnv {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+
+struct WinoParams {
+    const void *x;
+    const void *U;
+    void *V;
+    float *M;
+    const float *bias;
+    void *y;
+    int N, C, H, W, K, ph, pw, P, Q;
+    int th, tw, T, T16;     // tiles per image (rows, cols), total tiles, 16-blocks of tiles
+    int K16, cpad, csteps;  // cpad: channels padded to 4 (float32) / 32 (float16); csteps = cpad / that
+    int wn_shift;           // wavefronts of a workgroup along the tile dimension = 1 << wn_shift
+};
+
+// out[i][j] = sum_k L[i][k] * in[k][j] with a compile-time matrix L (zeros skipped).
+#define NNV_MATMUL_LEFT(L, ROWS, INNER, COLS, in, out)                                  \
+    _Pragma("unroll") for (int i_ = 0; i_ < ROWS; ++i_) _Pragma("unroll") for (int j_ = 0; j_ < COLS; ++j_) { \
+        float acc_ = 0.f;                                                               \
+        _Pragma("unroll") for (int k_ = 0; k_ < INNER; ++k_) if (L[i_][k_] != 0.f) acc_ += L[i_][k_] * in[k_][j_]; \
+        out[i_][j_] = acc_;                                                             \
+    }
+// out[i][j] = sum_k in[i][k] * Rm[j][k]   (right-multiply by Rm^T)
+#define NNV_MATMUL_RIGHT_T(Rm, ROWS, INNER, COLS, in, out)                              \
+    _Pragma("unroll") for (int i_ = 0; i_ < ROWS; ++i_) _Pragma("unroll") for (int j_ = 0; j_ < COLS; ++j_) { \
+        float acc_ = 0.f;                                                               \
+        _Pragma("unroll") for (int k_ = 0; k_ < INNER; ++k_) if (Rm[j_][k_] != 0.f) acc_ += in[i_][k_] * Rm[j_][k_]; \
+        out[i_][j_] = acc_;                                                             \
+    }
+
+template <typename T> __device__ static inline float ldx(const T *p, size_t i);
+template <> __device__ inline float ldx<float>(const float *p, size_t i) { return p[i]; }
+template <> __device__ inline float ldx<__half>(const __half *p, size_t i) { return __half2float(p[i]); }
+
+// ---- 1. input transform.  Block = 16 tiles x 16 channels.
+template <int SET, bool HALF>
+__global__ __launch_bounds__(256) void wino_input_kernel(const WinoParams w) {
+    using Wm = WinoMat<SET>;
+    constexpr int A = Wm::A, M = Wm::M;
+    typedef typename std::conditional<HALF, __half, float>::type T;
+    int t_in, c;
+    if (HALF) {   // lanes: 8 channels fastest, then tiles -> 128 B contiguous half stores
+        t_in = (threadIdx.x >> 3) & 15;
+        c = blockIdx.y * 16 + (threadIdx.x >> 7) * 8 + (threadIdx.x & 7);
+    } else {      // lanes: 16 tiles fastest, then channels -> 256 B contiguous stores
+        t_in = threadIdx.x & 15;
+        c = blockIdx.y * 16 + (threadIdx.x >> 4);
+    }
+    if (c >= w.cpad) return;
+    const int tb = blockIdx.x, t = tb * 16 + t_in;
+    float d[A][A];
+#pragma unroll
+    for (int u = 0; u < A; ++u)
+#pragma unroll
+        for (int v = 0; v < A; ++v) d[u][v] = 0.f;
+    if (t < w.T && c < w.C) {
+        const int per = w.th * w.tw;
+        const int img = t / per, rem = t - img * per;
+        const int ti = rem / w.tw, tj = rem - ti * w.tw;
+        const int ih0 = ti * M - w.ph, iw0 = tj * M - w.pw;
+        const T *xc = static_cast<const T *>(w.x) + ((size_t)img * w.C + c) * w.H * w.W;
+#pragma unroll
+        for (int u = 0; u < A; ++u) {
+            const int ih = ih0 + u;
+            const bool rok = ih >= 0 && ih < w.H;
+#pragma unroll
+            for (int v = 0; v < A; ++v) {
+                const int iw = iw0 + v;
+                if (rok && iw >= 0 && iw < w.W) d[u][v] = ldx<T>(xc, (size_t)ih * w.W + iw);
+            }
+        }
+    }
+    float tmp[A][A], V[A][A];
+    NNV_MATMUL_LEFT(Wm::BT, A, A, A, d, tmp)
+    NNV_MATMUL_RIGHT_T(Wm::BT, A, A, A, tmp, V)
+    if (HALF) {
+        __half *o = static_cast<__half *>(w.V) + ((size_t)tb * w.csteps + c / 32) * 512 + ((c % 32) / 8) * 128 + t_in * 8 + (c & 7);
+        const size_t xs = (size_t)w.T16 * w.csteps * 512;
+#pragma unroll
+        for (int u = 0; u < A; ++u)
+#pragma unroll
+            for (int v = 0; v < A; ++v) o[(u * A + v) * xs] = __float2half_rn(V[u][v]);
+    } else {
+        float *o = static_cast<float *>(w.V) + ((size_t)tb * w.cpad + c) * 16 + t_in;
+        const size_t xs = (size_t)w.T16 * w.cpad * 16;
+#pragma unroll
+        for (int u = 0; u < A; ++u)
+#pragma unroll
+            for (int v = 0; v < A; ++v) o[(u * A + v) * xs] = V[u][v];
+    }
+}
+
+// ---- 2. batched tile GEMM.  grid = (tile-block groups, k-block groups, alpha^2).
+template <bool HALF> struct WFrag {
+    typedef float type;
+    __device__ static inline float zero() { return 0.f; }
+};
+template <> struct WFrag<true> {
+    typedef half8 type;
+    __device__ static inline half8 zero() { return half8{0, 0, 0, 0, 0, 0, 0, 0}; }
+};
+
+template <bool HALF, int TM, int TN, int D>
+__global__ __launch_bounds__(256) void wino_gemm_kernel(const WinoParams w) {
+    typedef typename WFrag<HALF>::type frag_t;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wn = wave & ((1 << w.wn_shift) - 1), wm = wave >> w.wn_shift;
+    const int wm_count = 4 >> w.wn_shift;
+    const int kb0 = (blockIdx.y * wm_count + wm) * TM;
+    const int tb0 = ((blockIdx.x << w.wn_shift) + wn) * TN;
+    const int xi = blockIdx.z;
+    const frag_t *Uf = static_cast<const frag_t *>(w.U) + (size_t)xi * w.K16 * w.csteps * 64 + lane;
+    const frag_t *Vf = static_cast<const frag_t *>(w.V) + (size_t)xi * w.T16 * w.csteps * 64 + lane;
+
+    frag_t a[2][D][TM], b[2][D][TN];
+    int lstep = 0;
+    auto load_chunk = [&](int buf) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            const bool live = lstep < w.csteps;
+#pragma unroll
+            for (int m = 0; m < TM; ++m) {
+                frag_t v = WFrag<HALF>::zero();
+                if (live && kb0 + m < w.K16) v = Uf[((size_t)(kb0 + m) * w.csteps + lstep) * 64];
+                a[buf][d][m] = v;
+            }
+#pragma unroll
+            for (int t = 0; t < TN; ++t) {
+                frag_t v = WFrag<HALF>::zero();
+                if (live && tb0 + t < w.T16) v = Vf[((size_t)(tb0 + t) * w.csteps + lstep) * 64];
+                b[buf][d][t] = v;
+            }
+            ++lstep;
+        }
+    };
+    floatx4 acc[TM][TN];
+#pragma unroll
+    for (int m = 0; m < TM; ++m)
+#pragma unroll
+        for (int t = 0; t < TN; ++t) acc[m][t] = floatx4{0.f, 0.f, 0.f, 0.f};
+    auto compute = [&](int buf) {
+#pragma unroll
+        for (int d = 0; d < D; ++d)
+#pragma unroll
+            for (int m = 0; m < TM; ++m)
+#pragma unroll
+                for (int t = 0; t < TN; ++t) {
+                    if constexpr (HALF)
+                        acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[buf][d][m], b[buf][d][t], acc[m][t], 0, 0, 0);
+                    else
+                        acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[buf][d][m], b[buf][d][t], acc[m][t], 0, 0, 0);
+                }
+    };
+    load_chunk(0);
+    for (int base = 0; base < w.csteps; base += 2 * D) {
+        load_chunk(1);
+        compute(0);
+        load_chunk(0);
+        if (base + D < w.csteps) compute(1);
+    }
+    // M[xi][kb][tb][16 k][16 t]: lane holds rows 4*(lane/16)+j, column lane%16
+    const int col = lane & 15, slot = lane >> 4;
+#pragma unroll
+    for (int m = 0; m < TM; ++m) {
+        if (kb0 + m >= w.K16) continue;
+#pragma unroll
+        for (int t = 0; t < TN; ++t) {
+            if (tb0 + t >= w.T16) continue;
+            float *o = w.M + (((size_t)xi * w.K16 + kb0 + m) * w.T16 + tb0 + t) * 256 + slot * 64 + col;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) o[j * 16] = acc[m][t][j];
+        }
+    }
+}
+
+// ---- 3. output transform.  Block = 16 tiles x 16 output channels.
+template <int SET, bool HALF>
+__global__ __launch_bounds__(256) void wino_output_kernel(const WinoParams w) {
+    using Wm = WinoMat<SET>;
+    constexpr int A = Wm::A, M = Wm::M;
+    const int t_in = threadIdx.x & 15, k_in = threadIdx.x >> 4;
+    const int tb = blockIdx.x, kb = blockIdx.y;
+    const int t = tb * 16 + t_in, k = kb * 16 + k_in;
+    if (t >= w.T || k >= w.K) return;
+    const float *mp = w.M + ((size_t)kb * w.T16 + tb) * 256 + k_in * 16 + t_in;
+    const size_t xs = (size_t)w.K16 * w.T16 * 256;
+    float m[A][A];
+#pragma unroll
+    for (int u = 0; u < A; ++u)
+#pragma unroll
+        for (int v = 0; v < A; ++v) m[u][v] = mp[(u * A + v) * xs];
+    float tmp[M][A], Y[M][M];
+    NNV_MATMUL_LEFT(Wm::AT, M, A, A, m, tmp)
+    NNV_MATMUL_RIGHT_T(Wm::AT, M, A, M, tmp, Y)
+    const int per = w.th * w.tw;
+    const int img = t / per, rem = t - img * per;
+    const int ti = rem / w.tw, tj = rem - ti * w.tw;
+    const float bv = w.bias ? w.bias[k] : 0.f;
+    const size_t base = ((size_t)img * w.K + k) * w.P * w.Q;
+#pragma unroll
+    for (int a = 0; a < M; ++a) {
+        const int p = ti * M + a;
+        if (p >= w.P) continue;
+#pragma unroll
+        for (int b = 0; b < M; ++b) {
+            const int q = tj * M + b;
+            if (q >= w.Q) continue;
+            const float v = Y[a][b] + bv;
+            if (HALF) static_cast<__half *>(w.y)[base + (size_t)p * w.Q + q] = __float2half_rn(v);
+            else static_cast<float *>(w.y)[base + (size_t)p * w.Q + q] = v;
+        }
+    }
+}
+
+// ---------------------------------------------------------------- host side
+
+struct WinoPlan {
+    int m, alpha, th, tw, T, T16, K16, cpad, csteps;
+    size_t v_bytes, m_bytes;
+};
+
+static WinoPlan plan_wino(const Geo &g, int kind) {
+    WinoPlan p{};
+    const bool half = g.dtype == NNV_F16;
+    p.m = kind == NNV_WINO_F2 ? 2 : 4;
+    p.alpha = p.m + 2;
+    p.th = ceil_div(g.p, p.m);
+    p.tw = ceil_div(g.q, p.m);
+    p.T = g.n * p.th * p.tw;
+    p.T16 = ceil_div(p.T, 16);
+    p.K16 = ceil_div(g.k, 16);
+    const int cb = half ? 32 : 4;
+    p.csteps = ceil_div(g.c, cb);
+    p.cpad = p.csteps * cb;
+    const size_t aa = (size_t)p.alpha * p.alpha;
+    p.v_bytes = align_up(aa * p.T16 * 16 * p.cpad * (half ? 2 : 4), 256);
+    p.m_bytes = align_up(aa * p.K16 * p.T16 * 256 * sizeof(float), 256);
+    return p;
+}
+
+size_t wino_workspace_bytes(const Geo &g, int kind) {
+    const WinoPlan p = plan_wino(g, kind);
+    return p.v_bytes + p.m_bytes;
+}
+
+template <int SET, bool HALF>
+static hipError_t launch_wino_t(const Geo &g, const WinoPlan &p, WinoParams &w, hipStream_t st) {
+    {
+        dim3 grid(p.T16, ceil_div(p.cpad, 16), 1);
+        hipLaunchKernelGGL((wino_input_kernel<SET, HALF>), grid, dim3(256), 0, st, w);
+    }
+    {
+        // wavefront tile and workgroup shape: fill >= 1024 wavefronts when the layer allows it
+        const long aa = (long)p.alpha * p.alpha;
+        int tm = 2, tn = 2;
+        if (aa * ceil_div(p.K16, 2) * ceil_div(p.T16, 2) < 1024) { tn = 1; }
+        if (aa * ceil_div(p.K16, tm) * ceil_div(p.T16, tn) < 1024) { tm = 1; }
+        int wn_shift = 2;
+        while (wn_shift > 0 && (1 << wn_shift) * tn > p.T16) --wn_shift;   // do not spread waves over missing tiles
+        w.wn_shift = wn_shift;
+        const int wm_count = 4 >> wn_shift;
+        dim3 grid(ceil_div(p.T16, tn << wn_shift), ceil_div(p.K16, tm * wm_count), (unsigned)aa);
+        constexpr int D = HALF ? 2 : 4;
+        if (tm == 2 && tn == 2) hipLaunchKernelGGL((wino_gemm_kernel<HALF, 2, 2, D>), grid, dim3(256), 0, st, w);
+        else if (tm == 2 && tn == 1) hipLaunchKernelGGL((wino_gemm_kernel<HALF, 2, 1, D>), grid, dim3(256), 0, st, w);
+        else hipLaunchKernelGGL((wino_gemm_kernel<HALF, 1, 1, D>), grid, dim3(256), 0, st, w);
+    }
+    {
+        dim3 grid(p.T16, p.K16, 1);
+        hipLaunchKernelGGL((wino_output_kernel<SET, HALF>), grid, dim3(256), 0, st, w);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_wino(const Geo &g, int kind, const void *x, const void *U, const float *bias, void *y, void *ws,
+                       hipStream_t st) {
+    const WinoPlan p = plan_wino(g, kind);
+    if (p.T16 > 65535 * 16 || p.K16 > 65535) return hipErrorInvalidValue;
+    WinoParams w{};
+    w.x = x; w.U = U; w.bias = bias; w.y = y;
+    w.V = ws;
+    w.M = reinterpret_cast<float *>(static_cast<char *>(ws) + p.v_bytes);
+    w.N = g.n; w.C = g.c; w.H = g.h; w.W = g.w; w.K = g.k; w.ph = g.ph; w.pw = g.pw; w.P = g.p; w.Q = g.q;
+    w.th = p.th; w.tw = p.tw; w.T = p.T; w.T16 = p.T16; w.K16 = p.K16; w.cpad = p.cpad; w.csteps = p.csteps;
+    const int set = wino_set(kind, g.dtype);
+    if (set == WS_F2) {
+        if (g.dtype == NNV_F16) return launch_wino_t<0, true>(g, p, w, st);
+        return launch_wino_t<0, false>(g, p, w, st);
+    }
+    if (set == WS_F4) return launch_wino_t<1, false>(g, p, w, st);
+    return launch_wino_t<2, true>(g, p, w, st);
+}
+
+}  // namespace nnv

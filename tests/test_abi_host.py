@@ -1,0 +1,106 @@
+"""Host-only checks of the C ABI: the library loads, exports every declared symbol, and
+validates descriptors and arguments without touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2206_07446_amd as nnv
+from nnv_workloads import stack, STACK_NAMES
+from oracle import layouts as OL
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_header_symbols_exported():
+    hdr = open(os.path.join(ROOT, "include", "nnv.h")).read()
+    declared = set(re.findall(r"\b(nnv_[a-z_]+)\s*\(", hdr))
+    assert declared == set(nnv.EXPORTS)
+    lib = nnv.load()
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_version_and_status_strings():
+    assert nnv.nnv_layout_version() == 1
+    assert nnv.nnv_status_string(0) == "ok"
+    for s in range(-7, 0):
+        assert nnv.nnv_status_string(s) not in ("ok", "unknown status")
+    assert nnv.nnv_status_string(-99) == "unknown status"
+
+
+def D(**kw):
+    base = dict(n=1, c=16, h=32, w=32, k=16, r=3, s=3, stride_h=1, stride_w=1, pad_h=1, pad_w=1, groups=1, dtype=0)
+    base.update(kw)
+    return nnv.ConvDesc(**base)
+
+
+def test_kind_supported_rules():
+    d = D()
+    assert [nnv.nnv_kind_supported(d, k) for k in range(5)] == [True, True, True, True, False]
+    d = D(stride_h=2, stride_w=2)
+    assert [nnv.nnv_kind_supported(d, k) for k in range(5)] == [True, True, False, False, False]
+    d = D(groups=16)
+    assert [nnv.nnv_kind_supported(d, k) for k in range(5)] == [True, False, False, False, True]
+    d = D(groups=16, stride_h=2, stride_w=2)
+    assert nnv.nnv_kind_supported(d, nnv.DEPTHWISE)
+    d = D(r=7, s=7, pad_h=3, pad_w=3, stride_h=2, stride_w=2, c=3)
+    assert [nnv.nnv_kind_supported(d, k) for k in range(5)] == [True, True, False, False, False]
+    d = D(groups=2)
+    assert [nnv.nnv_kind_supported(d, k) for k in range(5)] == [True, False, False, False, False]
+
+
+@pytest.mark.parametrize("bad", [dict(n=0), dict(c=-1), dict(groups=3), dict(stride_h=0), dict(pad_w=-1),
+                                 dict(dtype=2), dict(h=1, w=1, pad_h=0, pad_w=0), dict(k=70000)])
+def test_bad_descriptors(bad):
+    d = D(**bad)
+    with pytest.raises(nnv.NnvError) as e:
+        nnv.nnv_kind_supported(d, 0)
+    assert e.value.status == -2
+    assert nnv.nnv_transformed_bytes(d, 0) == 0
+    assert nnv.nnv_workspace_bytes(d, 1) == 0
+
+
+def test_null_and_argument_errors_need_no_gpu():
+    lib = nnv.load()
+    d = D()
+    assert lib.nnv_transform_weights(None, 0, None, None, None) == -1
+    assert lib.nnv_transform_weights(ctypes.byref(d), 1, None, None, None) == -1
+    assert lib.nnv_transform_weights(ctypes.byref(d), 9, ctypes.c_void_p(256), ctypes.c_void_p(512), None) == -7
+    assert lib.nnv_transform_weights(ctypes.byref(d), 4, ctypes.c_void_p(256), ctypes.c_void_p(512), None) == -3
+    assert lib.nnv_transform_weights(ctypes.byref(d), 1, ctypes.c_void_p(260), ctypes.c_void_p(512), None) == -5
+    assert lib.nnv_conv_forward(ctypes.byref(d), 1, None, None, None, None, None, 0, None) == -1
+    assert lib.nnv_conv_forward(ctypes.byref(d), 3, ctypes.c_void_p(256), ctypes.c_void_p(256), None,
+                                ctypes.c_void_p(256), ctypes.c_void_p(256), 16, None) == -4
+    assert lib.nnv_time_layer(ctypes.byref(d), 1, None, None, None, None, None, 0, None, 0, 1, 1, None, None) == -1
+    t = nnv.Timing()
+    assert lib.nnv_time_layer(ctypes.byref(d), 1, ctypes.c_void_p(256), ctypes.c_void_p(256), ctypes.c_void_p(256),
+                              ctypes.c_void_p(256), None, 0, None, 0, 1, 0, None, ctypes.byref(t)) == -7
+    assert lib.nnv_transform_weights_grouped(-1, None, None, None, None, None) == -7
+    assert lib.nnv_transform_weights_grouped(0, None, None, None, None, None) == 0
+
+
+KNAME = {0: "direct", 1: "im2col_gemm", 2: "wino_f2", 3: "wino_f4", 4: "depthwise"}
+
+
+@pytest.mark.parametrize("name", STACK_NAMES)
+def test_transformed_bytes_match_oracle_layout_sizes(name):
+    for layer in stack(name):
+        for half in (False, True):
+            d = nnv.make_desc(layer, nnv.F16 if half else nnv.F32)
+            for kind in range(5):
+                if not nnv.nnv_kind_supported(d, kind):
+                    assert nnv.nnv_transformed_bytes(d, kind) == 0
+                    continue
+                exp = OL.transformed_bytes(KNAME[kind], layer.k, layer.cg, layer.r, layer.s, half)
+                assert nnv.nnv_transformed_bytes(d, kind) == exp, (layer.name, kind, half)
+
+
+def test_winograd_size_ratio_unpadded():
+    """alpha^2/9 growth of 3x3 weights (16/9, 4) when no padding is needed."""
+    d = D(c=64, k=64)
+    raw = 64 * 64 * 9 * 4
+    assert nnv.nnv_transformed_bytes(d, nnv.WINO_F2) * 9 == raw * 16
+    assert nnv.nnv_transformed_bytes(d, nnv.WINO_F4) * 9 == raw * 36
+    assert nnv.nnv_transformed_bytes(d, nnv.IM2COL_GEMM) == raw

@@ -1,0 +1,170 @@
+"""GPU parity of the weight transformations against the oracle's packed layouts."""
+import numpy as np
+import pytest
+
+from nnv_workloads import ConvLayer, stack, layer_tensors
+from nnv_testlib import gpu_transform, oracle_transformed, KIND_NAMES
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    import paper_2206_07446_amd as nnv
+    assert torch.cuda.is_available(), "GPU tests need the HIP device"
+    nnv.load()
+    return nnv, torch
+
+
+def L(c, k, r=3, hw=8, stride=1, pad=1, groups=1):
+    return ConvLayer(f"t{c}_{k}_{r}", c, hw, hw, k, r, r, stride, pad, groups)
+
+
+GEMM_LAYERS = [L(16, 16), L(37, 20), L(3, 64, r=7, hw=16, stride=2, pad=3), L(144, 24, r=1, pad=0),
+               L(1100, 40, r=1, pad=0), L(130, 33), L(5, 3, r=5, pad=2), L(64, 128, stride=2)]
+WINO_LAYERS = [L(16, 16), L(37, 20), L(64, 64), L(3, 64), L(130, 33), L(200, 17)]
+DW_LAYERS = [L(32, 32, groups=32), L(144, 144, groups=144), L(5, 5, groups=5), L(960, 960, groups=960)]
+
+
+def _index_coded(layer, half):
+    n = layer.k * layer.cg * layer.r * layer.s
+    w = np.arange(n, dtype=np.float64)
+    if half:
+        w = w % 2048          # exact in float16
+    assert n < 2 ** 24
+    return w.astype(np.float32).reshape(layer.k, layer.cg, layer.r, layer.s)
+
+
+@pytest.mark.parametrize("half", [False, True])
+@pytest.mark.parametrize("layer", GEMM_LAYERS, ids=lambda l: l.name)
+def test_gemm_pack_bit_exact(env, layer, half):
+    nnv, torch = env
+    for w in (_index_coded(layer, half), layer_tensors(layer, 5)[0]):
+        got, *_ = gpu_transform(nnv, torch, layer, nnv.IM2COL_GEMM, half, w)
+        exp, _ = oracle_transformed(w, nnv.IM2COL_GEMM, half)
+        assert got.dtype == exp.dtype and got.shape == exp.shape
+        assert np.array_equal(got.view(np.uint16 if half else np.uint32), exp.view(np.uint16 if half else np.uint32))
+
+
+@pytest.mark.parametrize("half", [False, True])
+@pytest.mark.parametrize("layer", DW_LAYERS, ids=lambda l: l.name)
+def test_depthwise_pack_bit_exact(env, layer, half):
+    nnv, torch = env
+    for w in (_index_coded(layer, half), layer_tensors(layer, 6)[0]):
+        got, *_ = gpu_transform(nnv, torch, layer, nnv.DEPTHWISE, half, w)
+        exp, _ = oracle_transformed(w, nnv.DEPTHWISE, half)
+        assert got.shape == exp.shape
+        assert np.array_equal(got.view(np.uint16 if half else np.uint32), exp.view(np.uint16 if half else np.uint32))
+
+
+def test_direct_transform_is_identity(env):
+    nnv, torch = env
+    layer = L(37, 20)
+    w = layer_tensors(layer, 7)[0]
+    got, wt, wd, desc = gpu_transform(nnv, torch, layer, nnv.DIRECT, False, w)
+    assert np.array_equal(got.view(np.uint32), w.reshape(-1).view(np.uint32))
+    nnv.nnv_transform_weights(desc, nnv.DIRECT, wd, wd)      # aliasing is a no-op
+    torch.cuda.synchronize()
+    assert np.array_equal(wd.cpu().numpy(), w)
+
+
+def check_wino_u(got, exp64, bound, half):
+    """Position: padding lanes are +0 bitwise and every logical element sits where the oracle
+    puts it.  Value: float32 within 8 * 2^-24 * (|G||g||G^T|) (two 3-term products with constants
+    rounded once); float16 additionally within one half-precision ulp of the rounded oracle value."""
+    u = 2.0 ** -24
+    tol = 8 * u * bound
+    if half:
+        tol = tol + 2.0 ** -10 * np.abs(exp64) + 2.0 ** -24
+    pad_mask = bound == 0
+    raw = got.view(np.uint16 if half else np.uint32)
+    g64 = got.astype(np.float64)
+    # where the bound is zero the expected value is exactly zero (padding or all-zero filters)
+    assert (np.abs(g64[pad_mask]) == 0).all()
+    err = np.abs(g64 - exp64)
+    assert (err <= tol).all(), f"max excess {(err - tol).max():.3e}"
+    return raw, pad_mask
+
+
+@pytest.mark.parametrize("half", [False, True])
+@pytest.mark.parametrize("kind", [2, 3], ids=["f2", "f4"])
+@pytest.mark.parametrize("layer", WINO_LAYERS, ids=lambda l: l.name)
+def test_wino_weight_transform(env, layer, kind, half):
+    nnv, torch = env
+    w = layer_tensors(layer, 8)[0]
+    got, *_ = gpu_transform(nnv, torch, layer, kind, half, w)
+    exp64, bound = oracle_transformed(w, kind, half)
+    assert got.shape == exp64.shape
+    raw, pad_mask = check_wino_u(got, exp64, bound, half)
+    # padding lanes must be +0.0 bitwise (random weights: bound == 0 only on padding)
+    assert (raw[pad_mask] == 0).all()
+
+
+@pytest.mark.parametrize("kind", [2, 3], ids=["f2", "f4"])
+def test_wino_positions_with_delta_filters(env, kind):
+    """Centre-delta filters scaled by a (k,c) code: U[xi,k,c] = code * (G[:,1] G[:,1]^T)[xi] puts a
+    distinct, exactly representable multiple at every position."""
+    nnv, torch = env
+    layer = L(37, 20)
+    code = (np.arange(layer.k * layer.c).reshape(layer.k, layer.c) + 1) * 64.0
+    w = np.zeros((layer.k, layer.c, 3, 3), np.float32)
+    w[:, :, 1, 1] = code
+    got, *_ = gpu_transform(nnv, torch, layer, kind, False, w)
+    exp64, bound = oracle_transformed(w, kind, False)
+    check_wino_u(got, exp64, bound, False)
+    nz = exp64 != 0
+    assert np.array_equal(got != 0, nz)
+
+
+def test_grouped_transform_matches_single(env):
+    nnv, torch = env
+    dev = torch.device("cuda:0")
+    layers = stack("resnet18") + stack("mobilenetv2")[:12]
+    descs, kinds, srcs, dsts, singles = [], [], [], [], []
+    for i, layer in enumerate(layers):
+        if layer.is_depthwise:
+            kind = nnv.DEPTHWISE
+        elif layer.winograd_ok:
+            kind = nnv.WINO_F4 if i % 2 else nnv.WINO_F2
+        else:
+            kind = nnv.IM2COL_GEMM
+        desc = nnv.make_desc(layer, nnv.F16 if i % 3 == 0 else nnv.F32)
+        w = torch.from_numpy(layer_tensors(layer, 100 + i)[0]).to(dev)
+        nb = nnv.nnv_transformed_bytes(desc, kind)
+        a = torch.zeros(nb, dtype=torch.uint8, device=dev)
+        b = torch.zeros(nb, dtype=torch.uint8, device=dev)
+        nnv.nnv_transform_weights(desc, kind, w, a)
+        descs.append(desc); kinds.append(kind); srcs.append(w); dsts.append(b); singles.append(a)
+    assert len(layers) < 40
+    nnv.nnv_transform_weights_grouped(descs, kinds, srcs, dsts)
+    torch.cuda.synchronize()
+    for a, b, layer in zip(singles, dsts, layers):
+        assert torch.equal(a, b), layer.name
+    # more layers than one launch carries
+    many = 45
+    layer = L(16, 16)
+    desc = nnv.make_desc(layer, nnv.F32)
+    w = torch.from_numpy(layer_tensors(layer, 3)[0]).to(dev)
+    nb = nnv.nnv_transformed_bytes(desc, nnv.WINO_F4)
+    outs = [torch.zeros(nb, dtype=torch.uint8, device=dev) for _ in range(many)]
+    nnv.nnv_transform_weights_grouped([desc] * many, [nnv.WINO_F4] * many, [w] * many, outs)
+    torch.cuda.synchronize()
+    for o in outs[1:]:
+        assert torch.equal(o, outs[0])
+    assert outs[0].any()
+
+
+def test_full_size_resnet18_transforms(env):
+    """Every ResNet-18-shaped layer, full size: GEMM panels bit-exact, Winograd U within bound."""
+    nnv, torch = env
+    for i, layer in enumerate(stack("resnet18")):
+        w = layer_tensors(layer, 220607446 + 2000 + i)[0]
+        got, *_ = gpu_transform(nnv, torch, layer, nnv.IM2COL_GEMM, False, w)
+        exp, _ = oracle_transformed(w, nnv.IM2COL_GEMM, False)
+        assert np.array_equal(got.view(np.uint32), exp.view(np.uint32)), layer.name
+        if layer.winograd_ok:
+            for kind in (2, 3):
+                got, *_ = gpu_transform(nnv, torch, layer, kind, False, w)
+                exp64, bound = oracle_transformed(w, kind, False)
+                check_wino_u(got, exp64, bound, False)

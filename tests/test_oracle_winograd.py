@@ -166,21 +166,27 @@ def test_input_transform_tile_geometry():
 
 
 def _sim_half(variant, C, K, HW, seed):
-    """Winograd with U, V and y rounded to float16 (fp32 in between), error vs direct."""
+    """Winograd with U, V and y stored in float16: error vs direct, share of subnormal U."""
     rng = np.random.default_rng(seed)
     w = (rng.standard_normal((K, C, 3, 3)) * np.sqrt(2 / (C * 9))).astype(np.float32)
     x = rng.uniform(-1, 1, (1, C, HW, HW)).astype(np.float16)
     ref = conv2d_direct(x.astype(np.float64), w.astype(np.float64), 1, 1)
-    AT, _, _ = wg.matrices(variant)
     U = wg.transform_weights(w, variant).astype(np.float32).astype(np.float16)
     sub = np.mean((np.abs(U.astype(np.float32)) < 2.0 ** -14) & (U != 0))
-    V = wg.transform_input(x.astype(np.float64), variant, 1).astype(np.float32).astype(np.float16)
-    m = wg.tile_m(variant)
-    Mf = np.einsum("uvkc,uvncij->uvnkij", U.astype(np.float64), V.astype(np.float64)).astype(np.float32)
-    th = V.shape[4]
-    Y = np.einsum("pu,uvnkij,qv->nkipjq", AT, Mf.astype(np.float64), AT).reshape(1, K, th * m, th * m)
-    y = Y[:, :, :HW, :HW].astype(np.float16).astype(np.float64)
+    y = wg.conv2d_winograd_stored(x, w, variant, 1, store=np.float16)
     return np.abs(y - ref).max() / np.abs(ref).max(), sub
+
+
+@pytest.mark.parametrize("variant", list(wg.VARIANTS))
+def test_stored_variant_with_float64_storage_is_the_plain_one(variant):
+    rng = np.random.default_rng(21)
+    x = rng.uniform(-1, 1, (2, 3, 9, 7))
+    w = rng.standard_normal((4, 3, 3, 3))
+    b = rng.standard_normal(4)
+    a = wg.conv2d_winograd_stored(x, w, variant, 1, b, store=np.float64)
+    ref = wg.conv2d_winograd(x, w, variant, 1, b)
+    # only the float32 hop of the accumulator separates the two
+    assert np.abs(a - ref).max() <= 1e-6 * np.abs(ref).max()
 
 
 def test_half_precision_error_study():
