@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the conv hot path: cold weight transformation + convolution of a whole
+ResNet-18-shaped conv stack (batch 1, float32, 224x224 input) on one MI355X.
+
+One step = every layer of the stack through every kernel alternative that can run it
+(direct, im2col GEMM, Winograd F(2x2) and F(4x4)): first the weight transformations of all
+(layer, kind) pairs from raw OIHW weights (grouped launches), then the convolution of every
+pair from its transformed weights.  Inputs and raw weights are synthetic (seeded) and resident
+in HBM before the timed region.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E
+MFMA_F32_PEAK_TFLOPS = 157.3  # dense float32 matrix-core peak
+
+
+def applicable_kinds(nnv, layer):
+    kinds = [nnv.DIRECT]
+    if layer.groups == 1:
+        kinds.append(nnv.IM2COL_GEMM)
+        if layer.winograd_ok:
+            kinds += [nnv.WINO_F2, nnv.WINO_F4]
+    if layer.is_depthwise:
+        kinds.append(nnv.DEPTHWISE)
+    return kinds
+
+
+class Pair:
+    """One (layer, kind): device buffers and the algorithmic traffic/work it stands for."""
+
+    def __init__(self, nnv, torch, layer, kind, w_raw, x, dev):
+        self.layer, self.kind = layer, kind
+        self.desc = nnv.make_desc(layer, nnv.F32)
+        self.w_raw, self.x = w_raw, x
+        self.tx_bytes = nnv.nnv_transformed_bytes(self.desc, kind)
+        # DIRECT executes from the raw layout: its transformed weights alias the raw ones (no work)
+        self.w_tx = w_raw if kind == nnv.DIRECT else torch.empty(self.tx_bytes, dtype=torch.uint8, device=dev)
+        self.ws_bytes = nnv.nnv_workspace_bytes(self.desc, kind)
+        self.y = torch.empty(layer.n * layer.k * layer.p * layer.q, dtype=torch.float32, device=dev)
+        raw = layer.params * 4
+        self.transform_bytes = 0 if kind == nnv.DIRECT else raw + self.tx_bytes
+        if kind in (nnv.WINO_F2, nnv.WINO_F4):
+            m = 2 if kind == nnv.WINO_F2 else 4
+            tiles = layer.n * -(-layer.p // m) * -(-layer.q // m)
+            self.flops = 2.0 * (m + 2) ** 2 * layer.k * layer.c * tiles
+        else:
+            self.flops = 2.0 * layer.macs
+        self.direct_flops = 2.0 * layer.macs
+        self.forward_bytes = 4.0 * (layer.n * layer.c * layer.h * layer.w + layer.n * layer.k * layer.p * layer.q) \
+            + self.tx_bytes
+
+
+def cpu_baseline(layers, nnv, budget_s=12.0):
+    """The oracle as it stands (float64 C direct convolution on all host cores; numpy weight
+    transforms and numpy reference Winograd) timed over whole passes of the same step, every
+    (layer, kind) pair, until about budget_s seconds of CPU work are done."""
+    from nnv_workloads import layer_tensors
+    from oracle import cdirect, layouts as OL, winograd as OW
+    data = [layer_tensors(layer, 220607446 + 2000 + i) for i, layer in enumerate(layers)]
+    passes, t_total, pairs_done = 0, 0.0, 0
+    n_pairs = sum(len(applicable_kinds(nnv, l)) for l in layers)
+    while t_total < budget_s and passes < 3:
+        for layer, (w, x) in zip(layers, data):
+            for kind in applicable_kinds(nnv, layer):
+                t0 = time.perf_counter()
+                if kind == nnv.IM2COL_GEMM:
+                    OL.pack_gemm(w, False)
+                elif kind in (nnv.WINO_F2, nnv.WINO_F4):
+                    var = "F2" if kind == nnv.WINO_F2 else "F4"
+                    OL.pack_wino(OW.transform_weights(w, var), False)
+                if kind in (nnv.WINO_F2, nnv.WINO_F4):
+                    OW.conv2d_winograd(x, w, var, layer.pad)
+                else:
+                    cdirect.conv2d_direct_c(x, w, layer.stride, layer.pad, layer.groups)
+                t_total += time.perf_counter() - t0
+                pairs_done += 1
+        passes += 1
+    return {"value": round(t_total * 1e3 / passes, 1), "unit": "ms", "cores": cdirect.threads(), "kind": "oracle",
+            "sample": f"{passes} whole pass(es) of the same step ({n_pairs} layer-kind pairs of the ResNet-18-shaped "
+                      f"stack: oracle weight transform + float64 forward), {t_total:.1f} s of CPU work; the C direct "
+                      f"convolution uses all cores, the numpy transforms and reference Winograd one"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only; use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2206_07446_amd as nnv
+    from nnv_workloads import stack, layer_tensors
+
+    nnv.load()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    layers = stack("resnet18")
+    pairs = []
+    for i, layer in enumerate(layers):
+        w, x = layer_tensors(layer, 220607446 + 2000 + i)
+        wd, xd = torch.from_numpy(w).to(dev), torch.from_numpy(x).to(dev)
+        for kind in applicable_kinds(nnv, layer):
+            pairs.append(Pair(nnv, torch, layer, kind, wd, xd, dev))
+    ws = torch.empty(max(max(p.ws_bytes for p in pairs), 256), dtype=torch.uint8, device=dev)
+    ws_bytes = ws.numel()
+    descs = [p.desc for p in pairs]
+    kinds = [p.kind for p in pairs]
+    srcs = [p.w_raw for p in pairs]
+    dsts = [p.w_tx for p in pairs]
+
+    def transform_all():     # on torch's current stream
+        nnv.nnv_transform_weights_grouped(descs, kinds, srcs, dsts)
+
+    def forward_all():
+        for p in pairs:
+            nnv.nnv_conv_forward(p.desc, p.kind, p.x, p.w_tx, None, p.y, ws, ws_bytes)
+
+    # The step is recorded once into a HIP graph on a side stream and replayed: batch-1 layers
+    # run for a few microseconds each, so launching ~150 kernels per step from Python would time
+    # the host, not the GPU.  Event records inside the graph split the two phases.
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        transform_all()
+        forward_all()
+    torch.cuda.synchronize()
+    graphs = {}
+    for name, fn in (("transform", transform_all), ("forward", forward_all)):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            fn()
+        graphs[name] = g
+    for _ in range(args.warmup):
+        graphs["transform"].replay()
+        graphs["forward"].replay()
+    torch.cuda.synchronize()
+
+    stream = torch.cuda.current_stream()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        ev[s][0].record(stream)
+        graphs["transform"].replay()
+        ev[s][1].record(stream)
+        graphs["forward"].replay()
+        ev[s][2].record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tx_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    fw_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+
+    tx_bytes = sum(p.transform_bytes for p in pairs)
+    fw_flops = sum(p.flops for p in pairs)
+    fw_direct_flops = sum(p.direct_flops for p in pairs)
+    # The transformation phase is the grouped kernel alone (two launches carry the 46 jobs; DIRECT
+    # aliases the raw weights and launches nothing): the events around it time that kernel.
+    n_tx_launches = 2
+    roofline = {"bound": "hbm", "kernel": "transform_kernel (grouped weight transformation)",
+                "achieved": round(tx_bytes / (tx_ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(tx_bytes / (tx_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4), "traffic": None,
+                "bytes_per_launch": tx_bytes / n_tx_launches, "launches_per_step": n_tx_launches,
+                "avg_launch_us": round(tx_ms * 1e3 / n_tx_launches, 2)}
+
+    # per-kind forward time of the whole stack (separate graph per kind, after the timed region)
+    per_kind = {}
+    names = {nnv.DIRECT: "direct", nnv.IM2COL_GEMM: "im2col_gemm", nnv.WINO_F2: "wino_f2", nnv.WINO_F4: "wino_f4"}
+    for kind, kname in names.items():
+        sel = [p for p in pairs if p.kind == kind]
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            for p in sel:
+                nnv.nnv_conv_forward(p.desc, p.kind, p.x, p.w_tx, None, p.y, ws, ws_bytes)
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(10):
+            g.replay()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 10
+        fl = sum(p.flops for p in sel)
+        per_kind[kname] = {"layers": len(sel), "forward_ms": round(ms, 4),
+                           "TFLOPs_executed": round(fl / (ms * 1e-3) / 1e12, 3),
+                           "TFLOPs_direct_equivalent": round(sum(p.direct_flops for p in sel) / (ms * 1e-3) / 1e12, 3)}
+
+    out = {
+        "metric": "cold transform+conv ms per model stack (weight-transform GB/s; conv TFLOP/s alongside)",
+        "value": round(ms_per_step, 4), "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "resnet18-shaped conv stack, batch 1, 224x224, every layer x every applicable "
+                               "kernel kind (direct, im2col_gemm, wino_f2, wino_f4)",
+                   "layers": len(layers), "layer_kind_pairs": len(pairs), "launch": "HIP graph replay"},
+        "weight_transform_GBps": round(tx_bytes / (tx_ms * 1e-3) / 1e9, 1),
+        "conv_TFLOPs_executed": round(fw_flops / (fw_ms * 1e-3) / 1e12, 3),
+        "conv_TFLOPs_direct_equivalent": round(fw_direct_flops / (fw_ms * 1e-3) / 1e12, 3),
+        "transform_ms": round(tx_ms, 4), "forward_ms": round(fw_ms, 4),
+        "forward_by_kind": per_kind,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(layers, nnv)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

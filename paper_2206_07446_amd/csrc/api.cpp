@@ -39,7 +39,22 @@ int make_geo(const nnv_conv_desc *d, Geo *g) {
     return NNV_OK;
 }
 
+size_t tx_bytes(const Geo &g, int kind);
+size_t ws_bytes(const Geo &g, int kind);
+
+bool kind_rules(const Geo &g, int kind);
+
+// A kind runs a layer if its shape rules hold and every buffer it touches stays below 2 GiB
+// (the kernels address them with 32-bit byte offsets).
 bool supported(const Geo &g, int kind) {
+    if (!kind_rules(g, kind)) return false;
+    const size_t lim = (size_t)1 << 31;
+    const size_t esz = g.dtype == NNV_F16 ? 2 : 4;
+    if ((size_t)g.n * g.c * g.h * g.w * esz >= lim || (size_t)g.n * g.k * g.p * g.q * esz >= lim) return false;
+    return tx_bytes(g, kind) < lim && ws_bytes(g, kind) < lim;
+}
+
+bool kind_rules(const Geo &g, int kind) {
     switch (kind) {
         case NNV_DIRECT: return true;
         case NNV_IM2COL_GEMM: return g.groups == 1 && g.r <= 32 && g.s <= 32 && g.r * g.s <= 64;

@@ -1,0 +1,28 @@
+// Buffer-resource loads: the hardware range check turns an out-of-range offset into a
+// zero result, so masked lanes (zero padding of the convolution, tails of a tile) need no
+// branch: they get an offset beyond the buffer.  All loads of a pipeline stage then sit in
+// straight-line code and can be kept in flight across the matrix instructions.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace nnv {
+
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr uint32_t kOobOffset = 0xFFFFFF00u;   // beyond any buffer (sizes are kept below 2 GiB)
+
+__device__ static inline __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, bytes, 0x00020000);
+}
+
+template <typename F> __device__ static inline F buf_load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff);
+template <> __device__ inline float buf_load<float>(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0));
+}
+template <> __device__ inline half8_t buf_load<half8_t>(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+    return __builtin_bit_cast(half8_t, __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0));
+}
+
+}  // namespace nnv

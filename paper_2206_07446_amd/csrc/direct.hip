@@ -22,10 +22,11 @@ template <typename T> __device__ static inline void st(T *p, size_t i, float v);
 template <> __device__ inline void st<float>(float *p, size_t i, float v) { p[i] = v; }
 template <> __device__ inline void st<__half>(__half *p, size_t i, float v) { p[i] = __float2half_rn(v); }
 
+// Fallback for channel counts the tiled kernel does not cover (few output channels per group).
 template <typename T, int KB>
-__global__ __launch_bounds__(256) void direct_conv_kernel(const T *__restrict__ x, const float *__restrict__ w,
-                                                          const float *__restrict__ bias, T *__restrict__ y,
-                                                          const DirectParams d) {
+__global__ __launch_bounds__(256) void direct_conv_simple_kernel(const T *__restrict__ x, const float *__restrict__ w,
+                                                                 const float *__restrict__ bias, T *__restrict__ y,
+                                                                 const DirectParams d) {
     const int pq = blockIdx.x * 256 + threadIdx.x;
     const int k0 = blockIdx.y * KB;
     const int img = blockIdx.z;
@@ -59,22 +60,173 @@ __global__ __launch_bounds__(256) void direct_conv_kernel(const T *__restrict__ 
     }
 }
 
+// Tiled direct convolution.  A thread owns TP consecutive output pixels x TK output channels;
+// the CS wavefronts of a block share those outputs and split the input channels between them
+// (summed through LDS at the end, fixed order), which is what keeps 1024 SIMDs busy on a
+// batch-1 layer.  The block's filter taps are staged in LDS per chunk of CC channels as
+// [c][r][s][TK] and read back as wave-uniform broadcasts.  FS = filter size when square and
+// known at compile time (1, 3), else 0.
+template <typename T, int TK, int TP, int FS>
+__global__ __launch_bounds__(1024) void direct_conv_tiled_kernel(const T *__restrict__ x, const float *__restrict__ w,
+                                                                 const float *__restrict__ bias, T *__restrict__ y,
+                                                                 const DirectParams d, const int CC) {
+    extern __shared__ __align__(16) float lds[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int CS = blockDim.x >> 6;
+    const int R = FS ? FS : d.R, S = FS ? FS : d.S, RS = R * S;
+    const int PQ = d.P * d.Q, HW = d.H * d.W;
+    const int k0 = blockIdx.y * TK, img = blockIdx.z;
+    const int grp = k0 / d.Kg;
+    int ih0[TP], iw0[TP];
+    bool live[TP];
+#pragma unroll
+    for (int t = 0; t < TP; ++t) {
+        const int pix = (blockIdx.x * 64 + lane) * TP + t;
+        live[t] = pix < PQ;
+        const int p = live[t] ? pix / d.Q : 0, q = live[t] ? pix - p * d.Q : 0;
+        ih0[t] = p * d.sh - d.ph;
+        iw0[t] = q * d.sw - d.pw;
+    }
+    float acc[TP][TK];
+#pragma unroll
+    for (int t = 0; t < TP; ++t)
+#pragma unroll
+        for (int j = 0; j < TK; ++j) acc[t][j] = 0.f;
+    const T *xb = x + ((size_t)img * d.C + (size_t)grp * d.Cg) * HW;
+    const size_t wk = (size_t)d.Cg * RS;
+    for (int c0 = 0; c0 < d.Cg; c0 += CC) {
+        const int ccn = min(CC, d.Cg - c0);
+        __syncthreads();
+        // stage taps: element i -> (idx = i / TK, j = i % TK), lds[idx * TK + j] = w[k0 + j][c0*RS + idx]
+        const float *wb = w + (size_t)k0 * wk + (size_t)c0 * RS;
+        for (int i = threadIdx.x; i < ccn * RS * TK; i += blockDim.x) lds[i] = wb[(size_t)(i % TK) * wk + i / TK];
+        __syncthreads();
+        for (int cc = wave; cc < ccn; cc += CS) {
+            const T *xc = xb + (size_t)(c0 + cc) * HW;
+            const float *wl = lds + cc * RS * TK;
+#pragma unroll 1
+            for (int r = 0; r < R; ++r) {
+#pragma unroll
+                for (int s = 0; s < S; ++s) {
+                    float xv[TP];
+#pragma unroll
+                    for (int t = 0; t < TP; ++t) {
+                        const int ih = ih0[t] + r, iw = iw0[t] + s;
+                        const bool ok = live[t] && ih >= 0 && ih < d.H && iw >= 0 && iw < d.W;
+                        xv[t] = ok ? ld<T>(xc, (size_t)ih * d.W + iw) : 0.f;
+                    }
+                    const float4 *w4 = reinterpret_cast<const float4 *>(wl + (r * S + s) * TK);
+#pragma unroll
+                    for (int j4 = 0; j4 < TK / 4; ++j4) {
+                        const float4 wv = w4[j4];
+#pragma unroll
+                        for (int t = 0; t < TP; ++t) {
+                            acc[t][j4 * 4 + 0] = fmaf(xv[t], wv.x, acc[t][j4 * 4 + 0]);
+                            acc[t][j4 * 4 + 1] = fmaf(xv[t], wv.y, acc[t][j4 * 4 + 1]);
+                            acc[t][j4 * 4 + 2] = fmaf(xv[t], wv.z, acc[t][j4 * 4 + 2]);
+                            acc[t][j4 * 4 + 3] = fmaf(xv[t], wv.w, acc[t][j4 * 4 + 3]);
+                        }
+                    }
+                }
+            }
+        }
+    }
+    // sum the CS partial tiles: red[(wave * TP*TK + o) * 64 + lane]
+    __syncthreads();
+    if (CS > 1) {
+#pragma unroll
+        for (int t = 0; t < TP; ++t)
+#pragma unroll
+            for (int j = 0; j < TK; ++j) lds[((wave * TP + t) * TK + j) * 64 + lane] = acc[t][j];
+        __syncthreads();
+    }
+    for (int o = wave; o < TP * TK; o += CS) {
+        const int t = o / TK, j = o - t * TK;
+        float v = 0.f;
+        if (CS > 1) {
+            for (int ws = 0; ws < CS; ++ws) v += lds[(ws * TP * TK + o) * 64 + lane];
+        } else {
+            // single wavefront: pick acc[t][j] without dynamic register indexing
+#pragma unroll
+            for (int tt = 0; tt < TP; ++tt)
+#pragma unroll
+                for (int jj = 0; jj < TK; ++jj)
+                    if (tt == t && jj == j) v = acc[tt][jj];
+        }
+        const int pix = (blockIdx.x * 64 + lane) * TP + t;
+        if (pix < PQ) st<T>(y, ((size_t)img * d.K + k0 + j) * PQ + pix, v + (bias ? bias[k0 + j] : 0.f));
+    }
+}
+
+struct DirectPlan {
+    int tk, tp, cs, cc;   // tk == 0: simple kernel
+    size_t lds;
+};
+
+static DirectPlan plan_direct(const Geo &g) {
+    DirectPlan pl{0, 1, 1, 0, 0};
+    if (g.kg % 8 != 0) return pl;
+    const int RS = g.r * g.s;
+    const long PQ = (long)g.p * g.q;
+    const int opt[3][2] = {{16, 2}, {16, 1}, {8, 1}};
+    long best_waves = -1;
+    for (int i = 0; i < 3; ++i) {
+        const int tk = opt[i][0], tp = opt[i][1];
+        if (g.kg % tk) continue;
+        int cs_max = 128 / (tk * tp);
+        while (cs_max > 1 && cs_max > g.cg) cs_max /= 2;
+        const long base = ((PQ + 64 * tp - 1) / (64 * tp)) * (g.k / tk) * g.n;
+        int cs = 1;
+        while (cs < cs_max && base * cs < 1024) cs *= 2;
+        const long waves = base * cs;
+        if (waves >= 1024 || waves > best_waves) {
+            pl.tk = tk; pl.tp = tp; pl.cs = cs;
+            best_waves = waves;
+            if (waves >= 1024) break;
+        }
+    }
+    // channels staged per chunk: a multiple of cs, about 16 KB of taps
+    int cc = (4096 / (RS * pl.tk)) / pl.cs * pl.cs;
+    if (cc < pl.cs) cc = pl.cs;
+    if (cc > g.cg) cc = g.cg;
+    pl.cc = cc;
+    const size_t wbytes = (size_t)cc * RS * pl.tk * sizeof(float);
+    const size_t rbytes = pl.cs > 1 ? (size_t)pl.cs * pl.tp * pl.tk * 64 * sizeof(float) : 0;
+    pl.lds = wbytes > rbytes ? wbytes : rbytes;
+    return pl;
+}
+
+template <typename T, int TK, int TP>
+static void launch_tiled(const Geo &g, const DirectPlan &pl, const DirectParams &d, const T *x, const float *w,
+                         const float *bias, T *y, hipStream_t st_) {
+    dim3 grid(ceil_div(g.p * g.q, 64 * TP), g.k / TK, g.n);
+    dim3 block(64 * pl.cs);
+    if (g.r == 3 && g.s == 3)
+        hipLaunchKernelGGL((direct_conv_tiled_kernel<T, TK, TP, 3>), grid, block, pl.lds, st_, x, w, bias, y, d, pl.cc);
+    else if (g.r == 1 && g.s == 1)
+        hipLaunchKernelGGL((direct_conv_tiled_kernel<T, TK, TP, 1>), grid, block, pl.lds, st_, x, w, bias, y, d, pl.cc);
+    else
+        hipLaunchKernelGGL((direct_conv_tiled_kernel<T, TK, TP, 0>), grid, block, pl.lds, st_, x, w, bias, y, d, pl.cc);
+}
+
 template <typename T>
 static hipError_t launch_direct_t(const Geo &g, const T *x, const float *w, const float *bias, T *y, hipStream_t st_) {
     DirectParams d{g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.sh, g.sw, g.ph, g.pw, g.p, g.q, g.cg, g.kg};
-    const int pq_blocks = ceil_div(g.p * g.q, 256);
-    int kb = 1;
-    if (g.kg % 8 == 0) kb = 8;
-    else if (g.kg % 4 == 0) kb = 4;
-    else if (g.kg % 2 == 0) kb = 2;
-    // keep the grid large enough to occupy the chip on small layers
-    while (kb > 1 && (long)pq_blocks * (g.k / kb) * g.n < 1024) kb /= 2;
-    dim3 grid(pq_blocks, g.k / kb, g.n);
-    switch (kb) {
-        case 8: hipLaunchKernelGGL((direct_conv_kernel<T, 8>), grid, dim3(256), 0, st_, x, w, bias, y, d); break;
-        case 4: hipLaunchKernelGGL((direct_conv_kernel<T, 4>), grid, dim3(256), 0, st_, x, w, bias, y, d); break;
-        case 2: hipLaunchKernelGGL((direct_conv_kernel<T, 2>), grid, dim3(256), 0, st_, x, w, bias, y, d); break;
-        default: hipLaunchKernelGGL((direct_conv_kernel<T, 1>), grid, dim3(256), 0, st_, x, w, bias, y, d); break;
+    const DirectPlan pl = plan_direct(g);
+    if (pl.tk == 16 && pl.tp == 2) launch_tiled<T, 16, 2>(g, pl, d, x, w, bias, y, st_);
+    else if (pl.tk == 16) launch_tiled<T, 16, 1>(g, pl, d, x, w, bias, y, st_);
+    else if (pl.tk == 8) launch_tiled<T, 8, 1>(g, pl, d, x, w, bias, y, st_);
+    else {
+        const int pq_blocks = ceil_div(g.p * g.q, 256);
+        int kb = 1;
+        if (g.kg % 4 == 0) kb = 4;
+        else if (g.kg % 2 == 0) kb = 2;
+        dim3 grid(pq_blocks, g.k / kb, g.n);
+        switch (kb) {
+            case 4: hipLaunchKernelGGL((direct_conv_simple_kernel<T, 4>), grid, dim3(256), 0, st_, x, w, bias, y, d); break;
+            case 2: hipLaunchKernelGGL((direct_conv_simple_kernel<T, 2>), grid, dim3(256), 0, st_, x, w, bias, y, d); break;
+            default: hipLaunchKernelGGL((direct_conv_simple_kernel<T, 1>), grid, dim3(256), 0, st_, x, w, bias, y, d); break;
+        }
     }
     return hipGetLastError();
 }

@@ -11,29 +11,34 @@
 // float16: v_mfma_f32_16x16x32_f16.  One k-step = 32 channels at one tap; lane l holds
 //   8 consecutive channels (slot group l/16), so x is first copied to a channel-last
 //   [N][H][W][Cpad32] half buffer in the workspace and both fragments are 16-byte loads.
-// A workgroup is 4 wavefronts side by side along n; a wavefront owns TM x TN 16x16
-// accumulator blocks.  Loads run D k-steps ahead of the MFMAs in registers.  Layers
-// with few output tiles but a long reduction split the k-steps over blockIdx.z into
-// float32 partial sums in the workspace, summed in fixed order by a second kernel.
+// A wavefront owns TM x TN 16x16 accumulator blocks; loads run D k-steps ahead of the
+// MFMAs in registers (no LDS on the operand path: at 32 cycles per float32 MFMA the L1/L2
+// path feeds fragments fast enough, what matters is enough loads in flight).  Batch-1
+// layers have few output tiles but long reductions, so KS wavefronts of a workgroup share
+// one output tile and split its k-steps; their partial sums meet in LDS and are added in
+// fixed order.  A workgroup holds 4/KS tiles side by side along n when KS < 4.
+#include <cstdio>
+#include <cstdlib>
 #include "nnv_internal.h"
+#include "buf.h"
 
 namespace nnv {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef half8_t half8;
 
 struct GemmParams {
     const void *x;       // float32 NCHW, or half channel-last copy
     const void *wp;      // packed panels
     const float *bias;
     void *y;
-    float *partial;      // [splits][K16*16][npix_pad] when splits > 1
     int N, C, H, W, K, R, S, sh, sw, ph, pw, P, Q;
     int npix, npix16;    // N*P*Q and its 16-blocks
     int K16;
     int nsteps;          // k-steps in total
-    int steps_per_split, splits;
+    int ks_shift;        // wavefronts sharing one output tile = 1 << ks_shift
     int cpad;            // channel stride of the half channel-last copy
+    uint32_t x_bytes, w_bytes;   // sizes of the x and wp buffers (range-checked loads)
     int half_out;
 };
 
@@ -47,15 +52,20 @@ template <> struct FragT<true> {
 };
 
 template <bool HALF, int TM, int TN, int D>
-__global__ __launch_bounds__(256) void im2col_gemm_kernel(const GemmParams g) {
+__global__ __launch_bounds__(1024) void im2col_gemm_kernel(const GemmParams g) {
     typedef typename FragT<HALF>::type frag_t;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    extern __shared__ __align__(16) float red[];
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index as a scalar
     const int col = lane & 15, slot = lane >> 4;
+    const int KS = 1 << g.ks_shift;
+    const int ks = wave & (KS - 1), nt = wave >> g.ks_shift;       // k-split index, tile within the workgroup
+    const int tiles_per_wg = (blockDim.x >> 6) >> g.ks_shift;
     const int mb0 = blockIdx.y * TM;
-    const int nb0 = (blockIdx.x * 4 + wave) * TN;
+    const int nb0 = (blockIdx.x * tiles_per_wg + nt) * TN;
     const int HW = g.H * g.W, PQ = g.P * g.Q, RS = g.R * g.S;
 
-    // per-lane pixel state of each of the TN column blocks
+    // per-lane pixel state of each of the TN column blocks: byte offset of the patch origin
+    // in x and the validity masks of its rows and columns (zero padding)
     int xoff[TN];
     uint32_t rmask[TN], smask[TN];
 #pragma unroll
@@ -71,45 +81,44 @@ __global__ __launch_bounds__(256) void im2col_gemm_kernel(const GemmParams g) {
                 if (ih0 + r >= 0 && ih0 + r < g.H) rmask[t] |= 1u << r;
             for (int s = 0; s < g.S; ++s)
                 if (iw0 + s >= 0 && iw0 + s < g.W) smask[t] |= 1u << s;
-            if (HALF) xoff[t] = ((img * g.H + ih0) * g.W + iw0) * g.cpad + slot * 8;
-            else xoff[t] = ((img * g.C + slot) * g.H + ih0) * g.W + iw0;
+            if (HALF) xoff[t] = (((img * g.H + ih0) * g.W + iw0) * g.cpad + slot * 8) * 2;
+            else xoff[t] = (((img * g.C + slot) * g.H + ih0) * g.W + iw0) * 4;
         }
     }
 
-    const int s_begin = blockIdx.z * g.steps_per_split;
-    const int s_end = min(g.nsteps, s_begin + g.steps_per_split);
+    const int per_wave = (g.nsteps + KS - 1) >> g.ks_shift;
+    const int s_begin = min(g.nsteps, ks * per_wave);
+    const int s_end = min(g.nsteps, s_begin + per_wave);
     // (channel block, r, s) of the next step to load
     int cb = s_begin / RS;
     int rs0 = s_begin - cb * RS;
     int lr = rs0 / g.S, ls = rs0 - lr * g.S;
     int lstep = s_begin;
 
-    const frag_t *wfrag = static_cast<const frag_t *>(g.wp);
+    const __amdgpu_buffer_rsrc_t wres = make_rsrc(g.wp, g.w_bytes);
+    const __amdgpu_buffer_rsrc_t xres = make_rsrc(g.x, g.x_bytes);
+    constexpr uint32_t FB = sizeof(frag_t);          // bytes per lane of one fragment
+    const uint32_t a_lane = lane * FB;
     frag_t a[2][D][TM], b[2][D][TN];
 
+    // all loads of a chunk are unconditional buffer loads: masked lanes read beyond the buffer -> 0
     auto load_chunk = [&](int buf) {
 #pragma unroll
         for (int d = 0; d < D; ++d) {
             const bool live = lstep < s_end;
 #pragma unroll
             for (int m = 0; m < TM; ++m) {
-                frag_t v = FragT<HALF>::zero();
-                if (live && mb0 + m < g.K16) v = wfrag[((size_t)(mb0 + m) * g.nsteps + lstep) * 64 + lane];
-                a[buf][d][m] = v;
+                const bool ok = live && mb0 + m < g.K16;
+                a[buf][d][m] = buf_load<frag_t>(wres, ok ? a_lane : kOobOffset,
+                                                ok ? (uint32_t)((mb0 + m) * g.nsteps + lstep) * (64 * FB) : 0u);
             }
+            // uniform part of the B offset for this step
+            const int step_off = HALF ? ((lr * g.W + ls) * g.cpad + cb * 32) * 2 : (cb * 4 * HW + lr * g.W + ls) * 4;
 #pragma unroll
             for (int t = 0; t < TN; ++t) {
-                frag_t v = FragT<HALF>::zero();
                 bool ok = live && ((rmask[t] >> lr) & (smask[t] >> ls) & 1u);
-                if (HALF) {
-                    if (ok) v = *reinterpret_cast<const frag_t *>(static_cast<const _Float16 *>(g.x) + xoff[t] +
-                                                                  (lr * g.W + ls) * g.cpad + cb * 32);
-                } else {
-                    ok = ok && (cb * 4 + slot < g.C);
-                    if (ok) v = *reinterpret_cast<const frag_t *>(static_cast<const float *>(g.x) + xoff[t] +
-                                                                  cb * 4 * HW + lr * g.W + ls);
-                }
-                b[buf][d][t] = v;
+                if (!HALF) ok = ok && (cb * 4 + slot < g.C);
+                b[buf][d][t] = buf_load<frag_t>(xres, ok ? (uint32_t)(xoff[t] + step_off) : kOobOffset, 0u);
             }
             ++lstep;
             if (++ls == g.S) { ls = 0; if (++lr == g.R) { lr = 0; ++cb; } }
@@ -144,22 +153,37 @@ __global__ __launch_bounds__(256) void im2col_gemm_kernel(const GemmParams g) {
         if (base + D < s_end) compute(1);
     }
 
-    // epilogue: lane holds rows 4*slot + j, column col of each block
+    // sum the KS partial tiles through LDS: red[((nt * KS + ks) * NREG + reg) * 64 + lane]
+    constexpr int NREG = TM * TN * 4;
+    if (KS > 1) {
 #pragma unroll
-    for (int t = 0; t < TN; ++t) {
-        const int n = (nb0 + t) * 16 + col;
+        for (int m = 0; m < TM; ++m)
 #pragma unroll
-        for (int m = 0; m < TM; ++m) {
-            if (mb0 + m >= g.K16) continue;
+            for (int t = 0; t < TN; ++t)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    red[((nt * KS + ks) * NREG + (m * TN + t) * 4 + j) * 64 + lane] = acc[m][t][j];
+        __syncthreads();
+    }
+    // epilogue: lane holds rows 4*slot + j, column col of each block; wave ks finishes the
+    // accumulator registers reg = ks, ks + KS, ...
+#pragma unroll
+    for (int m = 0; m < TM; ++m) {
+#pragma unroll
+        for (int t = 0; t < TN; ++t) {
+            const int n = (nb0 + t) * 16 + col;
+            const int img = n / PQ, pq = n - img * PQ;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
+                const int reg = (m * TN + t) * 4 + j;
+                if ((reg & (KS - 1)) != ks) continue;
+                float v = acc[m][t][j];
+                if (KS > 1) {
+                    v = 0.f;
+                    for (int z = 0; z < KS; ++z) v += red[((nt * KS + z) * NREG + reg) * 64 + lane];
+                }
                 const int k = (mb0 + m) * 16 + slot * 4 + j;
-                const float v = acc[m][t][j];
-                if (g.splits > 1) {
-                    if (n < g.npix16 * 16)
-                        g.partial[((size_t)blockIdx.z * g.K16 * 16 + k) * ((size_t)g.npix16 * 16) + n] = v;
-                } else if (k < g.K && n < g.npix) {
-                    const int img = n / PQ, pq = n - img * PQ;
+                if (k < g.K && n < g.npix) {
                     const size_t o = ((size_t)img * g.K + k) * PQ + pq;
                     const float r = v + (g.bias ? g.bias[k] : 0.f);
                     if (g.half_out) static_cast<__half *>(g.y)[o] = __float2half_rn(r);
@@ -168,23 +192,6 @@ __global__ __launch_bounds__(256) void im2col_gemm_kernel(const GemmParams g) {
             }
         }
     }
-}
-
-// y[k, n] = bias[k] + sum_z partial[z][k][n], fixed summation order.
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmParams g) {
-    const int n = blockIdx.x * 256 + threadIdx.x;
-    const int k = blockIdx.y;
-    if (n >= g.npix) return;
-    const size_t npad = (size_t)g.npix16 * 16;
-    const size_t zstride = (size_t)g.K16 * 16 * npad;
-    const float *p = g.partial + (size_t)k * npad + n;
-    float acc = g.bias ? g.bias[k] : 0.f;
-    for (int z = 0; z < g.splits; ++z) acc += p[z * zstride];
-    const int PQ = g.P * g.Q;
-    const int img = n / PQ, pq = n - img * PQ;
-    const size_t o = ((size_t)img * g.K + k) * PQ + pq;
-    if (g.half_out) static_cast<__half *>(g.y)[o] = __float2half_rn(acc);
-    else static_cast<float *>(g.y)[o] = acc;
 }
 
 // half NCHW -> half [N][H][W][cpad] (channels last, zero padded to a multiple of 32).
@@ -205,8 +212,8 @@ __global__ __launch_bounds__(256) void to_channels_last_kernel(const __half *__r
 // ---------------------------------------------------------------- host side
 
 struct GemmPlan {
-    int tm, tn, splits, steps_per_split;
-    size_t xt_bytes, partial_bytes;
+    int tm, tn, ks_shift, d;
+    size_t xt_bytes;
 };
 
 static GemmPlan plan_im2col(const Geo &g) {
@@ -215,40 +222,47 @@ static GemmPlan plan_im2col(const Geo &g) {
     const int K16 = ceil_div(g.k, 16);
     const int npix16 = ceil_div(g.n * g.p * g.q, 16);
     const int nsteps = (half ? ceil_div(g.c, 32) : ceil_div(g.c, 4)) * g.r * g.s;
-    auto waves = [&](int tm, int tn) { return (long)ceil_div(K16, tm) * ceil_div(npix16, tn); };
-    const long target = 1024;   // one wavefront per SIMD
-    if (waves(2, 2) >= target) { pl.tm = 2; pl.tn = 2; }
-    else if (waves(2, 1) >= target) { pl.tm = 2; pl.tn = 1; }
+    auto tiles = [&](int tm, int tn) { return (long)ceil_div(K16, tm) * ceil_div(npix16, tn); };
+    // Batch-1 layers are latency-bound: what pays is many wavefronts with a short reduction each.
+    // Split the k-steps over KS wavefronts until about 1.5 wavefronts per SIMD exist, keeping at
+    // least 12 k-steps per wavefront; take the 32x16 tile if that still gives enough wavefronts,
+    // the 32x32 tile only for layers with thousands of tiles.
+    auto split_for = [&](long t) {
+        int shift = 0;
+        while (shift < 4 && (t << shift) < 1536 && (nsteps >> (shift + 1)) >= 12) ++shift;
+        return shift;
+    };
+    if (tiles(2, 2) >= 4096) { pl.tm = 2; pl.tn = 2; }
+    else if ((tiles(2, 1) << split_for(tiles(2, 1))) >= 1536) { pl.tm = 2; pl.tn = 1; }
     else { pl.tm = 1; pl.tn = 1; }
-    long wv = waves(pl.tm, pl.tn);
-    int splits = 1;
-    if (wv < target / 2) {
-        splits = (int)((target + wv - 1) / wv);
-        const int max_splits = nsteps / 16 > 0 ? nsteps / 16 : 1;   // at least 16 k-steps each
-        if (splits > max_splits) splits = max_splits;
-        if (splits > 64) splits = 64;
+    pl.ks_shift = split_for(tiles(pl.tm, pl.tn));
+    pl.d = 4;
+    if (const char *e = getenv("NNV_GEMM_PLAN")) {   // tm,tn,ks_shift,d
+        int a, b, c, d;
+        if (sscanf(e, "%d,%d,%d,%d", &a, &b, &c, &d) == 4) { pl.tm = a; pl.tn = b; pl.ks_shift = c; pl.d = d; }
     }
-    pl.steps_per_split = ceil_div(nsteps, splits);
-    pl.splits = ceil_div(nsteps, pl.steps_per_split);
     pl.xt_bytes = half ? align_up((size_t)g.n * g.h * g.w * ceil_div(g.c, 32) * 32 * sizeof(__half), 256) : 0;
-    pl.partial_bytes = pl.splits > 1 ? (size_t)pl.splits * K16 * 16 * npix16 * 16 * sizeof(float) : 0;
     return pl;
 }
 
-size_t im2col_workspace_bytes(const Geo &g) {
-    const GemmPlan pl = plan_im2col(g);
-    return pl.xt_bytes + pl.partial_bytes;
+size_t im2col_workspace_bytes(const Geo &g) { return plan_im2col(g).xt_bytes; }
+
+template <bool HALF, int TM, int TN>
+static void launch_gemm_d(const GemmPlan &pl, const GemmParams &gp, dim3 grid, dim3 block, size_t lds, hipStream_t st) {
+    if (HALF) {
+        hipLaunchKernelGGL((im2col_gemm_kernel<HALF, TM, TN, 2>), grid, block, lds, st, gp);
+        return;
+    }
+    if (pl.d == 4) hipLaunchKernelGGL((im2col_gemm_kernel<HALF, TM, TN, 4>), grid, block, lds, st, gp);
+    else if (pl.d == 16 && TM * TN == 1) hipLaunchKernelGGL((im2col_gemm_kernel<HALF, TM, TN, 16>), grid, block, lds, st, gp);
+    else hipLaunchKernelGGL((im2col_gemm_kernel<HALF, TM, TN, 8>), grid, block, lds, st, gp);
 }
 
 template <bool HALF>
-static void launch_gemm_variant(const GemmPlan &pl, const GemmParams &gp, dim3 grid, hipStream_t st) {
-    constexpr int D = HALF ? 2 : 4;
-    if (pl.tm == 2 && pl.tn == 2)
-        hipLaunchKernelGGL((im2col_gemm_kernel<HALF, 2, 2, D>), grid, dim3(256), 0, st, gp);
-    else if (pl.tm == 2 && pl.tn == 1)
-        hipLaunchKernelGGL((im2col_gemm_kernel<HALF, 2, 1, D>), grid, dim3(256), 0, st, gp);
-    else
-        hipLaunchKernelGGL((im2col_gemm_kernel<HALF, 1, 1, D>), grid, dim3(256), 0, st, gp);
+static void launch_gemm_variant(const GemmPlan &pl, const GemmParams &gp, dim3 grid, dim3 block, size_t lds, hipStream_t st) {
+    if (pl.tm == 2 && pl.tn == 2) launch_gemm_d<HALF, 2, 2>(pl, gp, grid, block, lds, st);
+    else if (pl.tm == 2 && pl.tn == 1) launch_gemm_d<HALF, 2, 1>(pl, gp, grid, block, lds, st);
+    else launch_gemm_d<HALF, 1, 1>(pl, gp, grid, block, lds, st);
 }
 
 hipError_t launch_im2col(const Geo &g, const void *x, const void *w, const float *bias, void *y, void *ws, hipStream_t st) {
@@ -263,26 +277,24 @@ hipError_t launch_im2col(const Geo &g, const void *x, const void *w, const float
     gp.K16 = ceil_div(g.k, 16);
     gp.cpad = ceil_div(g.c, 32) * 32;
     gp.nsteps = (half ? ceil_div(g.c, 32) : ceil_div(g.c, 4)) * g.r * g.s;
-    gp.steps_per_split = pl.steps_per_split;
-    gp.splits = pl.splits;
+    gp.ks_shift = pl.ks_shift;
     gp.half_out = half;
-    char *wsp = static_cast<char *>(ws);
+    gp.x_bytes = half ? (uint32_t)((size_t)g.n * g.h * g.w * gp.cpad * 2) : (uint32_t)((size_t)g.n * g.c * g.h * g.w * 4);
+    gp.w_bytes = (uint32_t)((size_t)gp.K16 * gp.nsteps * 64 * (half ? 16 : 4));
     if (half) {
-        __half *xt = reinterpret_cast<__half *>(wsp);
+        __half *xt = static_cast<__half *>(ws);
         dim3 grid(ceil_div(g.h * g.w, 256), gp.cpad / 8, g.n);
         hipLaunchKernelGGL(to_channels_last_kernel, grid, dim3(256), 0, st, static_cast<const __half *>(x), xt, g.c,
                            g.h * g.w, gp.cpad);
         gp.x = xt;
-        wsp += pl.xt_bytes;
     }
-    gp.partial = pl.splits > 1 ? reinterpret_cast<float *>(wsp) : nullptr;
-    dim3 grid(ceil_div(gp.npix16, 4 * pl.tn), ceil_div(gp.K16, pl.tm), pl.splits);
-    if (half) launch_gemm_variant<true>(pl, gp, grid, st);
-    else launch_gemm_variant<false>(pl, gp, grid, st);
-    if (pl.splits > 1) {
-        dim3 rgrid(ceil_div(gp.npix, 256), g.k, 1);
-        hipLaunchKernelGGL(splitk_reduce_kernel, rgrid, dim3(256), 0, st, gp);
-    }
+    const int KS = 1 << pl.ks_shift;
+    const int waves = KS < 4 ? 4 : KS;
+    const int tiles_per_wg = waves / KS;
+    dim3 grid(ceil_div(ceil_div(gp.npix16, pl.tn), tiles_per_wg), ceil_div(gp.K16, pl.tm), 1);
+    const size_t lds = KS > 1 ? (size_t)waves * pl.tm * pl.tn * 4 * 64 * sizeof(float) : 0;
+    if (half) launch_gemm_variant<true>(pl, gp, grid, dim3(64 * waves), lds, st);
+    else launch_gemm_variant<false>(pl, gp, grid, dim3(64 * waves), lds, st);
     return hipGetLastError();
 }
 

@@ -3,18 +3,23 @@
 //   1. input transform   V[xi][tile block][c][16 tiles] = (B^T d B)[xi]   (vector ALU)
 //   2. batched tile GEMM M[xi] = U[xi] (K x C) * V[xi] (C x T), alpha^2 independent
 //      products on the matrix cores; U and V are stored as ready-made 16-row operand
-//      fragments, so both are read with one coalesced load per fragment and no LDS
+//      fragments, so both are read with one coalesced load per fragment and no LDS;
+//      deep layers with few tiles split the channels over the wavefronts of a workgroup
+//      and add the partial sums through LDS in fixed order
 //   3. output transform  Y = A^T M A, clipped to P x Q, plus bias        (vector ALU)
 // V and M live in the caller's workspace.  float16 storage keeps U, V and y in half
 // precision; the transforms and the accumulation are float32.
+#include <cstdio>
+#include <cstdlib>
 #include <type_traits>
 #include "nnv_internal.h"
+#include "buf.h"
 #include "wino_consts.h"
 
 namespace nnv {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef half8_t half8;
 
 struct WinoParams {
     const void *x;
@@ -26,7 +31,9 @@ struct WinoParams {
     int N, C, H, W, K, ph, pw, P, Q;
     int th, tw, T, T16;     // tiles per image (rows, cols), total tiles, 16-blocks of tiles
     int K16, cpad, csteps;  // cpad: channels padded to 4 (float32) / 32 (float16); csteps = cpad / that
-    int wn_shift;           // wavefronts of a workgroup along the tile dimension = 1 << wn_shift
+    int ks_shift;           // wavefronts sharing one output tile (splitting the channels) = 1 << ks_shift
+    int ntb;                // tile-block groups per frequency: ceil(T16 / TN)
+    uint32_t u_bytes, v_bytes;   // sizes of U and V (range-checked loads)
 };
 
 // out[i][j] = sum_k L[i][k] * in[k][j] with a compile-time matrix L (zeros skipped).
@@ -117,34 +124,44 @@ template <> struct WFrag<true> {
 };
 
 template <bool HALF, int TM, int TN, int D>
-__global__ __launch_bounds__(256) void wino_gemm_kernel(const WinoParams w) {
+__global__ __launch_bounds__(1024) void wino_gemm_kernel(const WinoParams w) {
     typedef typename WFrag<HALF>::type frag_t;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wn = wave & ((1 << w.wn_shift) - 1), wm = wave >> w.wn_shift;
-    const int wm_count = 4 >> w.wn_shift;
-    const int kb0 = (blockIdx.y * wm_count + wm) * TM;
-    const int tb0 = ((blockIdx.x << w.wn_shift) + wn) * TN;
-    const int xi = blockIdx.z;
-    const frag_t *Uf = static_cast<const frag_t *>(w.U) + (size_t)xi * w.K16 * w.csteps * 64 + lane;
-    const frag_t *Vf = static_cast<const frag_t *>(w.V) + (size_t)xi * w.T16 * w.csteps * 64 + lane;
+    extern __shared__ __align__(16) float red[];
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index as a scalar
+    const int KS = 1 << w.ks_shift;
+    const int ks = wave & (KS - 1), nt = wave >> w.ks_shift;
+    const int tiles_per_wg = (blockDim.x >> 6) >> w.ks_shift;
+    const int tile = blockIdx.x * tiles_per_wg + nt;      // flattened (k-block group, tile-block group)
+    const int kbt = tile / w.ntb, tbt = tile - kbt * w.ntb;
+    const int kb0 = kbt * TM, tb0 = tbt * TN;              // kb0 >= K16 for surplus wavefronts: they load nothing
+    const int xi = blockIdx.y;
+    const __amdgpu_buffer_rsrc_t ures = make_rsrc(w.U, w.u_bytes);
+    const __amdgpu_buffer_rsrc_t vres = make_rsrc(w.V, w.v_bytes);
+    constexpr uint32_t FB = sizeof(frag_t);
+    const uint32_t lane_off = lane * FB;
+    const uint32_t u_base = (uint32_t)xi * w.K16 * w.csteps, v_base = (uint32_t)xi * w.T16 * w.csteps;   // in fragments
+    const int per_wave = (w.csteps + KS - 1) >> w.ks_shift;
+    const int s_begin = min(w.csteps, ks * per_wave);
+    const int s_end = min(w.csteps, s_begin + per_wave);
 
     frag_t a[2][D][TM], b[2][D][TN];
-    int lstep = 0;
+    int lstep = s_begin;
+    // unconditional buffer loads: fragments outside the problem read beyond the buffer -> 0
     auto load_chunk = [&](int buf) {
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            const bool live = lstep < w.csteps;
+            const bool live = lstep < s_end && kb0 < w.K16;
 #pragma unroll
             for (int m = 0; m < TM; ++m) {
-                frag_t v = WFrag<HALF>::zero();
-                if (live && kb0 + m < w.K16) v = Uf[((size_t)(kb0 + m) * w.csteps + lstep) * 64];
-                a[buf][d][m] = v;
+                const bool ok = live && kb0 + m < w.K16;
+                a[buf][d][m] = buf_load<frag_t>(ures, ok ? lane_off : kOobOffset,
+                                                ok ? (u_base + (uint32_t)(kb0 + m) * w.csteps + lstep) * (64 * FB) : 0u);
             }
 #pragma unroll
             for (int t = 0; t < TN; ++t) {
-                frag_t v = WFrag<HALF>::zero();
-                if (live && tb0 + t < w.T16) v = Vf[((size_t)(tb0 + t) * w.csteps + lstep) * 64];
-                b[buf][d][t] = v;
+                const bool ok = live && tb0 + t < w.T16;
+                b[buf][d][t] = buf_load<frag_t>(vres, ok ? lane_off : kOobOffset,
+                                                ok ? (v_base + (uint32_t)(tb0 + t) * w.csteps + lstep) * (64 * FB) : 0u);
             }
             ++lstep;
         }
@@ -168,23 +185,42 @@ __global__ __launch_bounds__(256) void wino_gemm_kernel(const WinoParams w) {
                 }
     };
     load_chunk(0);
-    for (int base = 0; base < w.csteps; base += 2 * D) {
+    for (int base = s_begin; base < s_end; base += 2 * D) {
         load_chunk(1);
         compute(0);
         load_chunk(0);
-        if (base + D < w.csteps) compute(1);
+        if (base + D < s_end) compute(1);
+    }
+    constexpr int NREG = TM * TN * 4;
+    if (KS > 1) {
+#pragma unroll
+        for (int m = 0; m < TM; ++m)
+#pragma unroll
+            for (int t = 0; t < TN; ++t)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    red[((nt * KS + ks) * NREG + (m * TN + t) * 4 + j) * 64 + lane] = acc[m][t][j];
+        __syncthreads();
     }
     // M[xi][kb][tb][16 k][16 t]: lane holds rows 4*(lane/16)+j, column lane%16
     const int col = lane & 15, slot = lane >> 4;
 #pragma unroll
     for (int m = 0; m < TM; ++m) {
-        if (kb0 + m >= w.K16) continue;
 #pragma unroll
         for (int t = 0; t < TN; ++t) {
-            if (tb0 + t >= w.T16) continue;
+            const bool inb = kb0 + m < w.K16 && tb0 + t < w.T16;
             float *o = w.M + (((size_t)xi * w.K16 + kb0 + m) * w.T16 + tb0 + t) * 256 + slot * 64 + col;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) o[j * 16] = acc[m][t][j];
+            for (int j = 0; j < 4; ++j) {
+                const int reg = (m * TN + t) * 4 + j;
+                if ((reg & (KS - 1)) != ks) continue;
+                float v = acc[m][t][j];
+                if (KS > 1) {
+                    v = 0.f;
+                    for (int z = 0; z < KS; ++z) v += red[((nt * KS + z) * NREG + reg) * 64 + lane];
+                }
+                if (inb) o[j * 16] = v;
+            }
         }
     }
 }
@@ -266,20 +302,44 @@ static hipError_t launch_wino_t(const Geo &g, const WinoPlan &p, WinoParams &w, 
         hipLaunchKernelGGL((wino_input_kernel<SET, HALF>), grid, dim3(256), 0, st, w);
     }
     {
-        // wavefront tile and workgroup shape: fill >= 1024 wavefronts when the layer allows it
+        // wavefront tile, channel split and workgroup shape: cover >= 1024 wavefronts if possible
         const long aa = (long)p.alpha * p.alpha;
-        int tm = 2, tn = 2;
-        if (aa * ceil_div(p.K16, 2) * ceil_div(p.T16, 2) < 1024) { tn = 1; }
-        if (aa * ceil_div(p.K16, tm) * ceil_div(p.T16, tn) < 1024) { tm = 1; }
-        int wn_shift = 2;
-        while (wn_shift > 0 && (1 << wn_shift) * tn > p.T16) --wn_shift;   // do not spread waves over missing tiles
-        w.wn_shift = wn_shift;
-        const int wm_count = 4 >> wn_shift;
-        dim3 grid(ceil_div(p.T16, tn << wn_shift), ceil_div(p.K16, tm * wm_count), (unsigned)aa);
-        constexpr int D = HALF ? 2 : 4;
-        if (tm == 2 && tn == 2) hipLaunchKernelGGL((wino_gemm_kernel<HALF, 2, 2, D>), grid, dim3(256), 0, st, w);
-        else if (tm == 2 && tn == 1) hipLaunchKernelGGL((wino_gemm_kernel<HALF, 2, 1, D>), grid, dim3(256), 0, st, w);
-        else hipLaunchKernelGGL((wino_gemm_kernel<HALF, 1, 1, D>), grid, dim3(256), 0, st, w);
+        // latency-bound at batch 1: aim at ~4 wavefronts per SIMD, >= 8 channel steps each
+        int tm = 1, tn = 1;
+        if (aa * ceil_div(p.K16, 2) * ceil_div(p.T16, 2) >= 4096) { tm = 2; tn = 2; }
+        else if (aa * ceil_div(p.K16, 2) * p.T16 >= 4096) { tm = 2; }
+        int shift = 0;
+        const long tiles = (long)ceil_div(p.K16, tm) * ceil_div(p.T16, tn);
+        while (shift < 4 && ((aa * tiles) << shift) < 4096 && (p.csteps >> (shift + 1)) >= 8) ++shift;
+        int d = HALF ? 2 : 8;
+        if (const char *e = getenv("NNV_WINO_PLAN")) {   // tm,tn,ks_shift,d
+            int a_, b_, c_, d_;
+            if (sscanf(e, "%d,%d,%d,%d", &a_, &b_, &c_, &d_) == 4) { tm = a_; tn = b_; shift = c_; if (!HALF) d = d_; }
+        }
+        w.ks_shift = shift;
+        w.ntb = ceil_div(p.T16, tn);
+        w.u_bytes = (uint32_t)((size_t)aa * p.K16 * p.csteps * 64 * (HALF ? 16 : 4));
+        w.v_bytes = (uint32_t)((size_t)aa * p.T16 * p.csteps * 64 * (HALF ? 16 : 4));
+        const int KS = 1 << shift;
+        const int waves = KS < 4 ? 4 : KS;
+        const int tiles_per_wg = waves / KS;
+        const long ntiles = (long)ceil_div(p.K16, tm) * w.ntb;
+        dim3 grid((unsigned)ceil_div((int)ntiles, tiles_per_wg), (unsigned)aa, 1);
+        dim3 block(64 * waves);
+        const size_t lds = KS > 1 ? (size_t)waves * tm * tn * 4 * 64 * sizeof(float) : 0;
+        if constexpr (HALF) {
+            if (tm == 2 && tn == 2) hipLaunchKernelGGL((wino_gemm_kernel<HALF, 2, 2, 2>), grid, block, lds, st, w);
+            else if (tm == 2 && tn == 1) hipLaunchKernelGGL((wino_gemm_kernel<HALF, 2, 1, 2>), grid, block, lds, st, w);
+            else hipLaunchKernelGGL((wino_gemm_kernel<HALF, 1, 1, 2>), grid, block, lds, st, w);
+        } else if (d == 4) {
+            if (tm == 2 && tn == 2) hipLaunchKernelGGL((wino_gemm_kernel<false, 2, 2, 4>), grid, block, lds, st, w);
+            else if (tm == 2 && tn == 1) hipLaunchKernelGGL((wino_gemm_kernel<false, 2, 1, 4>), grid, block, lds, st, w);
+            else hipLaunchKernelGGL((wino_gemm_kernel<false, 1, 1, 4>), grid, block, lds, st, w);
+        } else {
+            if (tm == 2 && tn == 2) hipLaunchKernelGGL((wino_gemm_kernel<false, 2, 2, 8>), grid, block, lds, st, w);
+            else if (tm == 2 && tn == 1) hipLaunchKernelGGL((wino_gemm_kernel<false, 2, 1, 8>), grid, block, lds, st, w);
+            else hipLaunchKernelGGL((wino_gemm_kernel<false, 1, 1, 8>), grid, block, lds, st, w);
+        }
     }
     {
         dim3 grid(p.T16, p.K16, 1);
