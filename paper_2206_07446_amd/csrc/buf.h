@@ -11,7 +11,8 @@ namespace nnv {
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
-constexpr uint32_t kOobOffset = 0xFFFFFF00u;   // beyond any buffer (sizes are kept below 2 GiB)
+constexpr uint32_t kOobOffset = 0x80000000u;   // beyond any buffer (sizes are kept below 2 GiB); adding an
+                                               // immediate offset to it cannot wrap around
 
 __device__ static inline __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, bytes, 0x00020000);

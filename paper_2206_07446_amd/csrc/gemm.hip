@@ -2,7 +2,7 @@
 // Table 2 / Fig. 5, including 1x1 pointwise layers):
 //     y[k, n] = sum_kk Wp[k, kk] * col[kk, n],  n = (img, p, q),  kk = (c, r, s)
 // The col matrix is never materialised: every wavefront gathers its B fragments
-// straight from x with per-lane validity masks for the zero padding.
+// straight from x.
 //
 // float32: v_mfma_f32_16x16x4_f32.  One k-step = 4 channels at one filter tap (r,s);
 //   lane l holds row/column l%16 and channel slot l/16, so the packed weight fragment
@@ -11,12 +11,16 @@
 // float16: v_mfma_f32_16x16x32_f16.  One k-step = 32 channels at one tap; lane l holds
 //   8 consecutive channels (slot group l/16), so x is first copied to a channel-last
 //   [N][H][W][Cpad32] half buffer in the workspace and both fragments are 16-byte loads.
-// A wavefront owns TM x TN 16x16 accumulator blocks; loads run D k-steps ahead of the
-// MFMAs in registers (no LDS on the operand path: at 32 cycles per float32 MFMA the L1/L2
-// path feeds fragments fast enough, what matters is enough loads in flight).  Batch-1
-// layers have few output tiles but long reductions, so KS wavefronts of a workgroup share
-// one output tile and split its k-steps; their partial sums meet in LDS and are added in
-// fixed order.  A workgroup holds 4/KS tiles side by side along n when KS < 4.
+//
+// Batch-1 layers put one or two wavefronts on a SIMD, and a lone wavefront issues one
+// instruction every four cycles: the k-loop must be almost nothing but loads and MFMAs.
+// So all addressing is hoisted: operands come through buffer loads whose hardware range
+// check returns 0 for an out-of-range offset; each lane keeps one byte offset per filter
+// tap, already set beyond the buffer where the tap falls into the zero padding; the
+// channel advance is a scalar offset; fragments of consecutive steps use immediate
+// offsets.  A chunk (one channel block x all taps, or 8 channel blocks for 1x1) is loaded
+// one chunk ahead of the MFMAs (register ping-pong).  KS wavefronts of a workgroup share one
+// output tile and split the channel blocks; partial sums meet in LDS, fixed order.
 #include <cstdio>
 #include <cstdlib>
 #include "nnv_internal.h"
@@ -33,95 +37,147 @@ struct GemmParams {
     const float *bias;
     void *y;
     int N, C, H, W, K, R, S, sh, sw, ph, pw, P, Q;
-    int npix, npix16;    // N*P*Q and its 16-blocks
+    int npix;            // N*P*Q
     int K16;
-    int nsteps;          // k-steps in total
+    int cblocks;         // channel blocks (of 4 float32 / 32 half channels)
+    int c_rem;           // float32: C % 4 (channels of the last, partial block; 0 = full)
     int ks_shift;        // wavefronts sharing one output tile = 1 << ks_shift
     int cpad;            // channel stride of the half channel-last copy
     uint32_t x_bytes, w_bytes;   // sizes of the x and wp buffers (range-checked loads)
+    uint32_t cb_stride;  // bytes between channel blocks in x
     int half_out;
 };
 
-template <bool HALF> struct FragT {
-    typedef float type;
-    __device__ static inline float zero() { return 0.f; }
-};
-template <> struct FragT<true> {
-    typedef half8 type;
-    __device__ static inline half8 zero() { return half8{0, 0, 0, 0, 0, 0, 0, 0}; }
+template <bool HALF> struct FragT { typedef float type; };
+template <> struct FragT<true> { typedef half8 type; };
+
+// MODE: how the k-steps of a wavefront are grouped into chunks (a chunk is what is loaded ahead)
+//   1  1x1 filter: a unit is a channel block, a chunk is 8 units (2 in half precision)
+//   3  3x3 filter, float32: a unit = chunk = one channel block, 9 taps, tap offsets loop-invariant
+//      3x3 filter, half: row mode (fragments are four registers wide, nine steps do not fit)
+//   5,7  filters with S = 5 / 7 (float32): row mode, a unit = chunk = one filter row of a channel block
+//   0  anything else: a unit = chunk = one k-step
+template <bool HALF, int MODE> struct ModeT {
+    static constexpr bool ROW = MODE == 5 || MODE == 7 || (MODE == 3 && HALF);
+    static constexpr bool WHOLE3 = MODE == 3 && !HALF;
+    static constexpr int UNITS = MODE == 1 ? (HALF ? 2 : 8) : 1;                           // units per chunk
+    static constexpr int STEPS = MODE == 0 ? 1 : MODE == 1 ? UNITS : WHOLE3 ? 9 : MODE;    // k-steps per chunk
+    static constexpr int NVOFF = (MODE == 0 || MODE == 1) ? 1 : STEPS;                     // tap offsets kept per lane
 };
 
-template <bool HALF, int TM, int TN, int D>
+template <bool HALF, int TM, int TN, int MODE, int NBUF>
 __global__ __launch_bounds__(1024) void im2col_gemm_kernel(const GemmParams g) {
     typedef typename FragT<HALF>::type frag_t;
+    typedef ModeT<HALF, MODE> MT;
+    constexpr int STEPS = MT::STEPS, UNITS = MT::UNITS, NVOFF = MT::NVOFF;
+    constexpr bool ROW = MT::ROW, WHOLE3 = MT::WHOLE3;
+    constexpr uint32_t FB = sizeof(frag_t);            // bytes per lane of one fragment
+    constexpr uint32_t FRAG = 64 * FB;                 // bytes of one fragment
     extern __shared__ __align__(16) float red[];
-    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index as a scalar
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar
     const int col = lane & 15, slot = lane >> 4;
     const int KS = 1 << g.ks_shift;
-    const int ks = wave & (KS - 1), nt = wave >> g.ks_shift;       // k-split index, tile within the workgroup
+    const int ks = wave & (KS - 1), nt = wave >> g.ks_shift;             // k-split index, tile within the workgroup
     const int tiles_per_wg = (blockDim.x >> 6) >> g.ks_shift;
     const int mb0 = blockIdx.y * TM;
     const int nb0 = (blockIdx.x * tiles_per_wg + nt) * TN;
-    const int HW = g.H * g.W, PQ = g.P * g.Q, RS = g.R * g.S;
+    const int PQ = g.P * g.Q, RS = g.R * g.S;
 
-    // per-lane pixel state of each of the TN column blocks: byte offset of the patch origin
-    // in x and the validity masks of its rows and columns (zero padding)
-    int xoff[TN];
-    uint32_t rmask[TN], smask[TN];
+    // ---- per-lane pixel state: origin of the patch in x (bytes, may be negative) and tap offsets
+    int xbase[TN], ih0[TN], iw0[TN], pix_img[TN], pix_pq[TN];
+    bool pvalid[TN];
 #pragma unroll
     for (int t = 0; t < TN; ++t) {
         const int n = (nb0 + t) * 16 + col;
-        rmask[t] = smask[t] = 0;
-        xoff[t] = 0;
-        if (n < g.npix) {
-            const int img = n / PQ, pq = n - img * PQ;
-            const int p = pq / g.Q, q = pq - p * g.Q;
-            const int ih0 = p * g.sh - g.ph, iw0 = q * g.sw - g.pw;
-            for (int r = 0; r < g.R; ++r)
-                if (ih0 + r >= 0 && ih0 + r < g.H) rmask[t] |= 1u << r;
-            for (int s = 0; s < g.S; ++s)
-                if (iw0 + s >= 0 && iw0 + s < g.W) smask[t] |= 1u << s;
-            if (HALF) xoff[t] = (((img * g.H + ih0) * g.W + iw0) * g.cpad + slot * 8) * 2;
-            else xoff[t] = (((img * g.C + slot) * g.H + ih0) * g.W + iw0) * 4;
-        }
+        pvalid[t] = n < g.npix;
+        const int nn = pvalid[t] ? n : 0;
+        const int img = g.N == 1 ? 0 : nn / PQ;
+        const int pq = nn - img * PQ;
+        const int p = pq / g.Q, q = pq - p * g.Q;
+        pix_img[t] = img; pix_pq[t] = pq;
+        ih0[t] = p * g.sh - g.ph;
+        iw0[t] = q * g.sw - g.pw;
+        if (HALF) xbase[t] = (((img * g.H + ih0[t]) * g.W + iw0[t]) * g.cpad + slot * 8) * 2;
+        else xbase[t] = (((img * g.C + slot) * g.H + ih0[t]) * g.W + iw0[t]) * 4;
     }
+    const int tap_w = HALF ? g.cpad * 2 : 4;             // bytes per step along s
+    const int tap_h = g.W * tap_w;                       // bytes per step along r
+    auto tap_off = [&](int t, int r, int s) -> uint32_t {
+        const bool ok = pvalid[t] && (unsigned)(ih0[t] + r) < (unsigned)g.H && (unsigned)(iw0[t] + s) < (unsigned)g.W;
+        return ok ? (uint32_t)(xbase[t] + r * tap_h + s * tap_w) : kOobOffset;
+    };
+    // byte offset per tap of the current chunk; loop-invariant for MODE 1 and 3
+    uint32_t voff[TN][NVOFF];
+    if (MODE == 1) {
+#pragma unroll
+        for (int t = 0; t < TN; ++t) voff[t][0] = tap_off(t, 0, 0);
+    } else if (WHOLE3) {
+#pragma unroll
+        for (int t = 0; t < TN; ++t)
+#pragma unroll
+            for (int rs = 0; rs < NVOFF; ++rs) voff[t][rs] = tap_off(t, rs / 3, rs % 3);
+    }
+    // ---- this wavefront's range of units
+    const int nunits = MODE == 0 ? g.cblocks * RS : ROW ? g.cblocks * g.R : g.cblocks;
+    const int per_wave = (nunits + KS - 1) >> g.ks_shift;
+    const int u_begin = min(nunits, ks * per_wave);
+    const int u_end = min(nunits, u_begin + per_wave);
+    const int steps_per_unit = MODE == 0 ? 1 : ROW ? MODE : RS;   // MODE 1: RS == 1
+    const uint32_t nsteps_total = (uint32_t)g.cblocks * RS;
 
-    const int per_wave = (g.nsteps + KS - 1) >> g.ks_shift;
-    const int s_begin = min(g.nsteps, ks * per_wave);
-    const int s_end = min(g.nsteps, s_begin + per_wave);
-    // (channel block, r, s) of the next step to load
-    int cb = s_begin / RS;
-    int rs0 = s_begin - cb * RS;
-    int lr = rs0 / g.S, ls = rs0 - lr * g.S;
-    int lstep = s_begin;
-
-    const __amdgpu_buffer_rsrc_t wres = make_rsrc(g.wp, g.w_bytes);
     const __amdgpu_buffer_rsrc_t xres = make_rsrc(g.x, g.x_bytes);
-    constexpr uint32_t FB = sizeof(frag_t);          // bytes per lane of one fragment
     const uint32_t a_lane = lane * FB;
-    frag_t a[2][D][TM], b[2][D][TN];
+    frag_t a[NBUF][STEPS][TM], b[NBUF][STEPS][TN];
 
-    // all loads of a chunk are unconditional buffer loads: masked lanes read beyond the buffer -> 0
-    auto load_chunk = [&](int buf) {
+    // Load the chunk starting at unit u (clamped into the range: a chunk past the end re-reads
+    // valid data that is never used).  Straight-line code, no branches between the loads.
+    // The weight fragments of a chunk are consecutive in memory: they are read through a
+    // resource window that starts at the chunk (immediate offsets per step) and ends at the end
+    // of the buffer, so a read past this wavefront's range or past the last panel returns
+    // data that is not used, or zero, but never faults.
+    auto load_chunk = [&](int buf, int u) {
+        u = max(min(u, u_end - 1), 0);
 #pragma unroll
-        for (int d = 0; d < D; ++d) {
-            const bool live = lstep < s_end;
+        for (int m = 0; m < TM; ++m) {
+            uint32_t off = ((uint32_t)(mb0 + m) * nsteps_total + (uint32_t)u * steps_per_unit) * FRAG;
+            off = min(off, g.w_bytes);        // panels beyond K: empty window, all zeros
+            const __amdgpu_buffer_rsrc_t win = make_rsrc(static_cast<const char *>(g.wp) + off, g.w_bytes - off);
 #pragma unroll
-            for (int m = 0; m < TM; ++m) {
-                const bool ok = live && mb0 + m < g.K16;
-                a[buf][d][m] = buf_load<frag_t>(wres, ok ? a_lane : kOobOffset,
-                                                ok ? (uint32_t)((mb0 + m) * g.nsteps + lstep) * (64 * FB) : 0u);
+            for (int j = 0; j < STEPS; ++j) a[buf][j][m] = buf_load<frag_t>(win, a_lane + j * FRAG, 0u);
+        }
+        if (MODE == 1) {
+#pragma unroll
+            for (int j = 0; j < STEPS; ++j) {
+                const int cb = min(u + j, u_end - 1);
+#pragma unroll
+                for (int t = 0; t < TN; ++t) b[buf][j][t] = buf_load<frag_t>(xres, voff[t][0], (uint32_t)cb * g.cb_stride);
             }
-            // uniform part of the B offset for this step
-            const int step_off = HALF ? ((lr * g.W + ls) * g.cpad + cb * 32) * 2 : (cb * 4 * HW + lr * g.W + ls) * 4;
+        } else {
+            int cb, r0 = 0, s0 = 0;
+            if (WHOLE3) cb = u;
+            else if (MODE == 0) { cb = u / RS; const int rs = u - cb * RS; r0 = rs / g.S; s0 = rs - r0 * g.S; }
+            else { cb = u / g.R; r0 = u - cb * g.R; }
+            if (ROW) {
 #pragma unroll
-            for (int t = 0; t < TN; ++t) {
-                bool ok = live && ((rmask[t] >> lr) & (smask[t] >> ls) & 1u);
-                if (!HALF) ok = ok && (cb * 4 + slot < g.C);
-                b[buf][d][t] = buf_load<frag_t>(xres, ok ? (uint32_t)(xoff[t] + step_off) : kOobOffset, 0u);
+                for (int t = 0; t < TN; ++t)
+#pragma unroll
+                    for (int s = 0; s < NVOFF; ++s) voff[t][s] = tap_off(t, r0, s);
+            } else if (MODE == 0) {
+#pragma unroll
+                for (int t = 0; t < TN; ++t) voff[t][0] = tap_off(t, r0, s0);
             }
-            ++lstep;
-            if (++ls == g.S) { ls = 0; if (++lr == g.R) { lr = 0; ++cb; } }
+            const bool partial = !HALF && g.c_rem != 0 && cb == g.cblocks - 1;   // uniform
+            const uint32_t b_soff = (uint32_t)cb * g.cb_stride;
+#pragma unroll
+            for (int j = 0; j < STEPS; ++j) {
+#pragma unroll
+                for (int t = 0; t < TN; ++t) {
+                    uint32_t vo = voff[t][j < NVOFF ? j : 0];
+                    if (partial) vo = slot < g.c_rem ? vo : kOobOffset;
+                    b[buf][j][t] = buf_load<frag_t>(xres, vo, b_soff);
+                }
+            }
         }
     };
 
@@ -131,29 +187,43 @@ __global__ __launch_bounds__(1024) void im2col_gemm_kernel(const GemmParams g) {
 #pragma unroll
         for (int t = 0; t < TN; ++t) acc[m][t] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    auto compute = [&](int buf) {
+    auto mfma_step = [&](int buf, int j) {
 #pragma unroll
-        for (int d = 0; d < D; ++d)
+        for (int m = 0; m < TM; ++m)
 #pragma unroll
-            for (int m = 0; m < TM; ++m)
+            for (int t = 0; t < TN; ++t) {
+                if constexpr (HALF)
+                    acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[buf][j][m], b[buf][j][t], acc[m][t], 0, 0, 0);
+                else
+                    acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[buf][j][m], b[buf][j][t], acc[m][t], 0, 0, 0);
+            }
+    };
+    // MFMAs of the chunk starting at unit u: all of it, or (MODE 1 tail) only its valid units
+    auto compute = [&](int buf, int u) {
+        if (UNITS == 1 || u + UNITS <= u_end) {
 #pragma unroll
-                for (int t = 0; t < TN; ++t) {
-                    if constexpr (HALF)
-                        acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[buf][d][m], b[buf][d][t], acc[m][t], 0, 0, 0);
-                    else
-                        acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[buf][d][m], b[buf][d][t], acc[m][t], 0, 0, 0);
-                }
+            for (int j = 0; j < STEPS; ++j) mfma_step(buf, j);
+        } else {
+#pragma unroll
+            for (int j = 0; j < STEPS; ++j)
+                if (u + j < u_end) mfma_step(buf, j);
+        }
     };
 
-    load_chunk(0);
-    for (int base = s_begin; base < s_end; base += 2 * D) {
-        load_chunk(1);
-        compute(0);
-        load_chunk(0);
-        if (base + D < s_end) compute(1);
+    // ring of NBUF register sets: loads run NBUF-1 chunks ahead of the MFMAs
+    if (u_begin < u_end) {
+#pragma unroll
+        for (int i = 0; i < NBUF - 1; ++i) load_chunk(i, u_begin + i * UNITS);
+        for (int u = u_begin; u < u_end; u += NBUF * UNITS) {
+#pragma unroll
+            for (int i = 0; i < NBUF; ++i) {
+                load_chunk((i + NBUF - 1) % NBUF, u + (i + NBUF - 1) * UNITS);
+                if (i == 0 || u + i * UNITS < u_end) compute(i, u + i * UNITS);
+            }
+        }
     }
 
-    // sum the KS partial tiles through LDS: red[((nt * KS + ks) * NREG + reg) * 64 + lane]
+    // ---- sum the KS partial tiles through LDS: red[((nt * KS + ks) * NREG + reg) * 64 + lane]
     constexpr int NREG = TM * TN * 4;
     if (KS > 1) {
 #pragma unroll
@@ -165,14 +235,12 @@ __global__ __launch_bounds__(1024) void im2col_gemm_kernel(const GemmParams g) {
                     red[((nt * KS + ks) * NREG + (m * TN + t) * 4 + j) * 64 + lane] = acc[m][t][j];
         __syncthreads();
     }
-    // epilogue: lane holds rows 4*slot + j, column col of each block; wave ks finishes the
+    // epilogue: lane holds rows 4*slot + j, column col of each block; wavefront ks finishes the
     // accumulator registers reg = ks, ks + KS, ...
 #pragma unroll
     for (int m = 0; m < TM; ++m) {
 #pragma unroll
         for (int t = 0; t < TN; ++t) {
-            const int n = (nb0 + t) * 16 + col;
-            const int img = n / PQ, pq = n - img * PQ;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int reg = (m * TN + t) * 4 + j;
@@ -183,8 +251,8 @@ __global__ __launch_bounds__(1024) void im2col_gemm_kernel(const GemmParams g) {
                     for (int z = 0; z < KS; ++z) v += red[((nt * KS + z) * NREG + reg) * 64 + lane];
                 }
                 const int k = (mb0 + m) * 16 + slot * 4 + j;
-                if (k < g.K && n < g.npix) {
-                    const size_t o = ((size_t)img * g.K + k) * PQ + pq;
+                if (k < g.K && pvalid[t]) {
+                    const size_t o = ((size_t)pix_img[t] * g.K + k) * PQ + pix_pq[t];
                     const float r = v + (g.bias ? g.bias[k] : 0.f);
                     if (g.half_out) static_cast<__half *>(g.y)[o] = __float2half_rn(r);
                     else static_cast<float *>(g.y)[o] = r;
@@ -212,7 +280,7 @@ __global__ __launch_bounds__(256) void to_channels_last_kernel(const __half *__r
 // ---------------------------------------------------------------- host side
 
 struct GemmPlan {
-    int tm, tn, ks_shift, d;
+    int tm, tn, ks_shift, mode, nbuf;
     size_t xt_bytes;
 };
 
@@ -221,48 +289,69 @@ static GemmPlan plan_im2col(const Geo &g) {
     const bool half = g.dtype == NNV_F16;
     const int K16 = ceil_div(g.k, 16);
     const int npix16 = ceil_div(g.n * g.p * g.q, 16);
-    const int nsteps = (half ? ceil_div(g.c, 32) : ceil_div(g.c, 4)) * g.r * g.s;
+    const int cblocks = half ? ceil_div(g.c, 32) : ceil_div(g.c, 4);
+    const bool partial = !half && (g.c % 4) != 0;
+    if (g.r == 1 && g.s == 1 && !partial) pl.mode = 1;
+    else if (g.r == 3 && g.s == 3) pl.mode = 3;
+    else if (g.s == 7 && !half) pl.mode = 7;
+    else if (g.s == 5 && !half) pl.mode = 5;
+    else pl.mode = 0;
+    const bool row = pl.mode == 5 || pl.mode == 7 || (pl.mode == 3 && half);
+    const int nunits = pl.mode == 0 ? cblocks * g.r * g.s : row ? cblocks * g.r : cblocks;
+    const int unit_steps = pl.mode == 0 ? 1 : row ? pl.mode : g.r * g.s;
     auto tiles = [&](int tm, int tn) { return (long)ceil_div(K16, tm) * ceil_div(npix16, tn); };
-    // Batch-1 layers are latency-bound: what pays is many wavefronts with a short reduction each.
-    // Split the k-steps over KS wavefronts until about 1.5 wavefronts per SIMD exist, keeping at
-    // least 12 k-steps per wavefront; take the 32x16 tile if that still gives enough wavefronts,
-    // the 32x32 tile only for layers with thousands of tiles.
-    auto split_for = [&](long t) {
+    // Batch-1 layers are latency-bound.  What pays (measured on ResNet-18-shaped layers): the
+    // 32x32 tile only with thousands of tiles; the 32x16 tile while it still leaves >= 160 tiles,
+    // its units split over KS wavefronts up to ~2048 wavefronts; else the 16x16 tile with a
+    // moderate split (>= 768 wavefronts) and a deeper register ring, because its few workgroups
+    // stream the weights from HBM and each CU keeps only so many misses in flight.
+    auto split_for = [&](long t, long target) {
         int shift = 0;
-        while (shift < 4 && (t << shift) < 1536 && (nsteps >> (shift + 1)) >= 12) ++shift;
+        while (shift < 4 && (t << shift) < target && (nunits >> (shift + 1)) >= 1 &&
+               (((long)nunits * unit_steps) >> (shift + 1)) >= 9)
+            ++shift;
         return shift;
     };
-    if (tiles(2, 2) >= 4096) { pl.tm = 2; pl.tn = 2; }
-    else if ((tiles(2, 1) << split_for(tiles(2, 1))) >= 1536) { pl.tm = 2; pl.tn = 1; }
-    else { pl.tm = 1; pl.tn = 1; }
-    pl.ks_shift = split_for(tiles(pl.tm, pl.tn));
-    pl.d = 4;
-    if (const char *e = getenv("NNV_GEMM_PLAN")) {   // tm,tn,ks_shift,d
+    if (tiles(2, 2) >= 4096) { pl.tm = 2; pl.tn = 2; pl.ks_shift = 0; }
+    else if (tiles(2, 1) >= 160) { pl.tm = 2; pl.tn = 1; pl.ks_shift = split_for(tiles(2, 1), 2048); }
+    else { pl.tm = 1; pl.tn = 1; pl.ks_shift = split_for(tiles(1, 1), 768); }
+    const int units_per_wave = ceil_div(nunits, 1 << pl.ks_shift);
+    pl.nbuf = 2;
+    if (pl.tm == 1 && units_per_wave >= 8) pl.nbuf = 4;
+    else if (pl.tm == 2 && pl.tn == 1 && units_per_wave >= 8) pl.nbuf = 3;
+    if (const char *e = getenv("NNV_GEMM_PLAN")) {   // tm,tn,ks_shift,nbuf
         int a, b, c, d;
-        if (sscanf(e, "%d,%d,%d,%d", &a, &b, &c, &d) == 4) { pl.tm = a; pl.tn = b; pl.ks_shift = c; pl.d = d; }
+        if (sscanf(e, "%d,%d,%d,%d", &a, &b, &c, &d) == 4) { pl.tm = a; pl.tn = b; pl.ks_shift = c; pl.nbuf = d; }
     }
+    if (half || pl.tm * pl.tn == 4) pl.nbuf = 2;
     pl.xt_bytes = half ? align_up((size_t)g.n * g.h * g.w * ceil_div(g.c, 32) * 32 * sizeof(__half), 256) : 0;
     return pl;
 }
 
 size_t im2col_workspace_bytes(const Geo &g) { return plan_im2col(g).xt_bytes; }
 
-template <bool HALF, int TM, int TN>
-static void launch_gemm_d(const GemmPlan &pl, const GemmParams &gp, dim3 grid, dim3 block, size_t lds, hipStream_t st) {
-    if (HALF) {
-        hipLaunchKernelGGL((im2col_gemm_kernel<HALF, TM, TN, 2>), grid, block, lds, st, gp);
-        return;
+template <bool HALF, int TM, int TN, int NBUF>
+static void launch_gemm_mode(int mode, const GemmParams &gp, dim3 grid, dim3 block, size_t lds, hipStream_t st) {
+    switch (mode) {
+        case 1: hipLaunchKernelGGL((im2col_gemm_kernel<HALF, TM, TN, 1, NBUF>), grid, block, lds, st, gp); break;
+        case 3: hipLaunchKernelGGL((im2col_gemm_kernel<HALF, TM, TN, 3, NBUF>), grid, block, lds, st, gp); break;
+        case 5: if constexpr (!HALF) { hipLaunchKernelGGL((im2col_gemm_kernel<HALF, TM, TN, 5, NBUF>), grid, block, lds, st, gp); } break;
+        case 7: if constexpr (!HALF) { hipLaunchKernelGGL((im2col_gemm_kernel<HALF, TM, TN, 7, NBUF>), grid, block, lds, st, gp); } break;
+        default: hipLaunchKernelGGL((im2col_gemm_kernel<HALF, TM, TN, 0, NBUF>), grid, block, lds, st, gp); break;
     }
-    if (pl.d == 4) hipLaunchKernelGGL((im2col_gemm_kernel<HALF, TM, TN, 4>), grid, block, lds, st, gp);
-    else if (pl.d == 16 && TM * TN == 1) hipLaunchKernelGGL((im2col_gemm_kernel<HALF, TM, TN, 16>), grid, block, lds, st, gp);
-    else hipLaunchKernelGGL((im2col_gemm_kernel<HALF, TM, TN, 8>), grid, block, lds, st, gp);
 }
 
 template <bool HALF>
 static void launch_gemm_variant(const GemmPlan &pl, const GemmParams &gp, dim3 grid, dim3 block, size_t lds, hipStream_t st) {
-    if (pl.tm == 2 && pl.tn == 2) launch_gemm_d<HALF, 2, 2>(pl, gp, grid, block, lds, st);
-    else if (pl.tm == 2 && pl.tn == 1) launch_gemm_d<HALF, 2, 1>(pl, gp, grid, block, lds, st);
-    else launch_gemm_d<HALF, 1, 1>(pl, gp, grid, block, lds, st);
+    if (pl.tm == 2 && pl.tn == 2) launch_gemm_mode<HALF, 2, 2, 2>(pl.mode, gp, grid, block, lds, st);
+    else if (pl.tm == 2 && pl.tn == 1) {
+        if (!HALF && pl.nbuf >= 3) launch_gemm_mode<HALF, 2, 1, 3>(pl.mode, gp, grid, block, lds, st);
+        else launch_gemm_mode<HALF, 2, 1, 2>(pl.mode, gp, grid, block, lds, st);
+    } else {
+        if (!HALF && pl.nbuf >= 4) launch_gemm_mode<HALF, 1, 1, 4>(pl.mode, gp, grid, block, lds, st);
+        else if (!HALF && pl.nbuf == 3) launch_gemm_mode<HALF, 1, 1, 3>(pl.mode, gp, grid, block, lds, st);
+        else launch_gemm_mode<HALF, 1, 1, 2>(pl.mode, gp, grid, block, lds, st);
+    }
 }
 
 hipError_t launch_im2col(const Geo &g, const void *x, const void *w, const float *bias, void *y, void *ws, hipStream_t st) {
@@ -273,14 +362,15 @@ hipError_t launch_im2col(const Geo &g, const void *x, const void *w, const float
     gp.N = g.n; gp.C = g.c; gp.H = g.h; gp.W = g.w; gp.K = g.k; gp.R = g.r; gp.S = g.s;
     gp.sh = g.sh; gp.sw = g.sw; gp.ph = g.ph; gp.pw = g.pw; gp.P = g.p; gp.Q = g.q;
     gp.npix = g.n * g.p * g.q;
-    gp.npix16 = ceil_div(gp.npix, 16);
     gp.K16 = ceil_div(g.k, 16);
     gp.cpad = ceil_div(g.c, 32) * 32;
-    gp.nsteps = (half ? ceil_div(g.c, 32) : ceil_div(g.c, 4)) * g.r * g.s;
+    gp.cblocks = half ? ceil_div(g.c, 32) : ceil_div(g.c, 4);
+    gp.c_rem = half ? 0 : g.c % 4;
     gp.ks_shift = pl.ks_shift;
     gp.half_out = half;
     gp.x_bytes = half ? (uint32_t)((size_t)g.n * g.h * g.w * gp.cpad * 2) : (uint32_t)((size_t)g.n * g.c * g.h * g.w * 4);
-    gp.w_bytes = (uint32_t)((size_t)gp.K16 * gp.nsteps * 64 * (half ? 16 : 4));
+    gp.w_bytes = (uint32_t)((size_t)gp.K16 * gp.cblocks * g.r * g.s * 64 * (half ? 16 : 4));
+    gp.cb_stride = half ? 64u : (uint32_t)(4 * g.h * g.w * 4);
     if (half) {
         __half *xt = static_cast<__half *>(ws);
         dim3 grid(ceil_div(g.h * g.w, 256), gp.cpad / 8, g.n);
@@ -291,7 +381,8 @@ hipError_t launch_im2col(const Geo &g, const void *x, const void *w, const float
     const int KS = 1 << pl.ks_shift;
     const int waves = KS < 4 ? 4 : KS;
     const int tiles_per_wg = waves / KS;
-    dim3 grid(ceil_div(ceil_div(gp.npix16, pl.tn), tiles_per_wg), ceil_div(gp.K16, pl.tm), 1);
+    const int npix16 = ceil_div(gp.npix, 16);
+    dim3 grid(ceil_div(ceil_div(npix16, pl.tn), tiles_per_wg), ceil_div(gp.K16, pl.tm), 1);
     const size_t lds = KS > 1 ? (size_t)waves * pl.tm * pl.tn * 4 * 64 * sizeof(float) : 0;
     if (half) launch_gemm_variant<true>(pl, gp, grid, dim3(64 * waves), lds, st);
     else launch_gemm_variant<false>(pl, gp, grid, dim3(64 * waves), lds, st);

@@ -123,47 +123,54 @@ template <> struct WFrag<true> {
     __device__ static inline half8 zero() { return half8{0, 0, 0, 0, 0, 0, 0, 0}; }
 };
 
+// The k-loop is kept to loads and MFMAs: a lone wavefront on a SIMD issues one instruction
+// every four cycles, so every select or address computation in the loop costs as much as a
+// quarter of a float32 MFMA.  Offsets are a per-lane constant (or an out-of-range constant
+// for fragments outside the problem) plus a scalar that advances by one fragment per step.
 template <bool HALF, int TM, int TN, int D>
 __global__ __launch_bounds__(1024) void wino_gemm_kernel(const WinoParams w) {
     typedef typename WFrag<HALF>::type frag_t;
     extern __shared__ __align__(16) float red[];
-    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index as a scalar
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar
     const int KS = 1 << w.ks_shift;
     const int ks = wave & (KS - 1), nt = wave >> w.ks_shift;
     const int tiles_per_wg = (blockDim.x >> 6) >> w.ks_shift;
     const int tile = blockIdx.x * tiles_per_wg + nt;      // flattened (k-block group, tile-block group)
     const int kbt = tile / w.ntb, tbt = tile - kbt * w.ntb;
-    const int kb0 = kbt * TM, tb0 = tbt * TN;              // kb0 >= K16 for surplus wavefronts: they load nothing
+    const int kb0 = kbt * TM, tb0 = tbt * TN;              // kb0 >= K16 for surplus wavefronts
     const int xi = blockIdx.y;
     const __amdgpu_buffer_rsrc_t ures = make_rsrc(w.U, w.u_bytes);
     const __amdgpu_buffer_rsrc_t vres = make_rsrc(w.V, w.v_bytes);
-    constexpr uint32_t FB = sizeof(frag_t);
-    const uint32_t lane_off = lane * FB;
-    const uint32_t u_base = (uint32_t)xi * w.K16 * w.csteps, v_base = (uint32_t)xi * w.T16 * w.csteps;   // in fragments
+    constexpr uint32_t FB = sizeof(frag_t), FRAG = 64 * FB;
+    uint32_t a_voff[TM], b_voff[TN];
+    uint32_t a_base[TM], b_base[TN];     // fragment index of step 0 (scalars)
+#pragma unroll
+    for (int m = 0; m < TM; ++m) {
+        const bool ok = kb0 + m < w.K16;
+        a_voff[m] = ok ? lane * FB : kOobOffset;
+        a_base[m] = ok ? ((uint32_t)xi * w.K16 + kb0 + m) * w.csteps : 0u;
+    }
+#pragma unroll
+    for (int t = 0; t < TN; ++t) {
+        const bool ok = kb0 < w.K16 && tb0 + t < w.T16;
+        b_voff[t] = ok ? lane * FB : kOobOffset;
+        b_base[t] = ok ? ((uint32_t)xi * w.T16 + tb0 + t) * w.csteps : 0u;
+    }
     const int per_wave = (w.csteps + KS - 1) >> w.ks_shift;
     const int s_begin = min(w.csteps, ks * per_wave);
     const int s_end = min(w.csteps, s_begin + per_wave);
 
     frag_t a[2][D][TM], b[2][D][TN];
-    int lstep = s_begin;
-    // unconditional buffer loads: fragments outside the problem read beyond the buffer -> 0
-    auto load_chunk = [&](int buf) {
+    // chunk of D steps starting at step s0; steps past the end re-read the last valid step (unused)
+    auto load_chunk = [&](int buf, int s0) {
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            const bool live = lstep < s_end && kb0 < w.K16;
+            const int st = max(min(s0 + d, s_end - 1), 0);
 #pragma unroll
-            for (int m = 0; m < TM; ++m) {
-                const bool ok = live && kb0 + m < w.K16;
-                a[buf][d][m] = buf_load<frag_t>(ures, ok ? lane_off : kOobOffset,
-                                                ok ? (u_base + (uint32_t)(kb0 + m) * w.csteps + lstep) * (64 * FB) : 0u);
-            }
+            for (int m = 0; m < TM; ++m) a[buf][d][m] = buf_load<frag_t>(ures, a_voff[m], (a_base[m] + st) * FRAG);
 #pragma unroll
-            for (int t = 0; t < TN; ++t) {
-                const bool ok = live && tb0 + t < w.T16;
-                b[buf][d][t] = buf_load<frag_t>(vres, ok ? lane_off : kOobOffset,
-                                                ok ? (v_base + (uint32_t)(tb0 + t) * w.csteps + lstep) * (64 * FB) : 0u);
-            }
-            ++lstep;
+            for (int t = 0; t < TN; ++t) b[buf][d][t] = buf_load<frag_t>(vres, b_voff[t], (b_base[t] + st) * FRAG);
         }
     };
     floatx4 acc[TM][TN];
@@ -171,25 +178,35 @@ __global__ __launch_bounds__(1024) void wino_gemm_kernel(const WinoParams w) {
     for (int m = 0; m < TM; ++m)
 #pragma unroll
         for (int t = 0; t < TN; ++t) acc[m][t] = floatx4{0.f, 0.f, 0.f, 0.f};
-    auto compute = [&](int buf) {
+    auto mfma_step = [&](int buf, int d) {
 #pragma unroll
-        for (int d = 0; d < D; ++d)
+        for (int m = 0; m < TM; ++m)
 #pragma unroll
-            for (int m = 0; m < TM; ++m)
-#pragma unroll
-                for (int t = 0; t < TN; ++t) {
-                    if constexpr (HALF)
-                        acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[buf][d][m], b[buf][d][t], acc[m][t], 0, 0, 0);
-                    else
-                        acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[buf][d][m], b[buf][d][t], acc[m][t], 0, 0, 0);
-                }
+            for (int t = 0; t < TN; ++t) {
+                if constexpr (HALF)
+                    acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[buf][d][m], b[buf][d][t], acc[m][t], 0, 0, 0);
+                else
+                    acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[buf][d][m], b[buf][d][t], acc[m][t], 0, 0, 0);
+            }
     };
-    load_chunk(0);
-    for (int base = s_begin; base < s_end; base += 2 * D) {
-        load_chunk(1);
-        compute(0);
-        load_chunk(0);
-        if (base + D < s_end) compute(1);
+    auto compute = [&](int buf, int s0) {
+        if (s0 + D <= s_end) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) mfma_step(buf, d);
+        } else {
+#pragma unroll
+            for (int d = 0; d < D; ++d)
+                if (s0 + d < s_end) mfma_step(buf, d);
+        }
+    };
+    if (s_begin < s_end) {
+        load_chunk(0, s_begin);
+        for (int s0 = s_begin; s0 < s_end; s0 += 2 * D) {
+            load_chunk(1, s0 + D);
+            compute(0, s0);
+            load_chunk(0, s0 + 2 * D);
+            if (s0 + D < s_end) compute(1, s0 + D);
+        }
     }
     constexpr int NREG = TM * TN * 4;
     if (KS > 1) {
