@@ -7,7 +7,9 @@
 // scalar loads, and x is read along W (coalesced).  depthwise: HBM-bound, one thread per
 // output pixel of one channel plane, taps of the channel from the packed
 // [C/32][9][32] layout.
+#include <cstdlib>
 #include "nnv_internal.h"
+#include "buf.h"
 
 namespace nnv {
 
@@ -21,6 +23,15 @@ template <> __device__ inline float ld<__half>(const __half *p, size_t i) { retu
 template <typename T> __device__ static inline void st(T *p, size_t i, float v);
 template <> __device__ inline void st<float>(float *p, size_t i, float v) { p[i] = v; }
 template <> __device__ inline void st<__half>(__half *p, size_t i, float v) { p[i] = __float2half_rn(v); }
+
+template <typename T> __device__ static inline float buf_ld_x(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff);
+template <> __device__ inline float buf_ld_x<float>(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0));
+}
+template <> __device__ inline float buf_ld_x<__half>(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+    const unsigned short u = __builtin_amdgcn_raw_buffer_load_b16(r, voff, soff, 0);
+    return (float)__builtin_bit_cast(_Float16, u);
+}
 
 // Fallback for channel counts the tiled kernel does not cover (few output channels per group).
 template <typename T, int KB>
@@ -158,6 +169,91 @@ __global__ __launch_bounds__(1024) void direct_conv_tiled_kernel(const T *__rest
     }
 }
 
+// Direct convolution, lean form for groups == 1 and 3x3 / 1x1 filters: a lane owns one output
+// pixel and TK output channels; the CS wavefronts of a block split the input channels.  The
+// filter taps of a wavefront are uniform, so they are read straight from the raw OIHW tensor
+// into scalar registers (scalar cache; nine consecutive floats per output and input channel)
+// and feed the FMAs as scalar operands: no LDS staging, no barrier in the channel loop.  x comes
+// through buffer loads with one hoisted byte offset per tap (out of range in the zero padding).
+template <typename T, int TK, int FS>
+__global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__restrict__ x, const float *__restrict__ w,
+                                                                 const float *__restrict__ bias, T *__restrict__ y,
+                                                                 const DirectParams d) {
+    extern __shared__ __align__(16) float lds[];
+    constexpr int ESZ = sizeof(T);
+    constexpr int RS = FS * FS;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int CS = blockDim.x >> 6;
+    const int PQ = d.P * d.Q, HW = d.H * d.W;
+    const int k0 = blockIdx.y * TK, img = blockIdx.z;
+    const int pix = blockIdx.x * 64 + lane;
+    const bool live = pix < PQ;
+    const int p = live ? pix / d.Q : 0, q = live ? pix - p * d.Q : 0;
+    uint32_t voff[RS];
+#pragma unroll
+    for (int r = 0; r < FS; ++r)
+#pragma unroll
+        for (int s2 = 0; s2 < FS; ++s2) {
+            const int ih = p * d.sh - d.ph + r, iw = q * d.sw - d.pw + s2;
+            const bool ok = live && (unsigned)ih < (unsigned)d.H && (unsigned)iw < (unsigned)d.W;
+            voff[r * FS + s2] = ok ? (uint32_t)((ih * d.W + iw) * ESZ) : kOobOffset;
+        }
+    const __amdgpu_buffer_rsrc_t xres = make_rsrc(x + (size_t)img * d.C * HW, (uint32_t)((size_t)d.C * HW * ESZ));
+    const uint32_t plane = (uint32_t)(HW * ESZ);
+    const size_t wk = (size_t)d.C * RS;
+    const float *wrow = w + (size_t)k0 * wk;
+    float acc[TK];
+#pragma unroll
+    for (int j = 0; j < TK; ++j) acc[j] = 0.f;
+    // two channels per iteration: the loads of both are issued before the FMAs of the first
+    // (large filters: one channel at a time, their taps alone fill the registers)
+    int c = wave;
+    for (; FS <= 3 && c + CS < d.C; c += 2 * CS) {
+        float xa[RS], xb[RS];
+#pragma unroll
+        for (int i = 0; i < RS; ++i) xa[i] = buf_ld_x<T>(xres, voff[i], (uint32_t)c * plane);
+#pragma unroll
+        for (int i = 0; i < RS; ++i) xb[i] = buf_ld_x<T>(xres, voff[i], (uint32_t)(c + CS) * plane);
+        const float *wa = wrow + (size_t)c * RS, *wb = wrow + (size_t)(c + CS) * RS;
+#pragma unroll
+        for (int j = 0; j < TK; ++j)
+#pragma unroll
+            for (int i = 0; i < RS; ++i) acc[j] = fmaf(xa[i], wa[j * wk + i], acc[j]);
+#pragma unroll
+        for (int j = 0; j < TK; ++j)
+#pragma unroll
+            for (int i = 0; i < RS; ++i) acc[j] = fmaf(xb[i], wb[j * wk + i], acc[j]);
+    }
+    for (; c < d.C; c += CS) {
+        float xa[RS];
+#pragma unroll
+        for (int i = 0; i < RS; ++i) xa[i] = buf_ld_x<T>(xres, voff[i], (uint32_t)c * plane);
+        const float *wa = wrow + (size_t)c * RS;
+#pragma unroll
+        for (int j = 0; j < TK; ++j)
+#pragma unroll
+            for (int i = 0; i < RS; ++i) acc[j] = fmaf(xa[i], wa[j * wk + i], acc[j]);
+    }
+    // sum the CS partial results: red[(wave * TK + j) * 64 + lane], fixed order
+    if (CS > 1) {
+#pragma unroll
+        for (int j = 0; j < TK; ++j) lds[(wave * TK + j) * 64 + lane] = acc[j];
+        __syncthreads();
+    }
+    for (int j = wave; j < TK; j += CS) {
+        float v = 0.f;
+        if (CS > 1) {
+            for (int ws = 0; ws < CS; ++ws) v += lds[(ws * TK + j) * 64 + lane];
+        } else {
+#pragma unroll
+            for (int jj = 0; jj < TK; ++jj)
+                if (jj == j) v = acc[jj];
+        }
+        if (live) st<T>(y, ((size_t)img * d.K + k0 + j) * PQ + pix, v + (bias ? bias[k0 + j] : 0.f));
+    }
+}
+
 struct DirectPlan {
     int tk, tp, cs, cc;   // tk == 0: simple kernel
     size_t lds;
@@ -209,9 +305,44 @@ static void launch_tiled(const Geo &g, const DirectPlan &pl, const DirectParams 
         hipLaunchKernelGGL((direct_conv_tiled_kernel<T, TK, TP, 0>), grid, block, pl.lds, st_, x, w, bias, y, d, pl.cc);
 }
 
+// lean scalar-weight kernel: groups 1, square 1x1 / 3x3 / 5x5 / 7x7 filter, K a multiple of 4
+static bool slane_supported(const Geo &g) {
+    return g.groups == 1 && g.r == g.s && (g.r == 3 || g.r == 1 || g.r == 5 || g.r == 7) && g.k % 4 == 0;
+}
+
+template <typename T>
+static void launch_slane(const Geo &g, const DirectParams &d, const T *x, const float *w, const float *bias, T *y,
+                         hipStream_t st_) {
+    const long pixw = ceil_div(g.p * g.q, 64);
+    // 8 output channels per lane while that leaves enough blocks, else 4; channel split until about
+    // two wavefronts per SIMD exist (measured on ResNet-18-shaped layers)
+    int tk = (g.k % 8 == 0 && pixw * (g.k / 8) * g.n >= 160 && g.r <= 3) ? 8 : 4;
+    const long base = pixw * (g.k / tk) * g.n;
+    int cs = 1;
+    while (cs < 16 && base * cs < 2048 && cs * 2 <= g.c) cs *= 2;
+    const size_t lds = cs > 1 ? (size_t)cs * tk * 64 * sizeof(float) : 0;
+    dim3 grid((unsigned)pixw, g.k / tk, g.n);
+    dim3 block(64 * cs);
+    if (g.r == 3) {
+        if (tk == 8) hipLaunchKernelGGL((direct_conv_slane_kernel<T, 8, 3>), grid, block, lds, st_, x, w, bias, y, d);
+        else hipLaunchKernelGGL((direct_conv_slane_kernel<T, 4, 3>), grid, block, lds, st_, x, w, bias, y, d);
+    } else if (g.r == 1) {
+        if (tk == 8) hipLaunchKernelGGL((direct_conv_slane_kernel<T, 8, 1>), grid, block, lds, st_, x, w, bias, y, d);
+        else hipLaunchKernelGGL((direct_conv_slane_kernel<T, 4, 1>), grid, block, lds, st_, x, w, bias, y, d);
+    } else if (g.r == 5) {
+        hipLaunchKernelGGL((direct_conv_slane_kernel<T, 4, 5>), grid, block, lds, st_, x, w, bias, y, d);
+    } else {
+        hipLaunchKernelGGL((direct_conv_slane_kernel<T, 4, 7>), grid, block, lds, st_, x, w, bias, y, d);
+    }
+}
+
 template <typename T>
 static hipError_t launch_direct_t(const Geo &g, const T *x, const float *w, const float *bias, T *y, hipStream_t st_) {
     DirectParams d{g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.sh, g.sw, g.ph, g.pw, g.p, g.q, g.cg, g.kg};
+    if (slane_supported(g)) {
+        launch_slane<T>(g, d, x, w, bias, y, st_);
+        return hipGetLastError();
+    }
     const DirectPlan pl = plan_direct(g);
     if (pl.tk == 16 && pl.tp == 2) launch_tiled<T, 16, 2>(g, pl, d, x, w, bias, y, st_);
     else if (pl.tk == 16) launch_tiled<T, 16, 1>(g, pl, d, x, w, bias, y, st_);
