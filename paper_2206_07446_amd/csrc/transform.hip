@@ -249,7 +249,10 @@ int fill_transform_job(const Geo &g, int kind, const float *src, void *dst, Tran
     } else if (kind == NNV_IM2COL_GEMM) {
         job->type = JOB_GEMM;
         const int cpad = job->half ? ceil_div(g.cg, 32) * 32 : ceil_div(g.cg, 4) * 4;
-        int cc = (1024 / job->RS) / 32 * 32;
+        // about 18 KB of LDS per block (as many resident blocks as the Winograd jobs of the
+        // same launch allow): 288 floats per row, at least one 32-channel fragment column
+        // (float16 output: twice that, its fragments span 32 channels)
+        int cc = ((job->half ? 576 : 288) / job->RS) / 32 * 32;
         if (cc < 32) cc = 32;
         job->cchunk = cc;
         job->nchunks = ceil_div(cpad, cc);
