@@ -206,9 +206,23 @@ __global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__rest
     float acc[TK];
 #pragma unroll
     for (int j = 0; j < TK; ++j) acc[j] = 0.f;
+    int c = wave;
+    if (FS == 1 && (d.C & 7) == 0) {
+        // 1x1 filter: the taps of eight consecutive input channels are contiguous, one
+        // eight-dword scalar load per output channel; a wavefront takes channel blocks of 8
+        for (int cb = wave * 8; cb < d.C; cb += CS * 8) {
+            float xa[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) xa[i] = buf_ld_x<T>(xres, voff[0], (uint32_t)(cb + i) * plane);
+#pragma unroll
+            for (int j = 0; j < TK; ++j)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[j] = fmaf(xa[i], wrow[j * wk + cb + i], acc[j]);
+        }
+        c = d.C;
+    }
     // two channels per iteration: the loads of both are issued before the FMAs of the first
     // (large filters: one channel at a time, their taps alone fill the registers)
-    int c = wave;
     for (; FS <= 3 && c + CS < d.C; c += 2 * CS) {
         float xa[RS], xb[RS];
 #pragma unroll

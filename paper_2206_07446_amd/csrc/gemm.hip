@@ -315,10 +315,13 @@ static GemmPlan plan_im2col(const Geo &g) {
     if (tiles(2, 2) >= 4096) { pl.tm = 2; pl.tn = 2; pl.ks_shift = 0; }
     else if (tiles(2, 1) >= 160) { pl.tm = 2; pl.tn = 1; pl.ks_shift = split_for(tiles(2, 1), 2048); }
     else { pl.tm = 1; pl.tn = 1; pl.ks_shift = split_for(tiles(1, 1), 768); }
+    // depth of the register ring: never more sets than the wavefront has chunks to load
     const int units_per_wave = ceil_div(nunits, 1 << pl.ks_shift);
+    const int chunk_units = pl.mode == 1 ? (half ? 2 : 8) : 1;
+    const int chunks = ceil_div(units_per_wave, chunk_units);
     pl.nbuf = 2;
-    if (pl.tm == 1 && units_per_wave >= 8) pl.nbuf = 4;
-    else if (pl.tm == 2 && pl.tn == 1 && units_per_wave >= 8) pl.nbuf = 3;
+    if (pl.tm == 1 && chunks >= 6) pl.nbuf = 4;
+    else if (pl.tm * pl.tn <= 2 && chunks >= 3) pl.nbuf = 3;
     if (const char *e = getenv("NNV_GEMM_PLAN")) {   // tm,tn,ks_shift,nbuf
         int a, b, c, d;
         if (sscanf(e, "%d,%d,%d,%d", &a, &b, &c, &d) == 4) { pl.tm = a; pl.tn = b; pl.ks_shift = c; pl.nbuf = d; }
