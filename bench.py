@@ -22,6 +22,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E
 MFMA_F32_PEAK_TFLOPS = 157.3  # dense float32 matrix-core peak
+VALU_F32_PEAK_TFLOPS = 157.3  # float32 vector peak (packed FMA; plain FMA, as compiled here, tops out at 78.6)
 
 
 def applicable_kinds(nnv, layer):
@@ -124,83 +125,90 @@ def main():
     srcs = [p.w_raw for p in pairs]
     dsts = [p.w_tx for p in pairs]
 
+    names = {nnv.DIRECT: "direct", nnv.IM2COL_GEMM: "im2col_gemm", nnv.WINO_F2: "wino_f2", nnv.WINO_F4: "wino_f4"}
+
     def transform_all():     # on torch's current stream
         nnv.nnv_transform_weights_grouped(descs, kinds, srcs, dsts)
 
-    def forward_all():
+    def forward_kind(kind):
         for p in pairs:
-            nnv.nnv_conv_forward(p.desc, p.kind, p.x, p.w_tx, None, p.y, ws, ws_bytes)
+            if p.kind == kind:
+                nnv.nnv_conv_forward(p.desc, p.kind, p.x, p.w_tx, None, p.y, ws, ws_bytes)
 
-    # The step is recorded once into a HIP graph on a side stream and replayed: batch-1 layers
-    # run for a few microseconds each, so launching ~150 kernels per step from Python would time
-    # the host, not the GPU.  Event records inside the graph split the two phases.
+    # Every phase of the step (the grouped transformation, then the forward pass of the whole
+    # stack per kernel kind) is recorded once into a HIP graph on a side stream and replayed:
+    # batch-1 layers run for a few microseconds each, so launching ~120 kernels per step from
+    # Python would time the host, not the GPU.  Events between the replays split the phases.
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
         transform_all()
-        forward_all()
+        for kind in names:
+            forward_kind(kind)
     torch.cuda.synchronize()
-    graphs = {}
-    for name, fn in (("transform", transform_all), ("forward", forward_all)):
+    phases = [("transform", transform_all)] + [(names[k], (lambda k=k: forward_kind(k))) for k in names]
+    graphs = []
+    for name, fn in phases:
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g, stream=side):
             fn()
-        graphs[name] = g
+        graphs.append(g)
     for _ in range(args.warmup):
-        graphs["transform"].replay()
-        graphs["forward"].replay()
+        for g in graphs:
+            g.replay()
     torch.cuda.synchronize()
 
     stream = torch.cuda.current_stream()
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    nph = len(graphs)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(nph + 1)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
         ev[s][0].record(stream)
-        graphs["transform"].replay()
-        ev[s][1].record(stream)
-        graphs["forward"].replay()
-        ev[s][2].record(stream)
+        for i, g in enumerate(graphs):
+            g.replay()
+            ev[s][i + 1].record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    tx_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
-    fw_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+    phase_ms = {phases[i][0]: float(np.mean([e[i].elapsed_time(e[i + 1]) for e in ev])) for i in range(nph)}
+    tx_ms = phase_ms["transform"]
+    fw_ms = sum(v for k, v in phase_ms.items() if k != "transform")
 
     tx_bytes = sum(p.transform_bytes for p in pairs)
     fw_flops = sum(p.flops for p in pairs)
     fw_direct_flops = sum(p.direct_flops for p in pairs)
-    # The transformation phase is the grouped kernel alone (two launches carry the 46 jobs; DIRECT
-    # aliases the raw weights and launches nothing): the events around it time that kernel.
-    n_tx_launches = 2
-    roofline = {"bound": "hbm", "kernel": "transform_kernel (grouped weight transformation)",
-                "achieved": round(tx_bytes / (tx_ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(tx_bytes / (tx_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4), "traffic": None,
-                "bytes_per_launch": tx_bytes / n_tx_launches, "launches_per_step": n_tx_launches,
-                "avg_launch_us": round(tx_ms * 1e3 / n_tx_launches, 2)}
 
-    # per-kind forward time of the whole stack (separate graph per kind, after the timed region)
-    per_kind = {}
-    names = {nnv.DIRECT: "direct", nnv.IM2COL_GEMM: "im2col_gemm", nnv.WINO_F2: "wino_f2", nnv.WINO_F4: "wino_f4"}
+    # Roofline entries per kernel class, from the event-bracketed phase times of the timed region
+    # (phase time / launches of the phase = average launch duration incl. the gaps inside a graph).
+    # transform: two launches of transform_kernel carry the 46 jobs (DIRECT aliases the raw weights).
+    def entry(kernel, bound, work, unit_scale, peak, unit, ms, launches):
+        ach = work / (ms * 1e-3) / unit_scale
+        return {"kernel": kernel, "bound": bound, "achieved": round(ach, 2), "peak": peak, "unit": unit,
+                "frac": round(ach / peak, 4), "traffic": None, "launches_per_step": launches,
+                "avg_launch_us": round(ms * 1e3 / launches, 2), "phase_ms": round(ms, 4)}
+
+    per_kind, roof_all = {}, []
+    roof_all.append(entry("transform_kernel (grouped weight transformation, all kinds)", "hbm", tx_bytes, 1e9,
+                          HBM_PEAK_GBPS, "GB/s", tx_ms, 2))
     for kind, kname in names.items():
         sel = [p for p in pairs if p.kind == kind]
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g, stream=side):
-            for p in sel:
-                nnv.nnv_conv_forward(p.desc, p.kind, p.x, p.w_tx, None, p.y, ws, ws_bytes)
-        g.replay()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        for _ in range(10):
-            g.replay()
-        e1.record(stream)
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / 10
+        ms = phase_ms[kname]
         fl = sum(p.flops for p in sel)
         per_kind[kname] = {"layers": len(sel), "forward_ms": round(ms, 4),
                            "TFLOPs_executed": round(fl / (ms * 1e-3) / 1e12, 3),
                            "TFLOPs_direct_equivalent": round(sum(p.direct_flops for p in sel) / (ms * 1e-3) / 1e12, 3)}
+        if kind == nnv.DIRECT:
+            roof_all.append(entry("direct_conv_slane_kernel (direct convolution, vector ALU)", "alu", fl, 1e12,
+                                  VALU_F32_PEAK_TFLOPS, "TFLOP/s", ms, len(sel)))
+        elif kind == nnv.IM2COL_GEMM:
+            roof_all.append(entry("im2col_gemm_kernel (implicit GEMM, float32 MFMA)", "mfma", fl, 1e12,
+                                  MFMA_F32_PEAK_TFLOPS, "TFLOP/s", ms, len(sel)))
+        else:
+            roof_all.append(entry(f"{kname}: wino_input + wino_gemm (float32 MFMA) + wino_output", "mfma", fl, 1e12,
+                                  MFMA_F32_PEAK_TFLOPS, "TFLOP/s", ms, 3 * len(sel)))
+    # the dominant kernel of the step = the class with the largest share of the step time
+    roofline = max(roof_all, key=lambda r: r["phase_ms"])
 
     out = {
         "metric": "cold transform+conv ms per model stack (weight-transform GB/s; conv TFLOP/s alongside)",
@@ -216,6 +224,7 @@ def main():
         "transform_ms": round(tx_ms, 4), "forward_ms": round(fw_ms, 4),
         "forward_by_kind": per_kind,
         "roofline": roofline,
+        "roofline_all": roof_all,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layers, nnv)

@@ -21,8 +21,6 @@
 // offsets.  A chunk (one channel block x all taps, or 8 channel blocks for 1x1) is loaded
 // one chunk ahead of the MFMAs (register ping-pong).  KS wavefronts of a workgroup share one
 // output tile and split the channel blocks; partial sums meet in LDS, fixed order.
-#include <cstdio>
-#include <cstdlib>
 #include "nnv_internal.h"
 #include "buf.h"
 
@@ -322,10 +320,6 @@ static GemmPlan plan_im2col(const Geo &g) {
     pl.nbuf = 2;
     if (pl.tm == 1 && chunks >= 6) pl.nbuf = 4;
     else if (pl.tm * pl.tn <= 2 && chunks >= 3) pl.nbuf = 3;
-    if (const char *e = getenv("NNV_GEMM_PLAN")) {   // tm,tn,ks_shift,nbuf
-        int a, b, c, d;
-        if (sscanf(e, "%d,%d,%d,%d", &a, &b, &c, &d) == 4) { pl.tm = a; pl.tn = b; pl.ks_shift = c; pl.nbuf = d; }
-    }
     if (half || pl.tm * pl.tn == 4) pl.nbuf = 2;
     pl.xt_bytes = half ? align_up((size_t)g.n * g.h * g.w * ceil_div(g.c, 32) * 32 * sizeof(__half), 256) : 0;
     return pl;

@@ -9,8 +9,6 @@
 //   3. output transform  Y = A^T M A, clipped to P x Q, plus bias        (vector ALU)
 // V and M live in the caller's workspace.  float16 storage keeps U, V and y in half
 // precision; the transforms and the accumulation are float32.
-#include <cstdio>
-#include <cstdlib>
 #include <type_traits>
 #include "nnv_internal.h"
 #include "buf.h"
@@ -321,18 +319,16 @@ static hipError_t launch_wino_t(const Geo &g, const WinoPlan &p, WinoParams &w, 
     {
         // wavefront tile, channel split and workgroup shape: cover >= 1024 wavefronts if possible
         const long aa = (long)p.alpha * p.alpha;
-        // latency-bound at batch 1: aim at ~4 wavefronts per SIMD, >= 8 channel steps each
+        // latency-bound at batch 1 (measured on ResNet-18-shaped layers): the largest wavefront
+        // tile that still leaves >= 768 wavefronts; then split the channel steps over the
+        // wavefronts of a workgroup towards ~4 per SIMD, keeping >= 16 steps each
         int tm = 1, tn = 1;
-        if (aa * ceil_div(p.K16, 2) * ceil_div(p.T16, 2) >= 4096) { tm = 2; tn = 2; }
-        else if (aa * ceil_div(p.K16, 2) * p.T16 >= 4096) { tm = 2; }
+        if (aa * ceil_div(p.K16, 2) * ceil_div(p.T16, 2) >= 768) { tm = 2; tn = 2; }
+        else if (aa * ceil_div(p.K16, 2) * p.T16 >= 768) { tm = 2; }
         int shift = 0;
         const long tiles = (long)ceil_div(p.K16, tm) * ceil_div(p.T16, tn);
-        while (shift < 4 && ((aa * tiles) << shift) < 4096 && (p.csteps >> (shift + 1)) >= 8) ++shift;
-        int d = HALF ? 2 : 8;
-        if (const char *e = getenv("NNV_WINO_PLAN")) {   // tm,tn,ks_shift,d
-            int a_, b_, c_, d_;
-            if (sscanf(e, "%d,%d,%d,%d", &a_, &b_, &c_, &d_) == 4) { tm = a_; tn = b_; shift = c_; if (!HALF) d = d_; }
-        }
+        while (shift < 4 && ((aa * tiles) << shift) < 4096 && (p.csteps >> (shift + 1)) >= (HALF ? 4 : 16)) ++shift;
+        const int d = HALF ? 2 : 8;
         w.ks_shift = shift;
         w.ntb = ceil_div(p.T16, tn);
         w.u_bytes = (uint32_t)((size_t)aa * p.K16 * p.csteps * 64 * (HALF ? 16 : 4));
