@@ -98,6 +98,9 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--counter-pass", action="store_true",
+                    help="run every kernel of the step a few times eagerly plus a plain 256 MiB copy, nothing timed: "
+                         "the program to put under `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only; use --gpus 1", file=sys.stderr)
@@ -134,6 +137,22 @@ def main():
         for p in pairs:
             if p.kind == kind:
                 nnv.nnv_conv_forward(p.desc, p.kind, p.x, p.w_tx, None, p.y, ws, ws_bytes)
+
+    if args.counter_pass:
+        # calibration: the library's plain copy kernel over 64 Mi floats (256 MiB read, 256 MiB written)
+        big = type("L", (), dict(n=1, c=1024, h=256, w=256, k=1024, r=1, s=64, stride=1, pad=0, groups=1))()
+        src = torch.zeros(64 << 20, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        cd = nnv.make_desc(big, nnv.F32)
+        for _ in range(3):
+            nnv.nnv_transform_weights(cd, nnv.DIRECT, src, dst)
+            transform_all()
+            for kind in names:
+                forward_kind(kind)
+        torch.cuda.synchronize()
+        print(json.dumps({"counter_pass": "done", "copy_bytes_each_way": 4 * (64 << 20),
+                          "transform_bytes_per_step": sum(p.transform_bytes for p in pairs)}))
+        return
 
     # Every phase of the step (the grouped transformation, then the forward pass of the whole
     # stack per kernel kind) is recorded once into a HIP graph on a side stream and replayed:
