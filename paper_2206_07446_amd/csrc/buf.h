@@ -26,4 +26,17 @@ template <> __device__ inline half8_t buf_load<half8_t>(__amdgpu_buffer_rsrc_t r
     return __builtin_bit_cast(half8_t, __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0));
 }
 
+// XCD-aware workgroup order.  The chip has 8 XCDs with one L2 each and hands consecutive
+// workgroups of a launch to the XCDs round-robin, so workgroup i runs on XCD i % 8.  A 1-D grid
+// of `total` logical tiles (rounded up to a multiple of 8 workgroups) is remapped so that XCD x
+// works on the contiguous logical range [x * per, (x + 1) * per): tiles that share an operand
+// panel then share an L2 instead of fetching the panel once per XCD.  Returns -1 for the padding.
+__device__ static inline int xcd_logical_tile(int total) {
+    const int per = (total + 7) >> 3;
+    const int i = blockIdx.x;
+    const int l = (i & 7) * per + (i >> 3);
+    return l < total ? l : -1;
+}
+static inline unsigned xcd_grid(int total) { return (unsigned)(((total + 7) / 8) * 8); }
+
 }  // namespace nnv

@@ -15,6 +15,8 @@ namespace nnv {
 
 struct DirectParams {
     int N, C, H, W, K, R, S, sh, sw, ph, pw, P, Q, Cg, Kg;
+    int grid_nx, grid_ny;   // scalar-weight kernel: pixel groups, output-channel groups (logical grid)
+    int k_major;            // 1: consecutive logical blocks walk the pixels first (an XCD keeps few filters)
 };
 
 template <typename T> __device__ static inline float ld(const T *p, size_t i);
@@ -186,8 +188,15 @@ __global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__rest
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int CS = blockDim.x >> 6;
     const int PQ = d.P * d.Q, HW = d.H * d.W;
-    const int k0 = blockIdx.y * TK, img = blockIdx.z;
-    const int pix = blockIdx.x * 64 + lane;
+    // XCD-aware block order: an XCD gets a contiguous range of output-channel groups (deep layers,
+    // filters dominate the traffic) or of pixel groups (shallow layers, x dominates)
+    const int lblk = xcd_logical_tile(d.grid_nx * d.grid_ny * d.N);
+    if (lblk < 0) return;
+    const int img = lblk / (d.grid_nx * d.grid_ny), l2 = lblk - img * (d.grid_nx * d.grid_ny);
+    const int bx = d.k_major ? l2 % d.grid_nx : l2 / d.grid_ny;
+    const int by = d.k_major ? l2 / d.grid_nx : l2 % d.grid_ny;
+    const int k0 = by * TK;
+    const int pix = bx * 64 + lane;
     const bool live = pix < PQ;
     const int p = live ? pix / d.Q : 0, q = live ? pix - p * d.Q : 0;
     uint32_t voff[RS];
@@ -325,7 +334,7 @@ static bool slane_supported(const Geo &g) {
 }
 
 template <typename T>
-static void launch_slane(const Geo &g, const DirectParams &d, const T *x, const float *w, const float *bias, T *y,
+static void launch_slane(const Geo &g, DirectParams d, const T *x, const float *w, const float *bias, T *y,
                          hipStream_t st_) {
     const long pixw = ceil_div(g.p * g.q, 64);
     // 8 output channels per lane while that leaves enough blocks, else 4; channel split until about
@@ -335,7 +344,10 @@ static void launch_slane(const Geo &g, const DirectParams &d, const T *x, const 
     int cs = 1;
     while (cs < 16 && base * cs < 2048 && cs * 2 <= g.c) cs *= 2;
     const size_t lds = cs > 1 ? (size_t)cs * tk * 64 * sizeof(float) : 0;
-    dim3 grid((unsigned)pixw, g.k / tk, g.n);
+    d.grid_nx = (int)pixw;
+    d.grid_ny = g.k / tk;
+    d.k_major = (size_t)g.k * g.c * g.r * g.s * 4 >= (size_t)g.c * g.h * g.w * sizeof(T);
+    dim3 grid(xcd_grid(d.grid_nx * d.grid_ny * g.n), 1, 1);
     dim3 block(64 * cs);
     if (g.r == 3) {
         if (tk == 8) hipLaunchKernelGGL((direct_conv_slane_kernel<T, 8, 3>), grid, block, lds, st_, x, w, bias, y, d);
@@ -352,7 +364,7 @@ static void launch_slane(const Geo &g, const DirectParams &d, const T *x, const 
 
 template <typename T>
 static hipError_t launch_direct_t(const Geo &g, const T *x, const float *w, const float *bias, T *y, hipStream_t st_) {
-    DirectParams d{g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.sh, g.sw, g.ph, g.pw, g.p, g.q, g.cg, g.kg};
+    DirectParams d{g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.sh, g.sw, g.ph, g.pw, g.p, g.q, g.cg, g.kg, 0, 0, 0};
     if (slane_supported(g)) {
         launch_slane<T>(g, d, x, w, bias, y, st_);
         return hipGetLastError();

@@ -44,6 +44,9 @@ struct GemmParams {
     uint32_t x_bytes, w_bytes;   // sizes of the x and wp buffers (range-checked loads)
     uint32_t cb_stride;  // bytes between channel blocks in x
     int half_out;
+    int grid_nx, grid_ny;  // logical grid: tile groups along n, along m
+    int m_major;           // 1: consecutive logical tiles walk n first (an XCD keeps few weight panels),
+                           // 0: they walk m first (an XCD keeps a pixel range of x)
 };
 
 template <bool HALF> struct FragT { typedef float type; };
@@ -78,8 +81,12 @@ __global__ __launch_bounds__(1024) void im2col_gemm_kernel(const GemmParams g) {
     const int KS = 1 << g.ks_shift;
     const int ks = wave & (KS - 1), nt = wave >> g.ks_shift;             // k-split index, tile within the workgroup
     const int tiles_per_wg = (blockDim.x >> 6) >> g.ks_shift;
-    const int mb0 = blockIdx.y * TM;
-    const int nb0 = (blockIdx.x * tiles_per_wg + nt) * TN;
+    const int ltile = xcd_logical_tile(g.grid_nx * g.grid_ny);
+    if (ltile < 0) return;                                               // whole workgroup: grid padding
+    const int bx = g.m_major ? ltile % g.grid_nx : ltile / g.grid_ny;
+    const int by = g.m_major ? ltile / g.grid_nx : ltile % g.grid_ny;
+    const int mb0 = by * TM;
+    const int nb0 = (bx * tiles_per_wg + nt) * TN;
     const int PQ = g.P * g.Q, RS = g.R * g.S;
 
     // ---- per-lane pixel state: origin of the patch in x (bytes, may be negative) and tap offsets
@@ -379,7 +386,10 @@ hipError_t launch_im2col(const Geo &g, const void *x, const void *w, const float
     const int waves = KS < 4 ? 4 : KS;
     const int tiles_per_wg = waves / KS;
     const int npix16 = ceil_div(gp.npix, 16);
-    dim3 grid(ceil_div(ceil_div(npix16, pl.tn), tiles_per_wg), ceil_div(gp.K16, pl.tm), 1);
+    gp.grid_nx = ceil_div(ceil_div(npix16, pl.tn), tiles_per_wg);
+    gp.grid_ny = ceil_div(gp.K16, pl.tm);
+    gp.m_major = gp.w_bytes >= gp.x_bytes;
+    dim3 grid(xcd_grid(gp.grid_nx * gp.grid_ny), 1, 1);
     const size_t lds = KS > 1 ? (size_t)waves * pl.tm * pl.tn * 4 * 64 * sizeof(float) : 0;
     if (half) launch_gemm_variant<true>(pl, gp, grid, dim3(64 * waves), lds, st);
     else launch_gemm_variant<false>(pl, gp, grid, dim3(64 * waves), lds, st);

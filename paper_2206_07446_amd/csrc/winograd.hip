@@ -32,6 +32,8 @@ struct WinoParams {
     int ks_shift;           // wavefronts sharing one output tile (splitting the channels) = 1 << ks_shift
     int ntb;                // tile-block groups per frequency: ceil(T16 / TN)
     uint32_t u_bytes, v_bytes;   // sizes of U and V (range-checked loads)
+    int gemm_wgs_per_xi;         // workgroups per frequency in the tile GEMM
+    int alpha2;                  // number of frequencies
 };
 
 // out[i][j] = sum_k L[i][k] * in[k][j] with a compile-time matrix L (zeros skipped).
@@ -134,10 +136,14 @@ __global__ __launch_bounds__(1024) void wino_gemm_kernel(const WinoParams w) {
     const int KS = 1 << w.ks_shift;
     const int ks = wave & (KS - 1), nt = wave >> w.ks_shift;
     const int tiles_per_wg = (blockDim.x >> 6) >> w.ks_shift;
-    const int tile = blockIdx.x * tiles_per_wg + nt;      // flattened (k-block group, tile-block group)
+    // logical workgroup order: frequency slowest, so an XCD works on a few frequencies and keeps
+    // their U and V panels in its own L2
+    const int lwg = xcd_logical_tile(w.gemm_wgs_per_xi * w.alpha2);
+    if (lwg < 0) return;
+    const int xi = lwg / w.gemm_wgs_per_xi;
+    const int tile = (lwg - xi * w.gemm_wgs_per_xi) * tiles_per_wg + nt;   // flattened (k-block group, tile-block group)
     const int kbt = tile / w.ntb, tbt = tile - kbt * w.ntb;
     const int kb0 = kbt * TM, tb0 = tbt * TN;              // kb0 >= K16 for surplus wavefronts
-    const int xi = blockIdx.y;
     const __amdgpu_buffer_rsrc_t ures = make_rsrc(w.U, w.u_bytes);
     const __amdgpu_buffer_rsrc_t vres = make_rsrc(w.V, w.v_bytes);
     constexpr uint32_t FB = sizeof(frag_t), FRAG = 64 * FB;
@@ -337,7 +343,9 @@ static hipError_t launch_wino_t(const Geo &g, const WinoPlan &p, WinoParams &w, 
         const int waves = KS < 4 ? 4 : KS;
         const int tiles_per_wg = waves / KS;
         const long ntiles = (long)ceil_div(p.K16, tm) * w.ntb;
-        dim3 grid((unsigned)ceil_div((int)ntiles, tiles_per_wg), (unsigned)aa, 1);
+        w.gemm_wgs_per_xi = ceil_div((int)ntiles, tiles_per_wg);
+        w.alpha2 = (int)aa;
+        dim3 grid(xcd_grid(w.gemm_wgs_per_xi * (int)aa), 1, 1);
         dim3 block(64 * waves);
         const size_t lds = KS > 1 ? (size_t)waves * tm * tn * 4 * 64 * sizeof(float) : 0;
         if constexpr (HALF) {
