@@ -40,7 +40,8 @@ typedef enum {
     NNV_WINO_F2 = 2,     /* Winograd F(2x2,3x3): 4x4 tiles                                     */
     NNV_WINO_F4 = 3,     /* Winograd F(4x4,3x3): 6x6 tiles                                     */
     NNV_DEPTHWISE = 4,   /* 3x3 depthwise (groups = C = K) from channel-blocked tap-major weights */
-    NNV_KIND_COUNT = 5
+    NNV_WINO_F6 = 5,     /* Winograd F(6x6,3x3): 8x8 tiles, the tile size of Fig. 3; float32 only */
+    NNV_KIND_COUNT = 6
 } nnv_kind;
 
 typedef enum { NNV_F32 = 0, NNV_F16 = 1 } nnv_dtype;
@@ -91,8 +92,10 @@ const char *nnv_last_hip_error(void);
 
 /* 1 if `kind` can run the layer, 0 if not, NNV_E_* if the descriptor is invalid.
  *   WINO_F2/F4   : R = S = 3, stride 1, groups 1
+ *   WINO_F6      : the same, and dtype float32 (with U and V rounded to float16 its error
+ *                  exceeds the float16 bound of this library, so that pairing is refused)
  *   DEPTHWISE    : groups = C = K, R = S = 3, stride_h = stride_w in {1,2}
- *   IM2COL_GEMM  : groups 1, R,S <= 32, R*S <= 128
+ *   IM2COL_GEMM  : groups 1, R,S <= 32, R*S <= 64
  *   DIRECT       : any groups dividing C and K
  * (the paper's engine keys the usable kernels on filter size, stride and channel
  * divisibility in the same way, Fig. 5). */

@@ -127,6 +127,8 @@ def transformed_bytes(kind: str, K: int, Cg: int, R: int, S: int, half: bool) ->
         return wino_offsets(4, K, Cg, half)[0] * e
     if kind == "wino_f4":
         return wino_offsets(6, K, Cg, half)[0] * e
+    if kind == "wino_f6":
+        return wino_offsets(8, K, Cg, half)[0] * e
     if kind == "depthwise":
         return depthwise_offsets(K)[0] * e
     raise ValueError(kind)

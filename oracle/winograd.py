@@ -44,10 +44,13 @@ from .cooktoom import cook_toom, rescale
 #   F4H      points 0, 1, -1, 2, -1/2 with power-of-two G row scaling; used when
 #            U and V are stored in half precision (smaller dynamic range of U,
 #            smaller entries in A^T; see the error study in the test-suite).
+#   F6       points 0, +-1, +-2, +-1/2 (8 x 8 tiles, the tile size of Fig. 3), with the sign
+#            of G row 0 and B^T row 0 flipped so that G starts (1, 0, 0).
 VARIANTS = {
     "F2": (2, (0, 1, -1), (-1, 1, 1, 1), (-1, 1, 1, -1)),
     "F4": (4, (0, 1, -1, 2, -2), (1, 1, 1, 1, 1, 1), (1, 1, 1, 1, 1, 1)),
     "F4H": (4, (0, 1, -1, 2, Fr(-1, 2)), (4, 4, 4, 16, 4, 1), (1, 1, 1, 1, 1, 1)),
+    "F6": (6, (0, 1, -1, 2, -2, Fr(1, 2), Fr(-1, 2)), (-1, 1, 1, 1, 1, 1, 1, 1), (-1, 1, 1, 1, 1, 1, 1, 1)),
 }
 
 

@@ -9,9 +9,9 @@ from ctypes import c_char_p, c_double, c_int, c_int32, c_size_t, c_void_p, POINT
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libnnv.so")
 
-DIRECT, IM2COL_GEMM, WINO_F2, WINO_F4, DEPTHWISE = range(5)
+DIRECT, IM2COL_GEMM, WINO_F2, WINO_F4, DEPTHWISE, WINO_F6 = range(6)
 KINDS = {"direct": DIRECT, "im2col_gemm": IM2COL_GEMM, "wino_f2": WINO_F2, "wino_f4": WINO_F4,
-         "depthwise": DEPTHWISE}
+         "depthwise": DEPTHWISE, "wino_f6": WINO_F6}
 F32, F16 = 0, 1
 
 EXPORTS = ("nnv_layout_version", "nnv_status_string", "nnv_last_hip_error", "nnv_kind_supported",

@@ -60,6 +60,7 @@ bool kind_rules(const Geo &g, int kind) {
         case NNV_IM2COL_GEMM: return g.groups == 1 && g.r <= 32 && g.s <= 32 && g.r * g.s <= 64;
         case NNV_WINO_F2:
         case NNV_WINO_F4: return g.groups == 1 && g.r == 3 && g.s == 3 && g.sh == 1 && g.sw == 1;
+        case NNV_WINO_F6: return g.groups == 1 && g.r == 3 && g.s == 3 && g.sh == 1 && g.sw == 1 && g.dtype == NNV_F32;
         case NNV_DEPTHWISE:
             return g.groups == g.c && g.c == g.k && g.r == 3 && g.s == 3 && g.sh == g.sw && (g.sh == 1 || g.sh == 2);
         default: return false;
@@ -75,6 +76,7 @@ size_t tx_bytes(const Geo &g, int kind) {
         case NNV_IM2COL_GEMM: return k16 * frag * g.r * g.s;
         case NNV_WINO_F2: return 16 * k16 * frag;
         case NNV_WINO_F4: return 36 * k16 * frag;
+        case NNV_WINO_F6: return 64 * k16 * frag;
         case NNV_DEPTHWISE: return (size_t)ceil_div(g.c, 32) * 288 * (half ? 2 : 4);
         default: return 0;
     }
@@ -84,7 +86,8 @@ size_t ws_bytes(const Geo &g, int kind) {
     switch (kind) {
         case NNV_IM2COL_GEMM: return im2col_workspace_bytes(g);
         case NNV_WINO_F2:
-        case NNV_WINO_F4: return wino_workspace_bytes(g, kind);
+        case NNV_WINO_F4:
+        case NNV_WINO_F6: return wino_workspace_bytes(g, kind);
         default: return 0;
     }
 }
@@ -146,7 +149,8 @@ int forward_checked(const Geo &g, int kind, const void *x, const void *w_tx, con
         case NNV_DIRECT: e = launch_direct(g, x, static_cast<const float *>(w_tx), bias, y, st); break;
         case NNV_IM2COL_GEMM: e = launch_im2col(g, x, w_tx, bias, y, ws, st); break;
         case NNV_WINO_F2:
-        case NNV_WINO_F4: e = launch_wino(g, kind, x, w_tx, bias, y, ws, st); break;
+        case NNV_WINO_F4:
+        case NNV_WINO_F6: e = launch_wino(g, kind, x, w_tx, bias, y, ws, st); break;
         case NNV_DEPTHWISE: e = launch_depthwise(g, x, w_tx, bias, y, st); break;
         default: return NNV_E_ARG;
     }
@@ -290,8 +294,8 @@ int nnv_time_layer(const nnv_conv_desc *desc, nnv_kind kind, const float *w_raw,
     out->forward_bytes = esz * ((double)g.n * g.c * g.h * g.w + (double)g.n * g.k * g.p * g.q) + tx_b;
     const double macs = (double)g.n * g.k * g.p * g.q * g.cg * g.r * g.s;
     out->direct_equiv_flops = 2.0 * macs;
-    if (kind == NNV_WINO_F2 || kind == NNV_WINO_F4) {
-        const int m = kind == NNV_WINO_F2 ? 2 : 4;
+    if (is_wino(kind)) {
+        const int m = wino_m(kind);
         const double tiles = (double)g.n * ceil_div(g.p, m) * ceil_div(g.q, m);
         out->forward_flops = 2.0 * (m + 2) * (m + 2) * g.k * g.c * tiles;
     } else {

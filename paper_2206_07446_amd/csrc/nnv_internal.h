@@ -16,12 +16,15 @@ struct Geo {
 };
 
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+static inline bool is_wino(int kind) { return kind == NNV_WINO_F2 || kind == NNV_WINO_F4 || kind == NNV_WINO_F6; }
+static inline int wino_m(int kind) { return kind == NNV_WINO_F2 ? 2 : kind == NNV_WINO_F4 ? 4 : 6; }
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Winograd matrix sets (see wino_consts.h)
-enum WinoSet { WS_F2 = 0, WS_F4 = 1, WS_F4H = 2 };
+enum WinoSet { WS_F2 = 0, WS_F4 = 1, WS_F4H = 2, WS_F6 = 3 };
 static inline int wino_set(int kind, int dtype) {
     if (kind == NNV_WINO_F2) return WS_F2;
+    if (kind == NNV_WINO_F6) return WS_F6;
     return dtype == NNV_F16 ? WS_F4H : WS_F4;
 }
 

@@ -205,6 +205,10 @@ __device__ static inline void dw_block(const TransformJob &job, int local_block)
     else static_cast<float *>(job.dst)[o] = v;
 }
 
+// F6: the launch holds F(6x6) jobs.  Their 64 outputs per filter take more registers than
+// any other job, so launches without them run an instantiation that leaves that branch out
+// and keeps four wavefronts per SIMD.
+template <bool F6>
 __global__ __launch_bounds__(256) void transform_kernel(const JobTable tbl) {
     extern __shared__ __align__(16) float lds[];
     const int b = blockIdx.x;
@@ -217,6 +221,8 @@ __global__ __launch_bounds__(256) void transform_kernel(const JobTable tbl) {
             if (job.half) wino_block<0, true>(job, lb, lds); else wino_block<0, false>(job, lb, lds);
         } else if (job.wset == WS_F4) {
             wino_block<1, false>(job, lb, lds);
+        } else if (job.wset == WS_F6) {
+            if constexpr (F6) wino_block<3, false>(job, lb, lds);
         } else {
             wino_block<2, true>(job, lb, lds);
         }
@@ -239,7 +245,7 @@ int fill_transform_job(const Geo &g, int kind, const float *src, void *dst, Tran
     job->wset = 0;
     job->block0 = 0;
     const int k16 = ceil_div(g.k, 16);
-    if (kind == NNV_WINO_F2 || kind == NNV_WINO_F4) {
+    if (is_wino(kind)) {
         job->type = JOB_WINO;
         job->wset = wino_set(kind, g.dtype);
         const int cpad = job->half ? ceil_div(g.cg, 32) * 32 : ceil_div(g.cg, 4) * 4;
@@ -281,12 +287,16 @@ size_t transform_job_lds_bytes(const TransformJob &job) {
 
 hipError_t launch_transform_jobs(const JobTable &tbl, int total_blocks, size_t lds, hipStream_t st) {
     if (total_blocks <= 0) return hipSuccess;
+    bool f6 = false;
+    for (int j = 0; j < tbl.njobs; ++j) f6 = f6 || (tbl.job[j].type == JOB_WINO && tbl.job[j].wset == WS_F6);
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(transform_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        const void *fn = f6 ? reinterpret_cast<const void *>(transform_kernel<true>)
+                            : reinterpret_cast<const void *>(transform_kernel<false>);
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(transform_kernel, dim3(total_blocks), dim3(256), lds, st, tbl);
+    if (f6) hipLaunchKernelGGL(transform_kernel<true>, dim3(total_blocks), dim3(256), lds, st, tbl);
+    else hipLaunchKernelGGL(transform_kernel<false>, dim3(total_blocks), dim3(256), lds, st, tbl);
     return hipGetLastError();
 }
 

@@ -7,6 +7,7 @@
 //   set 2 (F4H) : points 0, 1, -1, 2, -1/2, with G rows scaled by 4,4,4,16,4,1 and
 //                 the columns of A^T divided by the same factors (6x6 tiles, float16
 //                 storage: smaller spread of U, smaller entries in A^T)
+//   set 3 (F6)  : points 0, 1, -1, 2, -2, 1/2, -1/2   (8x8 tiles, float32 storage)
 // written out literally.  G is alpha x 3, BT is alpha x alpha, AT is m x alpha.
 #pragma once
 
@@ -48,6 +49,32 @@ template <> struct WinoMat<2> {
                                        {0, .25f, -.25f, .125f, -.125f, 0},
                                        {0, .25f, .25f, .25f, .0625f, 0},
                                        {0, .25f, -.25f, .5f, -.03125f, 1}};
+};
+
+template <> struct WinoMat<3> {
+    static constexpr int M = 6, A = 8;
+    static constexpr float G[8][3] = {{1.f, 0.f, 0.f},
+                                      {-2.f / 9, -2.f / 9, -2.f / 9},
+                                      {-2.f / 9, 2.f / 9, -2.f / 9},
+                                      {1.f / 90, 1.f / 45, 2.f / 45},
+                                      {1.f / 90, -1.f / 45, 2.f / 45},
+                                      {32.f / 45, 16.f / 45, 8.f / 45},
+                                      {32.f / 45, -16.f / 45, 8.f / 45},
+                                      {0.f, 0.f, 1.f}};
+    static constexpr float BT[8][8] = {{1, 0, -5.25f, 0, 5.25f, 0, -1, 0},
+                                       {0, 1, 1, -4.25f, -4.25f, 1, 1, 0},
+                                       {0, -1, 1, 4.25f, -4.25f, -1, 1, 0},
+                                       {0, .5f, .25f, -2.5f, -1.25f, 2, 1, 0},
+                                       {0, -.5f, .25f, 2.5f, -1.25f, -2, 1, 0},
+                                       {0, 2, 4, -2.5f, -5, .5f, 1, 0},
+                                       {0, -2, 4, 2.5f, -5, -.5f, 1, 0},
+                                       {0, -1, 0, 5.25f, 0, -5.25f, 0, 1}};
+    static constexpr float AT[6][8] = {{1, 1, 1, 1, 1, 1, 1, 0},
+                                       {0, 1, -1, 2, -2, .5f, -.5f, 0},
+                                       {0, 1, 1, 4, 4, .25f, .25f, 0},
+                                       {0, 1, -1, 8, -8, .125f, -.125f, 0},
+                                       {0, 1, 1, 16, 16, .0625f, .0625f, 0},
+                                       {0, 1, -1, 32, -32, .03125f, -.03125f, 1}};
 };
 
 }  // namespace nnv

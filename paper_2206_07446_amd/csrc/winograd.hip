@@ -1,4 +1,4 @@
-// Winograd F(2x2,3x3) / F(4x4,3x3) convolution from transformed weights (the fastest
+// Winograd F(2x2,3x3) / F(4x4,3x3) / F(6x6,3x3) convolution from transformed weights (the fastest
 // executing, most expensive to prepare kernel family of Table 2).  Three kernels:
 //   1. input transform   V[xi][tile block][c][16 tiles] = (B^T d B)[xi]   (vector ALU)
 //   2. batched tile GEMM M[xi] = U[xi] (K x C) * V[xi] (C x T), alpha^2 independent
@@ -295,7 +295,7 @@ struct WinoPlan {
 static WinoPlan plan_wino(const Geo &g, int kind) {
     WinoPlan p{};
     const bool half = g.dtype == NNV_F16;
-    p.m = kind == NNV_WINO_F2 ? 2 : 4;
+    p.m = wino_m(kind);
     p.alpha = p.m + 2;
     p.th = ceil_div(g.p, p.m);
     p.tw = ceil_div(g.q, p.m);
@@ -385,6 +385,7 @@ hipError_t launch_wino(const Geo &g, int kind, const void *x, const void *U, con
         return launch_wino_t<0, false>(g, p, w, st);
     }
     if (set == WS_F4) return launch_wino_t<1, false>(g, p, w, st);
+    if (set == WS_F6) return launch_wino_t<3, false>(g, p, w, st);
     return launch_wino_t<2, true>(g, p, w, st);
 }
 

@@ -17,7 +17,7 @@ import json
 from dataclasses import dataclass, asdict
 from typing import Dict, List, Optional
 
-KIND_NAMES = {0: "direct", 1: "im2col_gemm", 2: "wino_f2", 3: "wino_f4", 4: "depthwise"}
+KIND_NAMES = {0: "direct", 1: "im2col_gemm", 2: "wino_f2", 3: "wino_f4", 4: "depthwise", 5: "wino_f6"}
 
 
 @dataclass
@@ -90,7 +90,7 @@ def profile_stack(stack_name: str, dtype: int = 0, reps: int = 10, flush_mb: int
             xd = xd.half()
         y = torch.empty(layer.n * layer.k * layer.p * layer.q, dtype=xd.dtype, device=dev)
         cands = []
-        for kind in range(5):
+        for kind in range(6):
             if not nnv.nnv_kind_supported(desc, kind):
                 continue
             nb = nnv.nnv_transformed_bytes(desc, kind)

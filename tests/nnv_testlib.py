@@ -8,29 +8,32 @@ from oracle import layouts as OL
 from oracle import winograd as OW
 from oracle.direct import conv2d_direct
 
-KIND_NAMES = {0: "direct", 1: "im2col_gemm", 2: "wino_f2", 3: "wino_f4", 4: "depthwise"}
+KIND_NAMES = {0: "direct", 1: "im2col_gemm", 2: "wino_f2", 3: "wino_f4", 4: "depthwise", 5: "wino_f6"}
 
 
 def wino_variant(kind: int, half: bool) -> str:
     if kind == 2:
         return "F2"
+    if kind == 5:
+        return "F6"
     return "F4H" if half else "F4"
 
 
 def conv_tolerance(kind: int, half: bool) -> float:
     """max|y - y_oracle| <= tol * max|y_oracle|: 1e-4 for the float32 direct, GEMM, depthwise and
-    F(2x2) kernels, 2e-3 for float32 F(4x4), 5e-3 for float16 storage."""
+    F(2x2) kernels, 2e-3 for float32 F(4x4) and F(6x6), 5e-3 for float16 storage."""
     if half:
         return 5e-3
-    return 2e-3 if kind == 3 else 1e-4
+    return 2e-3 if kind in (3, 5) else 1e-4
 
 
-def applicable_kinds(layer):
+def applicable_kinds(layer, half=False):
+    """Kernel kinds that can run the layer (F(6x6) exists in float32 only)."""
     kinds = [0]
     if layer.groups == 1:
         kinds.append(1)
         if layer.winograd_ok:
-            kinds += [2, 3]
+            kinds += [2, 3] if half else [2, 3, 5]
     if layer.is_depthwise and layer.r == 3 and layer.stride in (1, 2):
         kinds.append(4)
     return kinds

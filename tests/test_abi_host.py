@@ -81,7 +81,7 @@ def test_null_and_argument_errors_need_no_gpu():
     assert lib.nnv_transform_weights_grouped(0, None, None, None, None, None) == 0
 
 
-KNAME = {0: "direct", 1: "im2col_gemm", 2: "wino_f2", 3: "wino_f4", 4: "depthwise"}
+KNAME = {0: "direct", 1: "im2col_gemm", 2: "wino_f2", 3: "wino_f4", 4: "depthwise", 5: "wino_f6"}
 
 
 @pytest.mark.parametrize("name", STACK_NAMES)
@@ -89,7 +89,7 @@ def test_transformed_bytes_match_oracle_layout_sizes(name):
     for layer in stack(name):
         for half in (False, True):
             d = nnv.make_desc(layer, nnv.F16 if half else nnv.F32)
-            for kind in range(5):
+            for kind in range(6):
                 if not nnv.nnv_kind_supported(d, kind):
                     assert nnv.nnv_transformed_bytes(d, kind) == 0
                     continue
@@ -103,4 +103,5 @@ def test_winograd_size_ratio_unpadded():
     raw = 64 * 64 * 9 * 4
     assert nnv.nnv_transformed_bytes(d, nnv.WINO_F2) * 9 == raw * 16
     assert nnv.nnv_transformed_bytes(d, nnv.WINO_F4) * 9 == raw * 36
+    assert nnv.nnv_transformed_bytes(d, nnv.WINO_F6) * 9 == raw * 64    # the 7.1x of the paper's 8x8-tile example
     assert nnv.nnv_transformed_bytes(d, nnv.IM2COL_GEMM) == raw

@@ -69,20 +69,21 @@ SMALL = [
     Ly("dw_n2", 5, 7, 7, 5, 3, 1, 1, groups=5, n=2),
     Ly("grp2", 8, 9, 9, 12, 3, 1, 1, groups=2),
 ]
-CASES = [(l, k) for l in SMALL for k in applicable_kinds(l)]
+CASES = [(l, k, h) for h in (False, True) for l in SMALL for k in applicable_kinds(l, h)]
 
 
-@pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
-@pytest.mark.parametrize("layer,kind", CASES, ids=[f"{l.name}-{KIND_NAMES[k]}" for l, k in CASES])
+@pytest.mark.parametrize("layer,kind,half", CASES,
+                         ids=[f"{l.name}-{KIND_NAMES[k]}-{'f16' if h else 'f32'}" for l, k, h in CASES])
 def test_small_layers(env, layer, kind, half):
     std = 0.1 if layer.name == "cfg1" else None
     check(env, layer, kind, half, seed=1000 + len(layer.name), w_std=std)
 
 
-@pytest.mark.parametrize("kind", [0, 1, 2, 3])
+@pytest.mark.parametrize("kind", [0, 1, 2, 3, 5])
 def test_bias(env, kind):
     check(env, SMALL[1], kind, False, seed=77, bias=True)
-    check(env, SMALL[1], kind, True, seed=78, bias=True)
+    if kind != 5:
+        check(env, SMALL[1], kind, True, seed=78, bias=True)
 
 
 def test_bias_depthwise(env):
@@ -94,7 +95,7 @@ def test_cross_kind_agreement(env):
     nnv, torch = env
     layer = SMALL[1]
     w, x = layer_tensors(layer, 5)
-    ys = [gpu_forward(nnv, torch, layer, k, False, w, x) for k in (0, 1, 2, 3)]
+    ys = [gpu_forward(nnv, torch, layer, k, False, w, x) for k in (0, 1, 2, 3, 5)]
     scale = np.abs(ys[0]).max()
     for y in ys[1:]:
         assert np.abs(y - ys[0]).max() <= 2.1e-3 * scale
@@ -105,7 +106,7 @@ def test_linearity_and_channel_permutation(env):
     layer = SMALL[0]
     w, x1 = layer_tensors(layer, 11)
     _, x2 = layer_tensors(layer, 12)
-    for kind in (1, 3):
+    for kind in (1, 3, 5):
         ya = gpu_forward(nnv, torch, layer, kind, False, w, 2.0 * x1 + x2)
         yb = 2.0 * gpu_forward(nnv, torch, layer, kind, False, w, x1) + gpu_forward(nnv, torch, layer, kind, False, w, x2)
         assert np.abs(ya - yb).max() <= 1e-4 * np.abs(ya).max()
@@ -118,8 +119,8 @@ def test_linearity_and_channel_permutation(env):
 def _stack_cases(name, dtypes):
     idx = STACK_NAMES.index(name) + 1
     for i, layer in enumerate(stack(name)):
-        for kind in applicable_kinds(layer):
-            for half in dtypes:
+        for half in dtypes:
+            for kind in applicable_kinds(layer, half):
                 yield layer, kind, half, 220607446 + 1000 * idx + i
 
 
@@ -181,17 +182,19 @@ def test_time_layer(env):
     wd, xd = torch.from_numpy(w).to(dev), torch.from_numpy(x).to(dev)
     y = torch.empty(layer.k * layer.p * layer.q, device=dev)
     flush = torch.empty(64 << 20, dtype=torch.uint8, device=dev)
-    for kind in (0, 1, 2, 3):
+    for kind in (0, 1, 2, 3, 5):
         wt = torch.empty(nnv.nnv_transformed_bytes(desc, kind), dtype=torch.uint8, device=dev)
         ws = torch.empty(max(16, nnv.nnv_workspace_bytes(desc, kind)), dtype=torch.uint8, device=dev)
         t = nnv.nnv_time_layer(desc, kind, wd, wt, xd, y, ws, flush=flush, warmup=1, reps=5)
         assert t.forward_ms > 0 and t.transform_ms > 0
         # sanity floor: no faster than the rooflines allow (8 TB/s, 157.3 TFLOP/s)
         assert t.transform_ms * 1e-3 >= t.transform_bytes / 8e12
-        assert t.forward_ms * 1e-3 >= t.forward_flops / 157.3e12 * 0.999 or kind in (2, 3)
+        assert t.forward_ms * 1e-3 >= t.forward_flops / 157.3e12 * 0.999 or kind in (2, 3, 5)
         assert t.direct_equiv_flops == 2.0 * layer.macs
         if kind == 3:
             assert t.forward_flops == 2.0 * 36 * 64 * 64 * 196
+        if kind == 5:
+            assert t.forward_flops == 2.0 * 64 * 64 * 64 * 100     # 56/6 -> 10 x 10 tiles
         print(KIND_NAMES[kind], t.transform_ms, t.forward_ms)
     # aliasing direct transform costs nothing
     t = nnv.nnv_time_layer(desc, 0, wd, wd, xd, y, None, warmup=0, reps=2)

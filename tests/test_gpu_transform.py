@@ -88,10 +88,14 @@ def check_wino_u(got, exp64, bound, half):
 
 
 @pytest.mark.parametrize("half", [False, True])
-@pytest.mark.parametrize("kind", [2, 3], ids=["f2", "f4"])
+@pytest.mark.parametrize("kind", [2, 3, 5], ids=["f2", "f4", "f6"])
 @pytest.mark.parametrize("layer", WINO_LAYERS, ids=lambda l: l.name)
 def test_wino_weight_transform(env, layer, kind, half):
     nnv, torch = env
+    if half and kind == 5:
+        desc = nnv.make_desc(layer, nnv.F16)
+        assert nnv.nnv_kind_supported(desc, kind) == 0 and nnv.nnv_transformed_bytes(desc, kind) == 0
+        return
     w = layer_tensors(layer, 8)[0]
     got, *_ = gpu_transform(nnv, torch, layer, kind, half, w)
     exp64, bound = oracle_transformed(w, kind, half)
@@ -101,7 +105,7 @@ def test_wino_weight_transform(env, layer, kind, half):
     assert (raw[pad_mask] == 0).all()
 
 
-@pytest.mark.parametrize("kind", [2, 3], ids=["f2", "f4"])
+@pytest.mark.parametrize("kind", [2, 3, 5], ids=["f2", "f4", "f6"])
 def test_wino_positions_with_delta_filters(env, kind):
     """Centre-delta filters scaled by a (k,c) code: U[xi,k,c] = code * (G[:,1] G[:,1]^T)[xi] puts a
     distinct, exactly representable multiple at every position."""
@@ -164,7 +168,7 @@ def test_full_size_resnet18_transforms(env):
         exp, _ = oracle_transformed(w, nnv.IM2COL_GEMM, False)
         assert np.array_equal(got.view(np.uint32), exp.view(np.uint32)), layer.name
         if layer.winograd_ok:
-            for kind in (2, 3):
+            for kind in (2, 3, 5):
                 got, *_ = gpu_transform(nnv, torch, layer, kind, False, w)
                 exp64, bound = oracle_transformed(w, kind, False)
                 check_wino_u(got, exp64, bound, False)
