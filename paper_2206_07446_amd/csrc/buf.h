@@ -4,6 +4,7 @@
 // straight-line code and can be kept in flight across the matrix instructions.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
 #include <stdint.h>
 
 namespace nnv {
@@ -24,6 +25,16 @@ template <> __device__ inline float buf_load<float>(__amdgpu_buffer_rsrc_t r, ui
 }
 template <> __device__ inline half8_t buf_load<half8_t>(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
     return __builtin_bit_cast(half8_t, __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0));
+}
+
+// One activation element (float32 or float16 storage) as float.
+template <typename T> __device__ static inline float buf_load_x(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff);
+template <> __device__ inline float buf_load_x<float>(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0));
+}
+template <> __device__ inline float buf_load_x<__half>(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+    const unsigned short u = __builtin_amdgcn_raw_buffer_load_b16(r, voff, soff, 0);
+    return (float)__builtin_bit_cast(_Float16, u);
 }
 
 // XCD-aware workgroup order.  The chip has 8 XCDs with one L2 each and hands consecutive

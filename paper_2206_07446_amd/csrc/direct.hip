@@ -26,15 +26,6 @@ template <typename T> __device__ static inline void st(T *p, size_t i, float v);
 template <> __device__ inline void st<float>(float *p, size_t i, float v) { p[i] = v; }
 template <> __device__ inline void st<__half>(__half *p, size_t i, float v) { p[i] = __float2half_rn(v); }
 
-template <typename T> __device__ static inline float buf_ld_x(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff);
-template <> __device__ inline float buf_ld_x<float>(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
-    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0));
-}
-template <> __device__ inline float buf_ld_x<__half>(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
-    const unsigned short u = __builtin_amdgcn_raw_buffer_load_b16(r, voff, soff, 0);
-    return (float)__builtin_bit_cast(_Float16, u);
-}
-
 // Fallback for channel counts the tiled kernel does not cover (few output channels per group).
 template <typename T, int KB>
 __global__ __launch_bounds__(256) void direct_conv_simple_kernel(const T *__restrict__ x, const float *__restrict__ w,
@@ -222,7 +213,7 @@ __global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__rest
         for (int cb = wave * 8; cb < d.C; cb += CS * 8) {
             float xa[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) xa[i] = buf_ld_x<T>(xres, voff[0], (uint32_t)(cb + i) * plane);
+            for (int i = 0; i < 8; ++i) xa[i] = buf_load_x<T>(xres, voff[0], (uint32_t)(cb + i) * plane);
 #pragma unroll
             for (int j = 0; j < TK; ++j)
 #pragma unroll
@@ -235,9 +226,9 @@ __global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__rest
     for (; FS <= 3 && c + CS < d.C; c += 2 * CS) {
         float xa[RS], xb[RS];
 #pragma unroll
-        for (int i = 0; i < RS; ++i) xa[i] = buf_ld_x<T>(xres, voff[i], (uint32_t)c * plane);
+        for (int i = 0; i < RS; ++i) xa[i] = buf_load_x<T>(xres, voff[i], (uint32_t)c * plane);
 #pragma unroll
-        for (int i = 0; i < RS; ++i) xb[i] = buf_ld_x<T>(xres, voff[i], (uint32_t)(c + CS) * plane);
+        for (int i = 0; i < RS; ++i) xb[i] = buf_load_x<T>(xres, voff[i], (uint32_t)(c + CS) * plane);
         const float *wa = wrow + (size_t)c * RS, *wb = wrow + (size_t)(c + CS) * RS;
 #pragma unroll
         for (int j = 0; j < TK; ++j)
@@ -251,7 +242,7 @@ __global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__rest
     for (; c < d.C; c += CS) {
         float xa[RS];
 #pragma unroll
-        for (int i = 0; i < RS; ++i) xa[i] = buf_ld_x<T>(xres, voff[i], (uint32_t)c * plane);
+        for (int i = 0; i < RS; ++i) xa[i] = buf_load_x<T>(xres, voff[i], (uint32_t)c * plane);
         const float *wa = wrow + (size_t)c * RS;
 #pragma unroll
         for (int j = 0; j < TK; ++j)

@@ -32,6 +32,7 @@ struct WinoParams {
     int ks_shift;           // wavefronts sharing one output tile (splitting the channels) = 1 << ks_shift
     int ntb;                // tile-block groups per frequency: ceil(T16 / TN)
     uint32_t u_bytes, v_bytes;   // sizes of U and V (range-checked loads)
+    uint32_t x_bytes;            // size of x
     int gemm_wgs_per_xi;         // workgroups per frequency in the tile GEMM
     int alpha2;                  // number of frequencies
 };
@@ -51,10 +52,6 @@ struct WinoParams {
         out[i_][j_] = acc_;                                                             \
     }
 
-template <typename T> __device__ static inline float ldx(const T *p, size_t i);
-template <> __device__ inline float ldx<float>(const float *p, size_t i) { return p[i]; }
-template <> __device__ inline float ldx<__half>(const __half *p, size_t i) { return __half2float(p[i]); }
-
 // ---- 1. input transform.  Block = 16 tiles x 16 channels.
 template <int SET, bool HALF>
 __global__ __launch_bounds__(256) void wino_input_kernel(const WinoParams w) {
@@ -71,25 +68,27 @@ __global__ __launch_bounds__(256) void wino_input_kernel(const WinoParams w) {
     }
     if (c >= w.cpad) return;
     const int tb = blockIdx.x, t = tb * 16 + t_in;
+    // The alpha x alpha patch, all loads in flight at once: elements in the zero padding, of
+    // tiles past the end and of padding channels get an out-of-range offset and read as zero.
     float d[A][A];
-#pragma unroll
-    for (int u = 0; u < A; ++u)
-#pragma unroll
-        for (int v = 0; v < A; ++v) d[u][v] = 0.f;
-    if (t < w.T && c < w.C) {
+    {
+        const bool live = t < w.T && c < w.C;
+        const int tt = live ? t : 0, cc = live ? c : 0;
         const int per = w.th * w.tw;
-        const int img = t / per, rem = t - img * per;
+        const int img = tt / per, rem = tt - img * per;
         const int ti = rem / w.tw, tj = rem - ti * w.tw;
         const int ih0 = ti * M - w.ph, iw0 = tj * M - w.pw;
-        const T *xc = static_cast<const T *>(w.x) + ((size_t)img * w.C + c) * w.H * w.W;
+        const int base = (img * w.C + cc) * w.H * w.W;
+        const __amdgpu_buffer_rsrc_t xres = make_rsrc(w.x, w.x_bytes);
 #pragma unroll
         for (int u = 0; u < A; ++u) {
             const int ih = ih0 + u;
-            const bool rok = ih >= 0 && ih < w.H;
+            const bool rok = live && (unsigned)ih < (unsigned)w.H;
 #pragma unroll
             for (int v = 0; v < A; ++v) {
                 const int iw = iw0 + v;
-                if (rok && iw >= 0 && iw < w.W) d[u][v] = ldx<T>(xc, (size_t)ih * w.W + iw);
+                const bool ok = rok && (unsigned)iw < (unsigned)w.W;
+                d[u][v] = buf_load_x<T>(xres, ok ? (uint32_t)(base + ih * w.W + iw) * (uint32_t)sizeof(T) : kOobOffset, 0u);
             }
         }
     }
@@ -270,17 +269,47 @@ __global__ __launch_bounds__(256) void wino_output_kernel(const WinoParams w) {
     const int ti = rem / w.tw, tj = rem - ti * w.tw;
     const float bv = w.bias ? w.bias[k] : 0.f;
     const size_t base = ((size_t)img * w.K + k) * w.P * w.Q;
+    // Rows of a tile are stored VW elements at a time where Q is a multiple of VW (every group
+    // of VW columns is then entirely inside the image and aligned): adjacent lanes hold
+    // adjacent tiles, so a wavefront writes contiguous runs instead of 4-byte pieces.
+    constexpr int VW = M % 4 == 0 ? 4 : 2;
+    const bool vec = w.Q % VW == 0;
 #pragma unroll
     for (int a = 0; a < M; ++a) {
         const int p = ti * M + a;
         if (p >= w.P) continue;
+        if (vec) {
 #pragma unroll
-        for (int b = 0; b < M; ++b) {
-            const int q = tj * M + b;
-            if (q >= w.Q) continue;
-            const float v = Y[a][b] + bv;
-            if (HALF) static_cast<__half *>(w.y)[base + (size_t)p * w.Q + q] = __float2half_rn(v);
-            else static_cast<float *>(w.y)[base + (size_t)p * w.Q + q] = v;
+            for (int b = 0; b < M; b += VW) {
+                const int q = tj * M + b;
+                if (q >= w.Q) continue;
+                const size_t o = base + (size_t)p * w.Q + q;
+                if constexpr (HALF) {
+                    uint32_t pk[VW / 2];
+#pragma unroll
+                    for (int i = 0; i < VW / 2; ++i) {
+                        __half2 h = __floats2half2_rn(Y[a][b + 2 * i] + bv, Y[a][b + 2 * i + 1] + bv);
+                        pk[i] = *reinterpret_cast<uint32_t *>(&h);
+                    }
+                    if constexpr (VW == 4) *reinterpret_cast<uint2 *>(static_cast<__half *>(w.y) + o) = make_uint2(pk[0], pk[1]);
+                    else *reinterpret_cast<uint32_t *>(static_cast<__half *>(w.y) + o) = pk[0];
+                } else {
+                    if constexpr (VW == 4)
+                        *reinterpret_cast<float4 *>(static_cast<float *>(w.y) + o) =
+                            make_float4(Y[a][b] + bv, Y[a][b + 1] + bv, Y[a][b + 2] + bv, Y[a][b + 3] + bv);
+                    else
+                        *reinterpret_cast<float2 *>(static_cast<float *>(w.y) + o) = make_float2(Y[a][b] + bv, Y[a][b + 1] + bv);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int b = 0; b < M; ++b) {
+                const int q = tj * M + b;
+                if (q >= w.Q) continue;
+                const float v = Y[a][b] + bv;
+                if (HALF) static_cast<__half *>(w.y)[base + (size_t)p * w.Q + q] = __float2half_rn(v);
+                else static_cast<float *>(w.y)[base + (size_t)p * w.Q + q] = v;
+            }
         }
     }
 }
@@ -378,6 +407,7 @@ hipError_t launch_wino(const Geo &g, int kind, const void *x, const void *U, con
     w.V = ws;
     w.M = reinterpret_cast<float *>(static_cast<char *>(ws) + p.v_bytes);
     w.N = g.n; w.C = g.c; w.H = g.h; w.W = g.w; w.K = g.k; w.ph = g.ph; w.pw = g.pw; w.P = g.p; w.Q = g.q;
+    w.x_bytes = (uint32_t)((size_t)g.n * g.c * g.h * g.w * (g.dtype == NNV_F16 ? 2 : 4));
     w.th = p.th; w.tw = p.tw; w.T = p.T; w.T16 = p.T16; w.K16 = p.K16; w.cpad = p.cpad; w.csteps = p.csteps;
     const int set = wino_set(kind, g.dtype);
     if (set == WS_F2) {
