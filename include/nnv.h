@@ -5,12 +5,15 @@
  * executing the kernel (e_i); its scheduler chooses, per conv layer, which
  * kernel alternative to use from the measured cost of those operations
  * (Section 3.1.1 kernel selection, Table 2, Section 3.2, Algorithm 1's
- * profiling input).  This library is the w_i and e_i of a convolution for five
- * kernel alternatives, plus the per-operation timing the selection needs.
+ * profiling input).  This library is the w_i and e_i of a convolution for six
+ * kernel alternatives, the per-operation timing the selection needs, and the
+ * on-disk cache of transformed weights that lets a cold start skip w_i
+ * (Section 3.1.2).
  *
  * All data pointers are DEVICE pointers unless a parameter says "host".  The
  * caller owns every buffer; the library allocates no device memory and keeps
- * no mutable global state.  Device buffers must be 16-byte aligned.  Work is
+ * no mutable global state (one exception, stated there: the pinned staging
+ * buffer of nnv_cache_read).  Device buffers must be 16-byte aligned.  Work is
  * enqueued on the given HIP stream (a hipStream_t passed as void*, NULL = the
  * default stream) and the call returns without waiting, except nnv_time_layer.
  * Every function returns NNV_OK (0) or a negative nnv_status; none aborts or
@@ -54,7 +57,9 @@ typedef enum {
     NNV_E_WORKSPACE = -4,   /* workspace smaller than nnv_workspace_bytes                   */
     NNV_E_ALIGN = -5,       /* a device pointer is not 16-byte aligned                      */
     NNV_E_HIP = -6,         /* a HIP call failed; text via nnv_last_hip_error               */
-    NNV_E_ARG = -7          /* bad count / reps / enum value                                */
+    NNV_E_ARG = -7,         /* bad count / reps / enum value                                */
+    NNV_E_IO = -8,          /* a cache file could not be opened, read or written (errno set) */
+    NNV_E_CACHE = -9        /* a cache file does not hold what was asked for                 */
 } nnv_status;
 
 typedef struct {
@@ -148,6 +153,47 @@ int nnv_time_layer(const nnv_conv_desc *desc, nnv_kind kind, const float *w_raw,
                    const void *x, void *y, void *workspace, size_t workspace_bytes,
                    void *flush, size_t flush_bytes, int warmup, int reps, void *hip_stream,
                    nnv_timing *out);
+
+/* ---- cache of post-transformation weights on disk (Section 3.1.2, Table 2
+ * columns "Read Raw" / "Read Cache"): the decision stage writes the transformed
+ * weights of the kinds it picked, the cold start reads them back instead of
+ * transforming.  A file of kind NNV_DIRECT holds the raw weights, so reading it
+ * and transforming is the "Read Raw + Weights Trans." alternative.
+ *
+ * File: a 4096-byte header block (magic "NNVCACHE", format version, layout
+ * version, kind, dtype, K, C, R, S, groups, payload bytes, payload checksum)
+ * followed by the nnv_transformed_bytes(desc, kind) bytes of w_tx exactly as
+ * they lie in device memory. */
+
+/* What nnv_cache_read measured. */
+typedef struct {
+    double total_ms;   /* wall clock, open to last byte in device memory            */
+    double file_ms;    /* of that, time inside the file reads                        */
+    double bytes;      /* payload bytes                                              */
+    int32_t direct_io; /* 1: read with O_DIRECT, bypassing the page cache; 0: the file
+                        * system or the kernel refused that (no O_DIRECT, or no direct
+                        * I/O into pinned memory), the file's cached pages were dropped
+                        * with posix_fadvise first and buffered reads were used       */
+} nnv_cache_io;
+
+/* Copy w_tx (device) to host and write it to `path` (host string), replacing the
+ * file.  Synchronises hip_stream first.  Errors: NULL, BAD_DESC, ARG,
+ * UNSUPPORTED, HIP, IO. */
+int nnv_cache_write(const char *path, const nnv_conv_desc *desc, nnv_kind kind, const void *w_tx,
+                    void *hip_stream);
+
+/* Read the file into w_tx (device, nnv_transformed_bytes bytes).  The header
+ * must match desc's K, C, R, S, groups and dtype, `kind` and
+ * nnv_layout_version(), else NNV_E_CACHE and w_tx is untouched; with verify != 0
+ * the payload checksum is checked as well (NNV_E_CACHE after the copy if it
+ * differs).  The file is read in 8 MiB pieces into two pinned host buffers and
+ * copied to the device on hip_stream while the next piece is read; the call
+ * returns after the last copy has finished.  The pinned buffers (16 MiB) are
+ * allocated on the first call and kept until the process ends; calls are
+ * serialised by a lock.  `io` (host, may be NULL) receives the timing.
+ * Errors: NULL, BAD_DESC, ARG, UNSUPPORTED, ALIGN, HIP, IO, CACHE. */
+int nnv_cache_read(const char *path, const nnv_conv_desc *desc, nnv_kind kind, void *w_tx, int verify,
+                   void *hip_stream, nnv_cache_io *io);
 
 #ifdef __cplusplus
 }

@@ -16,7 +16,8 @@ F32, F16 = 0, 1
 
 EXPORTS = ("nnv_layout_version", "nnv_status_string", "nnv_last_hip_error", "nnv_kind_supported",
            "nnv_transformed_bytes", "nnv_workspace_bytes", "nnv_transform_weights",
-           "nnv_transform_weights_grouped", "nnv_conv_forward", "nnv_time_layer")
+           "nnv_transform_weights_grouped", "nnv_conv_forward", "nnv_time_layer", "nnv_cache_write",
+           "nnv_cache_read")
 
 
 class NnvError(RuntimeError):
@@ -25,6 +26,8 @@ class NnvError(RuntimeError):
         text = nnv_status_string(status)
         if status == -6:
             text += ": " + nnv_last_hip_error()
+        if status == -8:
+            text += ": " + os.strerror(ctypes.get_errno())
         super().__init__(f"{where}: {text} ({status})")
 
 
@@ -36,6 +39,10 @@ class ConvDesc(Structure):
 class Timing(Structure):
     _fields_ = [(n, c_double) for n in ("transform_ms", "forward_ms", "transform_bytes", "forward_bytes",
                                         "forward_flops", "direct_equiv_flops")]
+
+
+class CacheIo(Structure):
+    _fields_ = [("total_ms", c_double), ("file_ms", c_double), ("bytes", c_double), ("direct_io", c_int32)]
 
 
 _lib = None
@@ -51,7 +58,7 @@ def load():
     if not os.path.exists(LIB_PATH):
         from .build import build
         build()
-    lib = ctypes.CDLL(LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH, use_errno=True)
     lib.nnv_layout_version.restype = c_int
     lib.nnv_status_string.restype = c_char_p
     lib.nnv_status_string.argtypes = [c_int]
@@ -73,6 +80,10 @@ def load():
     lib.nnv_time_layer.restype = c_int
     lib.nnv_time_layer.argtypes = [POINTER(ConvDesc), c_int, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                    c_size_t, c_void_p, c_size_t, c_int, c_int, c_void_p, POINTER(Timing)]
+    lib.nnv_cache_write.restype = c_int
+    lib.nnv_cache_write.argtypes = [c_char_p, POINTER(ConvDesc), c_int, c_void_p, c_void_p]
+    lib.nnv_cache_read.restype = c_int
+    lib.nnv_cache_read.argtypes = [c_char_p, POINTER(ConvDesc), c_int, c_void_p, c_int, c_void_p, POINTER(CacheIo)]
     _lib = lib
     return lib
 
@@ -159,4 +170,15 @@ def nnv_time_layer(desc: ConvDesc, kind: int, w_raw, w_tx, x, y, workspace, flus
     _check(load().nnv_time_layer(byref(desc), kind, _ptr(w_raw), _ptr(w_tx), _ptr(x), _ptr(y), _ptr(workspace),
                                  ws_bytes, _ptr(flush), fl_bytes, warmup, reps, _stream(stream), byref(out)),
            "nnv_time_layer")
+    return out
+
+
+def nnv_cache_write(path: str, desc: ConvDesc, kind: int, w_tx, stream=None) -> None:
+    _check(load().nnv_cache_write(os.fsencode(path), byref(desc), kind, _ptr(w_tx), _stream(stream)), "nnv_cache_write")
+
+
+def nnv_cache_read(path: str, desc: ConvDesc, kind: int, w_tx, verify: bool = False, stream=None) -> CacheIo:
+    out = CacheIo()
+    _check(load().nnv_cache_read(os.fsencode(path), byref(desc), kind, _ptr(w_tx), int(verify), _stream(stream),
+                                 byref(out)), "nnv_cache_read")
     return out

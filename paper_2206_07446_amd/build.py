@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libnnv.so")
-SOURCES = ("api.cpp", "transform.hip", "direct.hip", "gemm.hip", "winograd.hip")
+SOURCES = ("api.cpp", "cache.cpp", "transform.hip", "direct.hip", "gemm.hip", "winograd.hip")
 # packed-fp32 VALU instructions are switched off for every device translation unit
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -16,6 +16,11 @@ int hip_fail(hipError_t e) {
     g_hip_error = hipGetErrorString(e);
     return NNV_E_HIP;
 }
+}  // namespace
+
+int nnv::record_hip_error(hipError_t e) { return hip_fail(e); }
+
+namespace {
 
 int make_geo(const nnv_conv_desc *d, Geo *g) {
     if (!d) return NNV_E_NULL;
@@ -195,6 +200,8 @@ const char *nnv_status_string(int status) {
         case NNV_E_ALIGN: return "device pointer not 16-byte aligned";
         case NNV_E_HIP: return "HIP runtime error";
         case NNV_E_ARG: return "invalid argument";
+        case NNV_E_IO: return "cache file could not be opened, read or written";
+        case NNV_E_CACHE: return "cache file does not match the requested layer, kind or layout version";
         default: return "unknown status";
     }
 }

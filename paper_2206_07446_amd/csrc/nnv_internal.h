@@ -48,6 +48,9 @@ struct JobTable {
     int njobs;
 };
 
+// Records the text of a failed HIP call for nnv_last_hip_error and returns NNV_E_HIP.
+int record_hip_error(hipError_t e);
+
 int fill_transform_job(const Geo &g, int kind, const float *src, void *dst, TransformJob *job);
 size_t transform_job_lds_bytes(const TransformJob &job);
 hipError_t launch_transform_jobs(const JobTable &tbl, int total_blocks, size_t lds, hipStream_t st);

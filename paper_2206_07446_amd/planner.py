@@ -8,7 +8,10 @@ and whether to read raw weights and transform them or to read cached post-transf
 `nnv_transformed_bytes`: the Pareto filter and, without the paper's multi-core pipelining
 (out of scope), the per-layer minimum of
     read(raw bytes) + transform + execute      versus      read(transformed bytes) + execute
-for a given weight-read bandwidth.  `python -m paper_2206_07446_amd.planner --stack resnet18`.
+for a given weight-read bandwidth, or, with --cache-dir, for read times measured by writing
+every candidate's weights to that directory with `nnv_cache_write` and reading them back cold
+with `nnv_cache_read` (the "Read Raw" / "Read Cache" columns of Table 2).
+`python -m paper_2206_07446_amd.planner --stack resnet18`.
 """
 from __future__ import annotations
 
@@ -28,6 +31,15 @@ class Candidate:
     execute_ms: float
     raw_bytes: int
     transformed_bytes: int
+    read_raw_ms: Optional[float] = None     # measured file -> device time of the raw weights
+    read_cache_ms: Optional[float] = None   # measured file -> device time of the transformed weights
+
+    def read_ms(self, cached: bool, read_gbps: float) -> float:
+        """Measured read time if there is one, else bytes over the given bandwidth."""
+        measured = self.read_cache_ms if cached else self.read_raw_ms
+        if measured is not None:
+            return measured
+        return (self.transformed_bytes if cached else self.raw_bytes) / (read_gbps * 1e6)
 
 
 @dataclass
@@ -58,9 +70,9 @@ def choose(layer: str, cands: List[Candidate], read_gbps: float, allow_cache: bo
     """Per-layer minimum over kernel x {raw + transform, cached} of read + transform + execute."""
     best: Optional[Choice] = None
     for c in cands:
-        options = [(False, c.raw_bytes / (read_gbps * 1e6), c.transform_ms)]
+        options = [(False, c.read_ms(False, read_gbps), c.transform_ms)]
         if allow_cache:
-            options.append((True, c.transformed_bytes / (read_gbps * 1e6), 0.0))
+            options.append((True, c.read_ms(True, read_gbps), 0.0))
         for cached, read_ms, tx_ms in options:
             total = read_ms + tx_ms + c.execute_ms
             if best is None or total < best.cold_ms:
@@ -73,8 +85,16 @@ def plan(table: Dict[str, List[Candidate]], read_gbps: float, allow_cache: bool 
     return [choose(name, pareto_filter(cands), read_gbps, allow_cache) for name, cands in table.items()]
 
 
-def profile_stack(stack_name: str, dtype: int = 0, reps: int = 10, flush_mb: int = 0) -> Dict[str, List[Candidate]]:
-    """Time every applicable kind of every layer of a workload on the GPU."""
+def _median_read_ms(nnv, path, desc, kind, dst, reps=3):
+    times = sorted(nnv.nnv_cache_read(path, desc, kind, dst).total_ms for _ in range(reps))
+    return times[len(times) // 2]
+
+
+def profile_stack(stack_name: str, dtype: int = 0, reps: int = 10, flush_mb: int = 0,
+                  cache_dir: Optional[str] = None) -> Dict[str, List[Candidate]]:
+    """Time every applicable kind of every layer of a workload on the GPU; with cache_dir also
+    write each candidate's weights there and time reading them back."""
+    import os
     import torch
     from nnv_workloads import stack, layer_tensors
     from . import binding as nnv
@@ -97,7 +117,22 @@ def profile_stack(stack_name: str, dtype: int = 0, reps: int = 10, flush_mb: int
             wt = wd if kind == nnv.DIRECT else torch.empty(nb, dtype=torch.uint8, device=dev)
             ws = torch.empty(max(16, nnv.nnv_workspace_bytes(desc, kind)), dtype=torch.uint8, device=dev)
             t = nnv.nnv_time_layer(desc, kind, wd, wt, xd, y, ws, flush=flush, warmup=2, reps=reps)
-            cands.append(Candidate(KIND_NAMES[kind], t.transform_ms, t.forward_ms, layer.params * 4, nb))
+            cand = Candidate(KIND_NAMES[kind], t.transform_ms, t.forward_ms, layer.params * 4, nb)
+            if cache_dir:
+                raw_path = os.path.join(cache_dir, f"{i:02d}_raw.nnvc")
+                if kind == nnv.DIRECT:
+                    nnv.nnv_cache_write(raw_path, desc, nnv.DIRECT, wd)
+                    raw_ms = _median_read_ms(nnv, raw_path, desc, nnv.DIRECT, torch.empty_like(wd))
+                    cand.read_cache_ms = raw_ms
+                else:
+                    path = os.path.join(cache_dir, f"{i:02d}_{KIND_NAMES[kind]}.nnvc")
+                    nnv.nnv_cache_write(path, desc, kind, wt)
+                    cand.read_cache_ms = _median_read_ms(nnv, path, desc, kind, wt)
+                    os.remove(path)
+                cand.read_raw_ms = raw_ms
+            cands.append(cand)
+        if cache_dir:
+            os.remove(os.path.join(cache_dir, f"{i:02d}_raw.nnvc"))
         table[f"{i:02d}_{layer.name}"] = cands
     return table
 
@@ -113,7 +148,7 @@ def report(table: Dict[str, List[Candidate]], read_gbps: float) -> dict:
     # the plan a warm-inference engine would use: fastest execution only, weights transformed cold
     warm = [min(cands, key=lambda c: c.execute_ms) for cands in table.values()]
     out["plans"]["fastest_execution_kernel_cold"] = {
-        "cold_ms": sum(c.raw_bytes / (read_gbps * 1e6) + c.transform_ms + c.execute_ms for c in warm),
+        "cold_ms": sum(c.read_ms(False, read_gbps) + c.transform_ms + c.execute_ms for c in warm),
         "kinds": [c.kind for c in warm]}
     return out
 
@@ -125,8 +160,9 @@ def main():
     ap.add_argument("--half", action="store_true")
     ap.add_argument("--reps", type=int, default=10)
     ap.add_argument("--flush-mb", type=int, default=0)
+    ap.add_argument("--cache-dir", default=None, help="measure weight reads through cache files written here")
     args = ap.parse_args()
-    table = profile_stack(args.stack, 1 if args.half else 0, args.reps, args.flush_mb)
+    table = profile_stack(args.stack, 1 if args.half else 0, args.reps, args.flush_mb, args.cache_dir)
     print(json.dumps(report(table, args.read_gbps), indent=1))
 
 

@@ -25,7 +25,7 @@ def test_header_symbols_exported():
 def test_version_and_status_strings():
     assert nnv.nnv_layout_version() == 1
     assert nnv.nnv_status_string(0) == "ok"
-    for s in range(-7, 0):
+    for s in range(-9, 0):
         assert nnv.nnv_status_string(s) not in ("ok", "unknown status")
     assert nnv.nnv_status_string(-99) == "unknown status"
 
@@ -105,3 +105,21 @@ def test_winograd_size_ratio_unpadded():
     assert nnv.nnv_transformed_bytes(d, nnv.WINO_F4) * 9 == raw * 36
     assert nnv.nnv_transformed_bytes(d, nnv.WINO_F6) * 9 == raw * 64    # the 7.1x of the paper's 8x8-tile example
     assert nnv.nnv_transformed_bytes(d, nnv.IM2COL_GEMM) == raw
+
+
+def test_cache_argument_and_file_errors_need_no_gpu(tmp_path):
+    """The cache reader validates its arguments and the file header before it touches the device."""
+    lib = nnv.load()
+    d = D()
+    p = str(tmp_path / "w.nnvc").encode()
+    dev = ctypes.c_void_p(256)
+    assert lib.nnv_cache_read(None, ctypes.byref(d), 1, dev, 0, None, None) == -1
+    assert lib.nnv_cache_read(p, ctypes.byref(d), 9, dev, 0, None, None) == -7
+    assert lib.nnv_cache_read(p, ctypes.byref(d), 4, dev, 0, None, None) == -3
+    assert lib.nnv_cache_read(p, ctypes.byref(d), 1, ctypes.c_void_p(260), 0, None, None) == -5
+    assert lib.nnv_cache_read(p, ctypes.byref(d), 1, dev, 0, None, None) == -8          # no such file
+    assert lib.nnv_cache_write(None, ctypes.byref(d), 1, dev, None) == -1
+    open(p, "wb").write(b"short")
+    assert lib.nnv_cache_read(p, ctypes.byref(d), 1, dev, 0, None, None) == -9          # no header block
+    open(p, "wb").write(b"\0" * 8192)
+    assert lib.nnv_cache_read(p, ctypes.byref(d), 1, dev, 0, None, None) == -9          # wrong magic

@@ -46,3 +46,15 @@ def test_plan_and_report_shapes():
     assert rep["plans"]["fastest_execution_kernel_cold"]["kinds"][0] == "wino_f4"
     assert rep["plans"]["fastest_execution_kernel_cold"]["cold_ms"] > rep["plans"]["raw_only"]["cold_ms"]
     assert any(not c["kept"] for c in rep["layers"]["l0"])
+
+
+def test_measured_read_times_replace_the_bandwidth_model():
+    """With Table 2's own read columns (0.70 ms raw, 5.23 ms cached Winograd) the cached Winograd
+    kernel wins (5.23 + 2.98) over raw direct (0.70 + 8.01), whatever bandwidth is passed."""
+    raw = 442368
+    cands = [Candidate("wino_f4", 38.23, 2.98, raw, int(raw * 64 / 9), read_raw_ms=0.70, read_cache_ms=5.23),
+             Candidate("direct", 0.0, 8.01, raw, raw, read_raw_ms=0.70, read_cache_ms=0.70)]
+    c = choose("l", cands, read_gbps=1e-6, allow_cache=True)
+    assert c.kind == "wino_f4" and c.cached and abs(c.cold_ms - 8.21) < 1e-9 and c.read_ms == 5.23
+    c = choose("l", cands, read_gbps=1e-6, allow_cache=False)
+    assert c.kind == "direct" and abs(c.cold_ms - 8.71) < 1e-9
