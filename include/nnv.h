@@ -154,6 +154,26 @@ int nnv_time_layer(const nnv_conv_desc *desc, nnv_kind kind, const float *w_raw,
                    void *flush, size_t flush_bytes, int warmup, int reps, void *hip_stream,
                    nnv_timing *out);
 
+/* Cold pass over a list of layers with the two operations pipelined (Section 3.1.3:
+ * the transformation of later layers overlaps the execution of earlier ones, layer
+ * by layer).  The layers are cut into stages of `stage_layers` consecutive layers
+ * (<= 0: one stage holding all).  Each stage's weights are transformed in one grouped
+ * launch on stream_tx; each layer's convolution runs on stream_exec once its stage
+ * is transformed.  With stream_tx == stream_exec the same launches are issued in
+ * the same order on one stream: the unpipelined baseline.
+ *   descs, kinds, w_raw, w_tx, x, y : HOST arrays of length n_layers (descriptors,
+ *       kinds, device pointers); bias is not applied
+ *   workspace : device, >= the largest nnv_workspace_bytes of the list, shared by
+ *       all layers (their convolutions are serialised on stream_exec)
+ * stream_tx first waits for the work already queued on stream_exec, and stream_exec
+ * ends up waiting for everything issued on stream_tx, so the call may be captured
+ * into a HIP graph from stream_exec; work the caller queues on either stream
+ * afterwards is ordered after the whole pass.  Returns without waiting.
+ * Errors: NULL, BAD_DESC, ARG, UNSUPPORTED, WORKSPACE, ALIGN, HIP. */
+int nnv_cold_stack(int n_layers, const nnv_conv_desc *descs, const nnv_kind *kinds, const float *const *w_raw,
+                   void *const *w_tx, const void *const *x, void *const *y, void *workspace,
+                   size_t workspace_bytes, int stage_layers, void *stream_exec, void *stream_tx);
+
 /* ---- cache of post-transformation weights on disk (Section 3.1.2, Table 2
  * columns "Read Raw" / "Read Cache"): the decision stage writes the transformed
  * weights of the kinds it picked, the cold start reads them back instead of

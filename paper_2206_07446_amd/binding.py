@@ -16,7 +16,7 @@ F32, F16 = 0, 1
 
 EXPORTS = ("nnv_layout_version", "nnv_status_string", "nnv_last_hip_error", "nnv_kind_supported",
            "nnv_transformed_bytes", "nnv_workspace_bytes", "nnv_transform_weights",
-           "nnv_transform_weights_grouped", "nnv_conv_forward", "nnv_time_layer", "nnv_cache_write",
+           "nnv_transform_weights_grouped", "nnv_conv_forward", "nnv_time_layer", "nnv_cold_stack", "nnv_cache_write",
            "nnv_cache_read")
 
 
@@ -80,6 +80,9 @@ def load():
     lib.nnv_time_layer.restype = c_int
     lib.nnv_time_layer.argtypes = [POINTER(ConvDesc), c_int, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                    c_size_t, c_void_p, c_size_t, c_int, c_int, c_void_p, POINTER(Timing)]
+    lib.nnv_cold_stack.restype = c_int
+    lib.nnv_cold_stack.argtypes = [c_int, POINTER(ConvDesc), POINTER(c_int), POINTER(c_void_p), POINTER(c_void_p),
+                                   POINTER(c_void_p), POINTER(c_void_p), c_void_p, c_size_t, c_int, c_void_p, c_void_p]
     lib.nnv_cache_write.restype = c_int
     lib.nnv_cache_write.argtypes = [c_char_p, POINTER(ConvDesc), c_int, c_void_p, c_void_p]
     lib.nnv_cache_read.restype = c_int
@@ -182,3 +185,14 @@ def nnv_cache_read(path: str, desc: ConvDesc, kind: int, w_tx, verify: bool = Fa
     _check(load().nnv_cache_read(os.fsencode(path), byref(desc), kind, _ptr(w_tx), int(verify), _stream(stream),
                                  byref(out)), "nnv_cache_read")
     return out
+
+
+def nnv_cold_stack(descs, kinds, w_raw, w_tx, x, y, workspace, stage_layers=1, stream_exec=None, stream_tx=None) -> None:
+    """stream_tx=None runs both operations on stream_exec (the unpipelined order)."""
+    n = len(descs)
+    arr = lambda ts: (c_void_p * n)(*[t if isinstance(t, int) else t.data_ptr() for t in ts])
+    se = _stream(stream_exec)
+    stx = se if stream_tx is None else _stream(stream_tx)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().nnv_cold_stack(n, (ConvDesc * n)(*descs), (c_int * n)(*kinds), arr(w_raw), arr(w_tx), arr(x), arr(y),
+                                 _ptr(workspace), ws_bytes, stage_layers, se, stx), "nnv_cold_stack")

@@ -248,6 +248,68 @@ int nnv_conv_forward(const nnv_conv_desc *desc, nnv_kind kind, const void *x, co
     return forward_checked(g, kind, x, w_tx, bias, y, workspace, static_cast<hipStream_t>(hip_stream));
 }
 
+int nnv_cold_stack(int n_layers, const nnv_conv_desc *descs, const nnv_kind *kinds, const float *const *w_raw,
+                   void *const *w_tx, const void *const *x, void *const *y, void *workspace, size_t workspace_bytes,
+                   int stage_layers, void *stream_exec, void *stream_tx) {
+    if (n_layers < 0) return NNV_E_ARG;
+    if (n_layers == 0) return NNV_OK;
+    if (!descs || !kinds || !w_raw || !w_tx || !x || !y) return NNV_E_NULL;
+    // validate everything before the first launch
+    std::vector<Geo> geos(n_layers);
+    for (int i = 0; i < n_layers; ++i) {
+        int rc = forward_args(&descs[i], kinds[i], x[i], w_tx[i], nullptr, y[i], workspace, workspace_bytes, &geos[i]);
+        if (rc) return rc;
+        if (!w_raw[i]) return NNV_E_NULL;
+        if (misaligned(w_raw[i])) return NNV_E_ALIGN;
+    }
+    hipStream_t se = static_cast<hipStream_t>(stream_exec), stx = static_cast<hipStream_t>(stream_tx);
+    const bool two = se != stx;
+    const int per = stage_layers <= 0 ? n_layers : stage_layers;
+    const int stages = (n_layers + per - 1) / per;
+    std::vector<hipEvent_t> ev;     // [0]: fork, [1 + s]: stage s transformed
+    auto cleanup = [&]() { for (hipEvent_t e : ev) (void)hipEventDestroy(e); };
+    auto fail = [&](hipError_t e) { cleanup(); return hip_fail(e); };
+    hipError_t e;
+    if (two) {
+        ev.reserve(stages + 1);
+        for (int i = 0; i < stages + 1; ++i) {
+            hipEvent_t h;
+            e = hipEventCreateWithFlags(&h, hipEventDisableTiming);
+            if (e != hipSuccess) return fail(e);
+            ev.push_back(h);
+        }
+        e = hipEventRecord(ev[0], se);
+        if (e == hipSuccess) e = hipStreamWaitEvent(stx, ev[0], 0);
+        if (e != hipSuccess) return fail(e);
+    }
+    // Stage s + 1 is handed to stream_tx before the convolutions of stage s are handed to
+    // stream_exec, so the host never holds the transformation stream back.
+    auto issue_tx = [&](int s) -> int {
+        const int b = s * per, n = std::min(per, n_layers - b);
+        int rc = transform_many(n, descs + b, kinds + b, w_raw + b, w_tx + b, stx);
+        if (rc) return rc;
+        if (two) {
+            hipError_t er = hipEventRecord(ev[1 + s], stx);
+            if (er != hipSuccess) return hip_fail(er);
+        }
+        return NNV_OK;
+    };
+    int rc = issue_tx(0);
+    for (int s = 0; s < stages && rc == NNV_OK; ++s) {
+        if (s + 1 < stages) rc = issue_tx(s + 1);
+        if (rc) break;
+        if (two) {
+            e = hipStreamWaitEvent(se, ev[1 + s], 0);
+            if (e != hipSuccess) { rc = hip_fail(e); break; }
+        }
+        const int b = s * per, n = std::min(per, n_layers - b);
+        for (int i = b; i < b + n && rc == NNV_OK; ++i)
+            rc = forward_checked(geos[i], kinds[i], x[i], w_tx[i], nullptr, y[i], workspace, se);
+    }
+    cleanup();
+    return rc;
+}
+
 int nnv_time_layer(const nnv_conv_desc *desc, nnv_kind kind, const float *w_raw, void *w_tx, const void *x, void *y,
                    void *workspace, size_t workspace_bytes, void *flush, size_t flush_bytes, int warmup, int reps,
                    void *hip_stream, nnv_timing *out) {

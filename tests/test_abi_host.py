@@ -123,3 +123,10 @@ def test_cache_argument_and_file_errors_need_no_gpu(tmp_path):
     assert lib.nnv_cache_read(p, ctypes.byref(d), 1, dev, 0, None, None) == -9          # no header block
     open(p, "wb").write(b"\0" * 8192)
     assert lib.nnv_cache_read(p, ctypes.byref(d), 1, dev, 0, None, None) == -9          # wrong magic
+
+
+def test_cold_stack_argument_errors_need_no_gpu():
+    lib = nnv.load()
+    assert lib.nnv_cold_stack(-1, None, None, None, None, None, None, None, 0, 1, None, None) == -7
+    assert lib.nnv_cold_stack(0, None, None, None, None, None, None, None, 0, 1, None, None) == 0
+    assert lib.nnv_cold_stack(1, None, None, None, None, None, None, None, 0, 1, None, None) == -1
