@@ -92,6 +92,77 @@ def cpu_baseline(layers, nnv, budget_s=12.0):
                       f"convolution uses all cores, the numpy transforms and reference Winograd one"}
 
 
+def graph_ms(torch, np, side, fn, reps=10):
+    """Mean time of fn's launches, captured once on `side` into a HIP graph and replayed."""
+    with torch.cuda.stream(side):
+        fn()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        fn()
+    g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ts = []
+    for _ in range(reps):
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1))
+    return float(np.mean(ts))
+
+
+def beyond_the_step(nnv, torch, np, layers, pairs, ws, side):
+    """Measurements outside the timed step, same stack and method (graph replay): the F(6x6)
+    Winograd kind, the whole cold pass of one kernel plan through nnv_cold_stack (one grouped
+    transformation then execution, versus two-layer stages pipelined on a second stream), and
+    the file-to-device rate of the transformed-weight cache."""
+    import tempfile
+    dev = ws.device
+    out = {}
+    # F(6x6,3x3) on the 13 eligible layers
+    f6 = [Pair(nnv, torch, p.layer, nnv.WINO_F6, p.w_raw, p.x, dev) for p in pairs if p.kind == nnv.WINO_F4]
+    ws6 = torch.empty(max(q.ws_bytes for q in f6), dtype=torch.uint8, device=dev)
+    t_tx = graph_ms(torch, np, side, lambda: nnv.nnv_transform_weights_grouped(
+        [q.desc for q in f6], [q.kind for q in f6], [q.w_raw for q in f6], [q.w_tx for q in f6]))
+
+    def f6_forward():
+        for q in f6:
+            nnv.nnv_conv_forward(q.desc, q.kind, q.x, q.w_tx, None, q.y, ws6, ws6.numel())
+    t_fw = graph_ms(torch, np, side, f6_forward)
+    out["wino_f6"] = {"layers": len(f6), "transform_ms": round(t_tx, 4), "forward_ms": round(t_fw, 4),
+                      "transform_GBps": round(sum(q.transform_bytes for q in f6) / (t_tx * 1e-3) / 1e9, 1),
+                      "TFLOPs_direct_equivalent": round(sum(q.direct_flops for q in f6) / (t_fw * 1e-3) / 1e12, 3)}
+    # cold pass of the im2col-GEMM plan (every layer) through nnv_cold_stack
+    plan = [p for p in pairs if p.kind == nnv.IM2COL_GEMM]
+    tx_stream = torch.cuda.Stream()
+    args = ([p.desc for p in plan], [p.kind for p in plan], [p.w_raw for p in plan], [p.w_tx for p in plan],
+            [p.x for p in plan], [p.y for p in plan], ws)
+    out["cold_pass_im2col_plan"] = {
+        "one_grouped_transform_then_execute_ms": round(graph_ms(torch, np, side, lambda: nnv.nnv_cold_stack(
+            *args, stage_layers=0, stream_exec=side)), 4),
+        "stages_of_2_layers_one_stream_ms": round(graph_ms(torch, np, side, lambda: nnv.nnv_cold_stack(
+            *args, stage_layers=2, stream_exec=side)), 4),
+        "stages_of_2_layers_pipelined_on_two_streams_ms": round(graph_ms(torch, np, side, lambda: nnv.nnv_cold_stack(
+            *args, stage_layers=2, stream_exec=side, stream_tx=tx_stream)), 4)}
+    # transformed-weight cache: largest F(4x4) tensor of the stack, file -> device
+    big = max((p for p in pairs if p.kind == nnv.WINO_F4), key=lambda p: p.tx_bytes)
+    try:
+        with tempfile.TemporaryDirectory() as d:
+            path = os.path.join(d, "w.nnvc")
+            nnv.nnv_cache_write(path, big.desc, big.kind, big.w_tx)
+            ios = [nnv.nnv_cache_read(path, big.desc, big.kind, big.w_tx) for _ in range(3)]
+        io = sorted(ios, key=lambda r: r.total_ms)[1]
+        out["cache_read"] = {"bytes": int(io.bytes), "total_ms": round(io.total_ms, 3), "file_ms": round(io.file_ms, 3),
+                             "GBps": round(io.bytes / (io.total_ms * 1e-3) / 1e9, 2), "direct_io": bool(io.direct_io)}
+    except (OSError, nnv.NnvError) as e:
+        if isinstance(e, nnv.NnvError) and e.status != -8:
+            raise
+        out["cache_read"] = None      # no writable temporary directory
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -245,6 +316,7 @@ def main():
         "roofline": roofline,
         "roofline_all": roof_all,
     }
+    out["beyond_the_step"] = beyond_the_step(nnv, torch, np, layers, pairs, ws, side)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layers, nnv)
     print(json.dumps(out))
