@@ -271,7 +271,7 @@ def main():
 
     # Roofline entries per kernel class, from the event-bracketed phase times of the timed region
     # (phase time / launches of the phase = average launch duration incl. the gaps inside a graph).
-    # transform: two launches of transform_kernel carry the 46 jobs (DIRECT aliases the raw weights).
+    # transform: one launch of transform_kernel carries the 46 jobs (DIRECT aliases the raw weights).
     def entry(kernel, bound, work, unit_scale, peak, unit, ms, launches):
         ach = work / (ms * 1e-3) / unit_scale
         return {"kernel": kernel, "bound": bound, "achieved": round(ach, 2), "peak": peak, "unit": unit,
@@ -280,7 +280,7 @@ def main():
 
     per_kind, roof_all = {}, []
     roof_all.append(entry("transform_kernel (grouped weight transformation, all kinds)", "hbm", tx_bytes, 1e9,
-                          HBM_PEAK_GBPS, "GB/s", tx_ms, 2))
+                          HBM_PEAK_GBPS, "GB/s", tx_ms, 1))
     for kind, kname in names.items():
         sel = [p for p in pairs if p.kind == kind]
         ms = phase_ms[kname]

@@ -42,11 +42,12 @@ struct TransformJob {
     int block0;      // first block of this job in the launch
     int nblocks;
 };
-constexpr int kMaxJobs = 40;
+constexpr int kMaxJobs = 64;   // 64 jobs of 56 bytes: the table still fits the 4 KB of kernel arguments
 struct JobTable {
     TransformJob job[kMaxJobs];
     int njobs;
 };
+static_assert(sizeof(JobTable) <= 4096, "the job table is passed by value as the kernel argument");
 
 // Records the text of a failed HIP call for nnv_last_hip_error and returns NNV_E_HIP.
 int record_hip_error(hipError_t e);

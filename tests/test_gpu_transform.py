@@ -146,7 +146,7 @@ def test_grouped_transform_matches_single(env):
     for a, b, layer in zip(singles, dsts, layers):
         assert torch.equal(a, b), layer.name
     # more layers than one launch carries
-    many = 45
+    many = 70
     layer = L(16, 16)
     desc = nnv.make_desc(layer, nnv.F32)
     w = torch.from_numpy(layer_tensors(layer, 3)[0]).to(dev)
