@@ -53,6 +53,12 @@ __device__ static inline void stage_rows(const float *__restrict__ src, float *l
     __syncthreads();
 }
 
+// Transformed weights are written once and not read again by this kernel: non-temporal stores
+// keep them from displacing the raw weights (which several jobs of a launch share) in L2.
+typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
+typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
+template <typename V> __device__ static inline void nt_store(V *p, V v) { __builtin_nontemporal_store(v, p); }
+
 // U = G g G^T for one 3x3 filter held in registers.
 template <int SET>
 __device__ static inline void wino_u(const float g[9], float u[WinoMat<SET>::A * WinoMat<SET>::A]) {
@@ -113,7 +119,7 @@ __device__ static inline void wino_block(const TransformJob &job, int local_bloc
             float *o = dst + ((size_t)kb * cpad + c0 + cl) * 16 + k_in;
             const size_t xi_stride = (size_t)K16 * cpad * 16;
 #pragma unroll
-            for (int xi = 0; xi < AA; ++xi) o[xi * xi_stride] = u[xi];
+            for (int xi = 0; xi < AA; ++xi) nt_store(&o[xi * xi_stride], u[xi]);
         }
     } else {
         __half *dst = static_cast<__half *>(job.dst);
@@ -144,7 +150,7 @@ __device__ static inline void wino_block(const TransformJob &job, int local_bloc
             const size_t xi_stride = (size_t)K16 * c32n * 512;
 #pragma unroll
             for (int xi = 0; xi < AA; ++xi)
-                *reinterpret_cast<uint2 *>(o + xi * xi_stride) = make_uint2(lo[xi], hi[xi]);
+                nt_store(reinterpret_cast<uint2v *>(o + xi * xi_stride), uint2v{lo[xi], hi[xi]});
         }
     }
 }
@@ -169,7 +175,7 @@ __device__ static inline void gemm_block(const TransformJob &job, int local_bloc
         while (rs >= RS) { rs -= RS; ++cb; }
         for (int f = wave; f < nfrag; f += 4) {
             const float v = lds[k_in * ROW + (cb * 4 + grp) * RS + rs];
-            dst[(size_t)f * 64 + lane] = v;
+            nt_store(&dst[(size_t)f * 64 + lane], v);
             rs += 4;
             while (rs >= RS) { rs -= RS; ++cb; }
         }
@@ -185,7 +191,7 @@ __device__ static inline void gemm_block(const TransformJob &job, int local_bloc
             v.y = pack_half2(lp[2 * RS], lp[3 * RS]);
             v.z = pack_half2(lp[4 * RS], lp[5 * RS]);
             v.w = pack_half2(lp[6 * RS], lp[7 * RS]);
-            *reinterpret_cast<uint4 *>(dst + (size_t)f * 512 + lane * 8) = v;
+            nt_store(reinterpret_cast<uint4v *>(dst + (size_t)f * 512 + lane * 8), uint4v{v.x, v.y, v.z, v.w});
             rs += 4;
             while (rs >= RS) { rs -= RS; ++cb; }
         }
