@@ -52,7 +52,8 @@ struct WinoParams {
         out[i_][j_] = acc_;                                                             \
     }
 
-// ---- 1. input transform.  Block = 16 tiles x 16 channels.
+// ---- 1. input transform.  Block = 16 tiles x 16 channels (float32: x blockDim/16 channels, so
+// that small layers can be spread over more, smaller workgroups).
 template <int SET, bool HALF>
 __global__ __launch_bounds__(256) void wino_input_kernel(const WinoParams w) {
     using Wm = WinoMat<SET>;
@@ -64,7 +65,7 @@ __global__ __launch_bounds__(256) void wino_input_kernel(const WinoParams w) {
         c = blockIdx.y * 16 + (threadIdx.x >> 7) * 8 + (threadIdx.x & 7);
     } else {      // lanes: 16 tiles fastest, then channels -> 256 B contiguous stores
         t_in = threadIdx.x & 15;
-        c = blockIdx.y * 16 + (threadIdx.x >> 4);
+        c = (blockIdx.y * blockDim.x + threadIdx.x) >> 4;
     }
     if (c >= w.cpad) return;
     const int tb = blockIdx.x, t = tb * 16 + t_in;
@@ -245,14 +246,15 @@ __global__ __launch_bounds__(1024) void wino_gemm_kernel(const WinoParams w) {
     }
 }
 
-// ---- 3. output transform.  Block = 16 tiles x 16 output channels.
+// ---- 3. output transform.  Block = 16 tiles x blockDim/16 output channels.
 template <int SET, bool HALF>
 __global__ __launch_bounds__(256) void wino_output_kernel(const WinoParams w) {
     using Wm = WinoMat<SET>;
     constexpr int A = Wm::A, M = Wm::M;
-    const int t_in = threadIdx.x & 15, k_in = threadIdx.x >> 4;
-    const int tb = blockIdx.x, kb = blockIdx.y;
-    const int t = tb * 16 + t_in, k = kb * 16 + k_in;
+    const int t_in = threadIdx.x & 15;
+    const int tb = blockIdx.x;
+    const int k = (blockIdx.y * blockDim.x + threadIdx.x) >> 4, kb = k >> 4, k_in = k & 15;
+    const int t = tb * 16 + t_in;
     if (t >= w.T || k >= w.K) return;
     const float *mp = w.M + ((size_t)kb * w.T16 + tb) * 256 + k_in * 16 + t_in;
     const size_t xs = (size_t)w.K16 * w.T16 * 256;
@@ -348,8 +350,11 @@ size_t wino_workspace_bytes(const Geo &g, int kind) {
 template <int SET, bool HALF>
 static hipError_t launch_wino_t(const Geo &g, const WinoPlan &p, WinoParams &w, hipStream_t st) {
     {
-        dim3 grid(p.T16, ceil_div(p.cpad, 16), 1);
-        hipLaunchKernelGGL((wino_input_kernel<SET, HALF>), grid, dim3(256), 0, st, w);
+        // one wavefront per workgroup (16 tiles x 4 channels) while that keeps the launch small:
+        // a batch-1 layer then occupies four times as many CUs
+        const int bt = (!HALF && (long)p.T16 * ceil_div(p.cpad, 16) < 4096) ? 64 : 256;
+        dim3 grid(p.T16, HALF ? ceil_div(p.cpad, 16) : ceil_div(p.cpad * 16, bt), 1);
+        hipLaunchKernelGGL((wino_input_kernel<SET, HALF>), grid, dim3(bt), 0, st, w);
     }
     {
         // wavefront tile, channel split and workgroup shape: cover >= 1024 wavefronts if possible
@@ -392,8 +397,9 @@ static hipError_t launch_wino_t(const Geo &g, const WinoPlan &p, WinoParams &w, 
         }
     }
     {
-        dim3 grid(p.T16, p.K16, 1);
-        hipLaunchKernelGGL((wino_output_kernel<SET, HALF>), grid, dim3(256), 0, st, w);
+        const int bt = (long)p.T16 * p.K16 < 4096 ? 64 : 256;
+        dim3 grid(p.T16, p.K16 * (256 / bt), 1);
+        hipLaunchKernelGGL((wino_output_kernel<SET, HALF>), grid, dim3(bt), 0, st, w);
     }
     return hipGetLastError();
 }
