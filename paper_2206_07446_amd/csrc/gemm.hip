@@ -383,7 +383,7 @@ hipError_t launch_im2col(const Geo &g, const void *x, const void *w, const float
         gp.x = xt;
     }
     const int KS = 1 << pl.ks_shift;
-    const int waves = KS < 4 ? 4 : KS;
+    const int waves = KS;
     const int tiles_per_wg = waves / KS;
     const int npix16 = ceil_div(gp.npix, 16);
     gp.grid_nx = ceil_div(ceil_div(npix16, pl.tn), tiles_per_wg);

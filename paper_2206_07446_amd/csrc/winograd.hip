@@ -374,7 +374,7 @@ static hipError_t launch_wino_t(const Geo &g, const WinoPlan &p, WinoParams &w, 
         w.u_bytes = (uint32_t)((size_t)aa * p.K16 * p.csteps * 64 * (HALF ? 16 : 4));
         w.v_bytes = (uint32_t)((size_t)aa * p.T16 * p.csteps * 64 * (HALF ? 16 : 4));
         const int KS = 1 << shift;
-        const int waves = KS < 4 ? 4 : KS;
+        const int waves = KS;
         const int tiles_per_wg = waves / KS;
         const long ntiles = (long)ceil_div(p.K16, tm) * w.ntb;
         w.gemm_wgs_per_xi = ceil_div((int)ntiles, tiles_per_wg);
