@@ -24,6 +24,27 @@ HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E
 MFMA_F32_PEAK_TFLOPS = 157.3  # dense float32 matrix-core peak
 VALU_F32_PEAK_TFLOPS = 157.3  # float32 vector peak (packed FMA; plain FMA, as compiled here, tops out at 78.6)
 
+# HBM bytes per step and kernel class, (read MB, written MB), from the two `rocprofv3 --pmc` runs of
+# `bench.py --counter-pass` summarised in profiles/bench_resnet18_hbm_traffic.md (counter values scaled
+# by what the same counters read for the plain copy kernel).  They describe the kernel sources with
+# the digest below; once a source file changes, `traffic` is reported as null until the counters
+# are taken again.
+MEASURED_TRAFFIC = {
+    "csrc_sha256_16": "6ba09ed396f819ee",
+    "MB_per_step": {"transform_kernel": (78.6, 262.8), "direct_conv_slane_kernel": (137.0, 10.0),
+                    "im2col_gemm_kernel": (84.7, 10.0)},
+}
+
+
+def csrc_digest():
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2206_07446_amd", "csrc", "*"))):
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
 
 def applicable_kinds(nnv, layer):
     kinds = [nnv.DIRECT]
@@ -169,6 +190,9 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--step-only", action="store_true",
+                    help="only the timed step: no measurements beside it and no CPU baseline (the command profiled "
+                         "under rocprofv3 --kernel-trace --stats)")
     ap.add_argument("--counter-pass", action="store_true",
                     help="run every kernel of the step a few times eagerly plus a plain 256 MiB copy, nothing timed: "
                          "the program to put under `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`")
@@ -272,10 +296,17 @@ def main():
     # Roofline entries per kernel class, from the event-bracketed phase times of the timed region
     # (phase time / launches of the phase = average launch duration incl. the gaps inside a graph).
     # transform: one launch of transform_kernel carries the 46 jobs (DIRECT aliases the raw weights).
+    counters_valid = csrc_digest() == MEASURED_TRAFFIC["csrc_sha256_16"]
+
     def entry(kernel, bound, work, unit_scale, peak, unit, ms, launches):
         ach = work / (ms * 1e-3) / unit_scale
+        mb = MEASURED_TRAFFIC["MB_per_step"].get(kernel.split(" ")[0]) if counters_valid else None
+        # HBM bytes per launch (read + written), counters scaled as described at MEASURED_TRAFFIC
+        traffic = None if mb is None else round((mb[0] + mb[1]) * 1e6 / launches)
         return {"kernel": kernel, "bound": bound, "achieved": round(ach, 2), "peak": peak, "unit": unit,
-                "frac": round(ach / peak, 4), "traffic": None, "launches_per_step": launches,
+                "frac": round(ach / peak, 4), "traffic": traffic,
+                "traffic_read_written": None if mb is None else [round(mb[0] * 1e6 / launches), round(mb[1] * 1e6 / launches)],
+                "launches_per_step": launches,
                 "avg_launch_us": round(ms * 1e3 / launches, 2), "phase_ms": round(ms, 4)}
 
     per_kind, roof_all = {}, []
@@ -316,8 +347,9 @@ def main():
         "roofline": roofline,
         "roofline_all": roof_all,
     }
-    out["beyond_the_step"] = beyond_the_step(nnv, torch, np, layers, pairs, ws, side)
-    if not args.no_cpu_baseline:
+    if not args.step_only:
+        out["beyond_the_step"] = beyond_the_step(nnv, torch, np, layers, pairs, ws, side)
+    if not (args.no_cpu_baseline or args.step_only):
         out["cpu_baseline"] = cpu_baseline(layers, nnv)
     print(json.dumps(out))
 

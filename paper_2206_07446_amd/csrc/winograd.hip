@@ -363,7 +363,7 @@ static hipError_t launch_wino_t(const Geo &g, const WinoPlan &p, WinoParams &w, 
         // tile that still leaves >= 768 wavefronts; then split the channel steps over the
         // wavefronts of a workgroup towards ~4 per SIMD, keeping >= 16 steps each
         int tm = 1, tn = 1;
-        if (aa * ceil_div(p.K16, 2) * ceil_div(p.T16, 2) >= 768) { tm = 2; tn = 2; }
+        if (p.T16 >= 2 && aa * ceil_div(p.K16, 2) * ceil_div(p.T16, 2) >= 768) { tm = 2; tn = 2; }
         else if (aa * ceil_div(p.K16, 2) * p.T16 >= 768) { tm = 2; }
         int shift = 0;
         const long tiles = (long)ceil_div(p.K16, tm) * ceil_div(p.T16, tn);
