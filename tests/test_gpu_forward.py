@@ -68,6 +68,10 @@ SMALL = [
     Ly("dw_s2", 48, 15, 15, 48, 3, 2, 1, groups=48),
     Ly("dw_n2", 5, 7, 7, 5, 3, 1, 1, groups=5, n=2),
     Ly("grp2", 8, 9, 9, 12, 3, 1, 1, groups=2),
+    Ly("batch3", 20, 11, 13, 40, 3, 1, 1, n=3),
+    Ly("batch3_pw", 24, 9, 7, 72, 1, 1, 0, n=3),
+    Ly("batch2_s2", 16, 17, 15, 24, 3, 2, 1, n=2),
+    Ly("batch5_deep", 128, 7, 7, 64, 3, 1, 1, n=5),
 ]
 CASES = [(l, k, h) for h in (False, True) for l in SMALL for k in applicable_kinds(l, h)]
 
