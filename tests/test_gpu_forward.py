@@ -203,3 +203,35 @@ def test_time_layer(env):
     # aliasing direct transform costs nothing
     t = nnv.nnv_time_layer(desc, 0, wd, wd, xd, y, None, warmup=0, reps=2)
     assert t.transform_ms == 0 and t.transform_bytes == 0
+
+
+def _random_layers(count, seed):
+    """Seeded random small layers: odd sizes, channel counts off every block multiple, all filter
+    sizes the kernels special-case, grouped and depthwise ones."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        r = int(rng.choice([1, 3, 3, 3, 5, 7]))
+        stride = int(rng.choice([1, 1, 2]))
+        pad = int(rng.integers(0, r // 2 + 2))
+        h, w = int(rng.integers(max(r - 2 * pad, 1), 21)), int(rng.integers(max(r - 2 * pad, 1), 21))
+        n = int(rng.choice([1, 1, 2, 3]))
+        mode = rng.choice(["plain", "plain", "plain", "grouped", "depthwise"])
+        if mode == "depthwise":
+            c = k = g = int(rng.integers(1, 70))
+            r, pad = 3, 1
+        elif mode == "grouped":
+            g = int(rng.choice([2, 3, 4]))
+            c, k = g * int(rng.integers(1, 12)), g * int(rng.integers(1, 12))
+        else:
+            g, c, k = 1, int(rng.integers(1, 70)), int(rng.integers(1, 70))
+        out.append(Ly(f"rnd{len(out)}", c, h, w, k, r, stride, pad, groups=g, n=n))
+    return out
+
+
+def test_random_small_layers(env):
+    """60 seeded random layers through every applicable kind, float32 and float16 alternating."""
+    for i, layer in enumerate(_random_layers(60, 9)):
+        half = bool(i % 2)
+        for kind in applicable_kinds(layer, half):
+            check(env, layer, kind, half, seed=500 + i)
