@@ -1,0 +1,99 @@
+"""Per-layer roofline table of a workload: for every layer and every kernel kind that can run it,
+the forward time, the algorithmic bytes and executed flops, the roofline bound
+max(bytes / HBM peak, flops / compute peak), which side sets it, and bound / time.
+
+Times come from HIP graph replays of repeated launches of one layer (kernel time plus the
+gap between two kernels of a graph), the weight transformation from `nnv_time_layer`.
+`python -m paper_2206_07446_amd.layer_report --stack resnet18 > table.md`
+"""
+from __future__ import annotations
+
+import argparse
+
+HBM_PEAK = 8.0e12            # bytes/s
+MFMA_F32_PEAK = 157.3e12     # flop/s, float32 matrix cores
+MFMA_F16_PEAK = 2.5e15       # flop/s, float16 matrix cores
+VALU_F32_PEAK = 157.3e12     # flop/s, float32 vector ALU
+
+KIND_NAMES = {0: "direct", 1: "im2col_gemm", 2: "wino_f2", 3: "wino_f4", 4: "depthwise", 5: "wino_f6"}
+
+
+def forward_us(nnv, torch, desc, kind, x, w_tx, y, ws, reps=20):
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        for _ in range(3):
+            nnv.nnv_conv_forward(desc, kind, x, w_tx, None, y, ws)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        for _ in range(reps):
+            nnv.nnv_conv_forward(desc, kind, x, w_tx, None, y, ws)
+    g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    best = float("inf")
+    for _ in range(5):
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        best = min(best, e0.elapsed_time(e1) * 1e3 / reps)
+    return best
+
+
+def rows(stack_name: str, half: bool):
+    import torch
+    from nnv_workloads import stack, layer_tensors
+    from . import binding as nnv
+    dev = torch.device("cuda:0")
+    dtype = nnv.F16 if half else nnv.F32
+    for i, layer in enumerate(stack(stack_name)):
+        desc = nnv.make_desc(layer, dtype)
+        w, x = layer_tensors(layer, 220607446 + i)
+        wd, xd = torch.from_numpy(w).to(dev), torch.from_numpy(x).to(dev)
+        if half:
+            xd = xd.half()
+        y = torch.empty(layer.n * layer.k * layer.p * layer.q, dtype=xd.dtype, device=dev)
+        for kind in range(6):
+            if not nnv.nnv_kind_supported(desc, kind):
+                continue
+            nb = nnv.nnv_transformed_bytes(desc, kind)
+            wt = wd if kind == nnv.DIRECT else torch.empty(nb, dtype=torch.uint8, device=dev)
+            ws = torch.empty(max(16, nnv.nnv_workspace_bytes(desc, kind)), dtype=torch.uint8, device=dev)
+            t = nnv.nnv_time_layer(desc, kind, wd, wt, xd, y, ws, warmup=1, reps=5)
+            us = forward_us(nnv, torch, desc, kind, xd, wt, y, ws)
+            peak = VALU_F32_PEAK if kind in (nnv.DIRECT, nnv.DEPTHWISE) else (MFMA_F16_PEAK if half else MFMA_F32_PEAK)
+            t_mem, t_cmp = t.forward_bytes / HBM_PEAK * 1e6, t.forward_flops / peak * 1e6
+            bound = max(t_mem, t_cmp)
+            yield {"layer": f"{i:02d} {layer.name}", "kind": KIND_NAMES[kind], "us": us,
+                   "GBps": t.forward_bytes / us / 1e3, "TFLOPs": t.forward_flops / us / 1e6,
+                   "TFLOPs_direct_equiv": t.direct_equiv_flops / us / 1e6, "bound_us": bound,
+                   "side": "hbm" if t_mem >= t_cmp else ("alu" if kind in (nnv.DIRECT, nnv.DEPTHWISE) else "mfma"),
+                   "frac": bound / us, "transform_us": t.transform_ms * 1e3,
+                   "transform_GBps": (t.transform_bytes / (t.transform_ms * 1e-3) / 1e9) if t.transform_ms > 0 else 0.0}
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__.split("\n")[0])
+    ap.add_argument("--stack", default="resnet18")
+    ap.add_argument("--half", action="store_true")
+    args = ap.parse_args()
+    print(f"| layer | kind | forward us | GB/s | TFLOP/s executed | TFLOP/s direct-equivalent | bound us | bound by | "
+          f"bound/time | transform us | transform GB/s |")
+    print("|---|---|---:|---:|---:|---:|---:|---|---:|---:|---:|")
+    tot = {}
+    for r in rows(args.stack, args.half):
+        print(f"| {r['layer']} | {r['kind']} | {r['us']:.2f} | {r['GBps']:.0f} | {r['TFLOPs']:.2f} | "
+              f"{r['TFLOPs_direct_equiv']:.2f} | {r['bound_us']:.2f} | {r['side']} | {r['frac']:.3f} | "
+              f"{r['transform_us']:.2f} | {r['transform_GBps']:.0f} |", flush=True)
+        a = tot.setdefault(r["kind"], [0.0, 0.0, 0])
+        a[0] += r["us"]; a[1] += r["bound_us"]; a[2] += 1
+    print()
+    print("| kind | layers | sum forward us | sum of bounds us | bound/time |")
+    print("|---|---:|---:|---:|---:|")
+    for k, (us, b, n) in tot.items():
+        print(f"| {k} | {n} | {us:.1f} | {b:.1f} | {b / us:.3f} |")
+
+
+if __name__ == "__main__":
+    main()
