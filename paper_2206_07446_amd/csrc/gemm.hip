@@ -9,8 +9,11 @@
 //   of a step is 64 consecutive floats (one coalesced 256 B load) and the B fragment is
 //   x[c0 + l/16][ih][iw + l%16...] (contiguous along W for stride 1).
 // float16: v_mfma_f32_16x16x32_f16.  One k-step = 32 channels at one tap; lane l holds
-//   8 consecutive channels (slot group l/16), so x is first copied to a channel-last
-//   [N][H][W][Cpad32] half buffer in the workspace and both fragments are 16-byte loads.
+//   8 consecutive channels (slot group l/16).  For filters larger than 1x1, x is first copied
+//   to a channel-last [N][H][W][Cpad32] half buffer in the workspace and both fragments are
+//   16-byte loads.  For 1x1 filters (most layers of the bottleneck and inverted-residual
+//   networks) that copy would cost a launch of its own, as long as the layer itself: there a
+//   lane gathers its 8 channels straight from NCHW with eight 2-byte loads per fragment.
 //
 // Batch-1 layers put one or two wavefronts on a SIMD, and a lone wavefront issues one
 // instruction every four cycles: the k-loop must be almost nothing but loads and MFMAs.
@@ -38,7 +41,8 @@ struct GemmParams {
     int npix;            // N*P*Q
     int K16;
     int cblocks;         // channel blocks (of 4 float32 / 32 half channels)
-    int c_rem;           // float32: C % 4 (channels of the last, partial block; 0 = full)
+    int c_rem;           // float32: C % 4, float16 1x1: C % 32 (channels of the last, partial block; 0 = full)
+    uint32_t plane_bytes;   // float16 1x1: bytes of one channel plane of x (H*W*2)
     int ks_shift;        // wavefronts sharing one output tile = 1 << ks_shift
     int cpad;            // channel stride of the half channel-last copy
     uint32_t x_bytes, w_bytes;   // sizes of the x and wp buffers (range-checked loads)
@@ -103,7 +107,8 @@ __global__ __launch_bounds__(1024) void im2col_gemm_kernel(const GemmParams g) {
         pix_img[t] = img; pix_pq[t] = pq;
         ih0[t] = p * g.sh - g.ph;
         iw0[t] = q * g.sw - g.pw;
-        if (HALF) xbase[t] = (((img * g.H + ih0[t]) * g.W + iw0[t]) * g.cpad + slot * 8) * 2;
+        if (HALF && MODE == 1) xbase[t] = (((img * g.C + slot * 8) * g.H + ih0[t]) * g.W + iw0[t]) * 2;   // NCHW
+        else if (HALF) xbase[t] = (((img * g.H + ih0[t]) * g.W + iw0[t]) * g.cpad + slot * 8) * 2;
         else xbase[t] = (((img * g.C + slot) * g.H + ih0[t]) * g.W + iw0[t]) * 4;
     }
     const int tap_w = HALF ? g.cpad * 2 : 4;             // bytes per step along s
@@ -151,7 +156,28 @@ __global__ __launch_bounds__(1024) void im2col_gemm_kernel(const GemmParams g) {
 #pragma unroll
             for (int j = 0; j < STEPS; ++j) a[buf][j][m] = buf_load<frag_t>(win, a_lane + j * FRAG, 0u);
         }
-        if (MODE == 1) {
+        if constexpr (MODE == 1 && HALF) {
+            // x is NCHW: the lane's 8 channels are 8 planes apart; channels past C (last block)
+            // read as zero through an out-of-range offset
+#pragma unroll
+            for (int j = 0; j < STEPS; ++j) {
+                const int cb = min(u + j, u_end - 1);
+                const bool part = g.c_rem != 0 && cb == g.cblocks - 1;   // uniform
+#pragma unroll
+                for (int t = 0; t < TN; ++t) {
+                    half8 v;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        uint32_t vo = voff[t][0];
+                        if (part) vo = slot * 8 + i < g.c_rem ? vo : kOobOffset;
+                        const unsigned short h = __builtin_amdgcn_raw_buffer_load_b16(
+                            xres, vo, (uint32_t)cb * g.cb_stride + (uint32_t)i * g.plane_bytes, 0);
+                        v[i] = __builtin_bit_cast(_Float16, h);
+                    }
+                    b[buf][j][t] = v;
+                }
+            }
+        } else if (MODE == 1) {
 #pragma unroll
             for (int j = 0; j < STEPS; ++j) {
                 const int cb = min(u + j, u_end - 1);
@@ -317,7 +343,8 @@ static GemmPlan plan_im2col(const Geo &g) {
             ++shift;
         return shift;
     };
-    if (tiles(2, 2) >= 4096) { pl.tm = 2; pl.tn = 2; pl.ks_shift = 0; }
+    // (the float16 1x1 gather keeps eight loads per fragment in flight: no room for the 32x32 tile)
+    if (tiles(2, 2) >= 4096 && !(half && pl.mode == 1)) { pl.tm = 2; pl.tn = 2; pl.ks_shift = 0; }
     else if (tiles(2, 1) >= 160) { pl.tm = 2; pl.tn = 1; pl.ks_shift = split_for(tiles(2, 1), 2048); }
     else { pl.tm = 1; pl.tn = 1; pl.ks_shift = split_for(tiles(1, 1), 768); }
     // depth of the register ring: never more sets than the wavefront has chunks to load
@@ -328,7 +355,8 @@ static GemmPlan plan_im2col(const Geo &g) {
     if (pl.tm == 1 && chunks >= 6) pl.nbuf = 4;
     else if (pl.tm * pl.tn <= 2 && chunks >= 3) pl.nbuf = 3;
     if (half || pl.tm * pl.tn == 4) pl.nbuf = 2;
-    pl.xt_bytes = half ? align_up((size_t)g.n * g.h * g.w * ceil_div(g.c, 32) * 32 * sizeof(__half), 256) : 0;
+    // float16 needs the channel-last copy of x, except for 1x1 filters (gathered from NCHW)
+    pl.xt_bytes = (half && pl.mode != 1) ? align_up((size_t)g.n * g.h * g.w * ceil_div(g.c, 32) * 32 * sizeof(__half), 256) : 0;
     return pl;
 }
 
@@ -369,13 +397,16 @@ hipError_t launch_im2col(const Geo &g, const void *x, const void *w, const float
     gp.K16 = ceil_div(g.k, 16);
     gp.cpad = ceil_div(g.c, 32) * 32;
     gp.cblocks = half ? ceil_div(g.c, 32) : ceil_div(g.c, 4);
-    gp.c_rem = half ? 0 : g.c % 4;
+    const bool gather = half && pl.mode == 1;      // float16 1x1: B fragments gathered from NCHW
+    gp.c_rem = gather ? g.c % 32 : half ? 0 : g.c % 4;
+    gp.plane_bytes = (uint32_t)(g.h * g.w * 2);
     gp.ks_shift = pl.ks_shift;
     gp.half_out = half;
-    gp.x_bytes = half ? (uint32_t)((size_t)g.n * g.h * g.w * gp.cpad * 2) : (uint32_t)((size_t)g.n * g.c * g.h * g.w * 4);
+    gp.x_bytes = gather ? (uint32_t)((size_t)g.n * g.c * g.h * g.w * 2)
+                 : half ? (uint32_t)((size_t)g.n * g.h * g.w * gp.cpad * 2) : (uint32_t)((size_t)g.n * g.c * g.h * g.w * 4);
     gp.w_bytes = (uint32_t)((size_t)gp.K16 * gp.cblocks * g.r * g.s * 64 * (half ? 16 : 4));
-    gp.cb_stride = half ? 64u : (uint32_t)(4 * g.h * g.w * 4);
-    if (half) {
+    gp.cb_stride = gather ? 32u * gp.plane_bytes : half ? 64u : (uint32_t)(4 * g.h * g.w * 4);
+    if (half && !gather) {
         __half *xt = static_cast<__half *>(ws);
         dim3 grid(ceil_div(g.h * g.w, 256), gp.cpad / 8, g.n);
         hipLaunchKernelGGL(to_channels_last_kernel, grid, dim3(256), 0, st, static_cast<const __half *>(x), xt, g.c,
