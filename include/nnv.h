@@ -86,7 +86,8 @@ typedef struct {
 /* Version of the transformed-weight layouts and of the Winograd matrix sets.
  * Version 1: 16-row fragments (float32: 16x4, float16: 16x32); Winograd points
  * {0,1,-1} (F2), {0,+-1,+-2} (F4 float32), {0,1,-1,2,-1/2} with G rows scaled by
- * (4,4,4,16,4,1) (F4 float16). */
+ * (4,4,4,16,4,1) (F4 float16), {0,+-1,+-2,+-1/2} (F6 float32).  Cache files carry
+ * this number and are refused under any other. */
 int nnv_layout_version(void);
 
 /* Static text for a status code (never NULL). */
