@@ -306,6 +306,11 @@ int nnv_cold_stack(int n_layers, const nnv_conv_desc *descs, const nnv_kind *kin
         for (int i = b; i < b + n && rc == NNV_OK; ++i)
             rc = forward_checked(geos[i], kinds[i], x[i], w_tx[i], nullptr, y[i], workspace, se);
     }
+    if (two && rc != NNV_OK) {
+        // an error cut the pass short: still join stream_tx back into stream_exec, so that a
+        // capture that is under way stays well-formed
+        if (hipEventRecord(ev[0], stx) == hipSuccess) (void)hipStreamWaitEvent(se, ev[0], 0);
+    }
     cleanup();
     return rc;
 }
