@@ -153,6 +153,28 @@ def report(table: Dict[str, List[Candidate]], read_gbps: float) -> dict:
     return out
 
 
+def markdown(rep: dict) -> str:
+    """The report as two tables: candidates per layer (Table 2's columns) and the plans."""
+    out = ["| layer | kind | kept | read raw ms | transform ms | read cache ms | execute ms | raw+transform+execute | cache+execute |",
+           "|---|---|---|---:|---:|---:|---:|---:|---:|"]
+    gbps = rep["read_GBps"]
+    for name, cands in rep["layers"].items():
+        for c in cands:
+            cand = Candidate(**{k: c[k] for k in ("kind", "transform_ms", "execute_ms", "raw_bytes", "transformed_bytes",
+                                                 "read_raw_ms", "read_cache_ms")})
+            rr, rc = cand.read_ms(False, gbps), cand.read_ms(True, gbps)
+            out.append(f"| {name} | {c['kind']} | {'yes' if c['kept'] else 'no'} | {rr:.3f} | {c['transform_ms']:.3f} | {rc:.3f} | "
+                       f"{c['execute_ms']:.3f} | {rr + c['transform_ms'] + c['execute_ms']:.3f} | {rc + c['execute_ms']:.3f} |")
+    out += ["", "| plan | cold ms (sum over layers) | choices (layer: kind, * = cached) |", "|---|---:|---|"]
+    for label, p in rep["plans"].items():
+        if "choices" in p:
+            ch = ", ".join(f"{c['layer'].split('_')[0]}: {c['kind']}{'*' if c['cached'] else ''}" for c in p["choices"])
+        else:
+            ch = ", ".join(p["kinds"])
+        out.append(f"| {label} | {p['cold_ms']:.3f} | {ch} |")
+    return "\n".join(out)
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__.split("\n")[0])
     ap.add_argument("--stack", default="resnet18")
@@ -161,9 +183,11 @@ def main():
     ap.add_argument("--reps", type=int, default=10)
     ap.add_argument("--flush-mb", type=int, default=0)
     ap.add_argument("--cache-dir", default=None, help="measure weight reads through cache files written here")
+    ap.add_argument("--markdown", action="store_true", help="print tables instead of JSON")
     args = ap.parse_args()
     table = profile_stack(args.stack, 1 if args.half else 0, args.reps, args.flush_mb, args.cache_dir)
-    print(json.dumps(report(table, args.read_gbps), indent=1))
+    rep = report(table, args.read_gbps)
+    print(markdown(rep) if args.markdown else json.dumps(rep, indent=1))
 
 
 if __name__ == "__main__":

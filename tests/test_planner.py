@@ -58,3 +58,12 @@ def test_measured_read_times_replace_the_bandwidth_model():
     assert c.kind == "wino_f4" and c.cached and abs(c.cold_ms - 8.21) < 1e-9 and c.read_ms == 5.23
     c = choose("l", cands, read_gbps=1e-6, allow_cache=False)
     assert c.kind == "direct" and abs(c.cold_ms - 8.71) < 1e-9
+
+
+def test_markdown_has_a_row_per_candidate_and_plan():
+    from paper_2206_07446_amd.planner import markdown
+    table = {"00_l0": table2_like(), "01_l1": table2_like()[1:]}
+    text = markdown(report(table, 0.63))
+    rows = [l for l in text.splitlines() if l.startswith("| 0")]
+    assert len(rows) == 9
+    assert "| with_cache |" in text and "wino_f4*" in text
