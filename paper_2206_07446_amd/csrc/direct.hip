@@ -168,7 +168,16 @@ __global__ __launch_bounds__(1024) void direct_conv_tiled_kernel(const T *__rest
 // into scalar registers (scalar cache; nine consecutive floats per output and input channel)
 // and feed the FMAs as scalar operands: no LDS staging, no barrier in the channel loop.  x comes
 // through buffer loads with one hoisted byte offset per tap (out of range in the zero padding).
-template <typename T, int TK, int FS>
+//
+// GRID8 (3x3, stride 1, input planes up to 7x7: the last stage of an ImageNet CNN).  There the
+// nine pixel loads per channel, not the FMAs, set the time (measured: the kernel with its FMAs
+// cut to a ninth runs as long as the full one).  The 64 lanes form an 8x8 grid that holds the
+// whole plane, fetched by ONE load per channel, and every lane takes its eight neighbours from
+// the other lanes with ds_bpermute (a register crossbar, no memory).  Row 7 and column 7 of the
+// grid hold zeros, and because lane indices wrap modulo 64 they serve as the zero padding on
+// all four sides.  (Cutting larger planes into 6x6-output tiles with an 8x8 halo patch was
+// measured too and loses: 36 useful lanes of 64 cost more than the loads save.)
+template <typename T, int TK, int FS, bool GRID8 = false>
 __global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__restrict__ x, const float *__restrict__ w,
                                                                  const float *__restrict__ bias, T *__restrict__ y,
                                                                  const DirectParams d) {
@@ -187,18 +196,34 @@ __global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__rest
     const int bx = d.k_major ? l2 % d.grid_nx : l2 / d.grid_ny;
     const int by = d.k_major ? l2 / d.grid_nx : l2 % d.grid_ny;
     const int k0 = by * TK;
-    const int pix = bx * 64 + lane;
-    const bool live = pix < PQ;
-    const int p = live ? pix / d.Q : 0, q = live ? pix - p * d.Q : 0;
-    uint32_t voff[RS];
+    int pix;
+    bool live;
+    uint32_t voff[GRID8 ? 1 : RS];
+    int nb[GRID8 ? RS : 1];       // GRID8: byte index (lane * 4) of the lane that holds tap (r, s)
+    if constexpr (GRID8) {
+        // lane (gy, gx) holds x[gy][gx] (zero beyond the plane) and computes output (gy, gx); tap
+        // (r, s) of that output is x[gy - pad_h + r][gx - pad_w + s], i.e. the lane 8 (r - pad_h) +
+        // (s - pad_w) further on, modulo 64
+        const int gy = lane >> 3, gx = lane & 7;
+        const bool ok = gy < d.H && gx < d.W;
+        voff[0] = ok ? (uint32_t)((gy * d.W + gx) * ESZ) : kOobOffset;
 #pragma unroll
-    for (int r = 0; r < FS; ++r)
+        for (int rs = 0; rs < RS; ++rs) nb[rs] = ((lane + (rs / 3 - d.ph) * 8 + rs % 3 - d.pw) & 63) * 4;
+        live = gy < d.P && gx < d.Q;
+        pix = gy * d.Q + gx;
+    } else {
+        pix = bx * 64 + lane;
+        live = pix < PQ;
+        const int p = live ? pix / d.Q : 0, q = live ? pix - p * d.Q : 0;
 #pragma unroll
-        for (int s2 = 0; s2 < FS; ++s2) {
-            const int ih = p * d.sh - d.ph + r, iw = q * d.sw - d.pw + s2;
-            const bool ok = live && (unsigned)ih < (unsigned)d.H && (unsigned)iw < (unsigned)d.W;
-            voff[r * FS + s2] = ok ? (uint32_t)((ih * d.W + iw) * ESZ) : kOobOffset;
-        }
+        for (int r = 0; r < FS; ++r)
+#pragma unroll
+            for (int s2 = 0; s2 < FS; ++s2) {
+                const int ih = p * d.sh - d.ph + r, iw = q * d.sw - d.pw + s2;
+                const bool ok = live && (unsigned)ih < (unsigned)d.H && (unsigned)iw < (unsigned)d.W;
+                voff[r * FS + s2] = ok ? (uint32_t)((ih * d.W + iw) * ESZ) : kOobOffset;
+            }
+    }
     const __amdgpu_buffer_rsrc_t xres = make_rsrc(x + (size_t)img * d.C * HW, (uint32_t)((size_t)d.C * HW * ESZ));
     const uint32_t plane = (uint32_t)(HW * ESZ);
     const size_t wk = (size_t)d.C * RS;
@@ -223,12 +248,22 @@ __global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__rest
     }
     // two channels per iteration: the loads of both are issued before the FMAs of the first
     // (large filters: one channel at a time, their taps alone fill the registers)
+    // pixels of the RS taps of channel cc: RS loads, or one load and RS - 1 lane exchanges
+    auto load_pixels = [&](float (&xv)[RS], int cc) __attribute__((always_inline)) {
+        if constexpr (GRID8) {
+            const float own = buf_load_x<T>(xres, voff[0], (uint32_t)cc * plane);
+#pragma unroll
+            for (int i = 0; i < RS; ++i)
+                xv[i] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(nb[i], __builtin_bit_cast(int, own)));
+        } else {
+#pragma unroll
+            for (int i = 0; i < RS; ++i) xv[i] = buf_load_x<T>(xres, voff[i], (uint32_t)cc * plane);
+        }
+    };
     for (; FS <= 3 && c + CS < d.C; c += 2 * CS) {
         float xa[RS], xb[RS];
-#pragma unroll
-        for (int i = 0; i < RS; ++i) xa[i] = buf_load_x<T>(xres, voff[i], (uint32_t)c * plane);
-#pragma unroll
-        for (int i = 0; i < RS; ++i) xb[i] = buf_load_x<T>(xres, voff[i], (uint32_t)(c + CS) * plane);
+        load_pixels(xa, c);
+        load_pixels(xb, c + CS);
         const float *wa = wrow + (size_t)c * RS, *wb = wrow + (size_t)(c + CS) * RS;
 #pragma unroll
         for (int j = 0; j < TK; ++j)
@@ -241,8 +276,7 @@ __global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__rest
     }
     for (; c < d.C; c += CS) {
         float xa[RS];
-#pragma unroll
-        for (int i = 0; i < RS; ++i) xa[i] = buf_load_x<T>(xres, voff[i], (uint32_t)c * plane);
+        load_pixels(xa, c);
         const float *wa = wrow + (size_t)c * RS;
 #pragma unroll
         for (int j = 0; j < TK; ++j)
@@ -327,7 +361,10 @@ static bool slane_supported(const Geo &g) {
 template <typename T>
 static void launch_slane(const Geo &g, DirectParams d, const T *x, const float *w, const float *bias, T *y,
                          hipStream_t st_) {
-    const long pixw = ceil_div(g.p * g.q, 64);
+    // 3x3 stride-1 layers on planes up to 7x7 take the 8x8 lane grid (one pixel load per channel
+    // instead of nine; needs a zero row and column, and pads <= 1 so that taps wrap into them)
+    const bool grid8 = g.r == 3 && g.sh == 1 && g.sw == 1 && g.h <= 7 && g.w <= 7 && g.ph <= 1 && g.pw <= 1;
+    const long pixw = grid8 ? 1 : ceil_div(g.p * g.q, 64);
     // 8 output channels per lane while that leaves enough blocks, else 4; channel split until about
     // two wavefronts per SIMD exist (measured on ResNet-18-shaped layers)
     int tk = (g.k % 8 == 0 && pixw * (g.k / 8) * g.n >= 160 && g.r <= 3) ? 8 : 4;
@@ -340,7 +377,10 @@ static void launch_slane(const Geo &g, DirectParams d, const T *x, const float *
     d.k_major = (size_t)g.k * g.c * g.r * g.s * 4 >= (size_t)g.c * g.h * g.w * sizeof(T);
     dim3 grid(xcd_grid(d.grid_nx * d.grid_ny * g.n), 1, 1);
     dim3 block(64 * cs);
-    if (g.r == 3) {
+    if (g.r == 3 && grid8) {
+        if (tk == 8) hipLaunchKernelGGL((direct_conv_slane_kernel<T, 8, 3, true>), grid, block, lds, st_, x, w, bias, y, d);
+        else hipLaunchKernelGGL((direct_conv_slane_kernel<T, 4, 3, true>), grid, block, lds, st_, x, w, bias, y, d);
+    } else if (g.r == 3) {
         if (tk == 8) hipLaunchKernelGGL((direct_conv_slane_kernel<T, 8, 3>), grid, block, lds, st_, x, w, bias, y, d);
         else hipLaunchKernelGGL((direct_conv_slane_kernel<T, 4, 3>), grid, block, lds, st_, x, w, bias, y, d);
     } else if (g.r == 1) {
