@@ -72,6 +72,9 @@ SMALL = [
     Ly("batch3_pw", 24, 9, 7, 72, 1, 1, 0, n=3),
     Ly("batch2_s2", 16, 17, 15, 24, 3, 2, 1, n=2),
     Ly("batch5_deep", 128, 7, 7, 64, 3, 1, 1, n=5),
+    ConvLayer("plane5x7", 9, 5, 7, 8, 3, 3, 1, 1),          # whole plane in one wavefront, not square
+    Ly("plane7_pad0", 9, 7, 7, 8, 3, 1, 0),
+    Ly("plane8", 9, 8, 8, 8, 3, 1, 1),                       # one more than the lane grid takes
 ]
 CASES = [(l, k, h) for h in (False, True) for l in SMALL for k in applicable_kinds(l, h)]
 
