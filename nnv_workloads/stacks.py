@@ -1,4 +1,4 @@
-"""Conv-layer shape lists for the five synthetic workloads.
+"""Conv-layer shape lists for the synthetic workloads.
 
 The paper evaluates whole trained CNNs (Table 4: MobileNetV2, ResNet-18,
 ResNet-50, ... at 224x224 input, batch 1).  Only the *shapes* of their
@@ -58,7 +58,8 @@ class ConvLayer:
         return (self.r == 3 and self.s == 3 and self.stride == 1 and self.groups == 1)
 
 
-STACK_NAMES = ("single3x3", "resnet18", "mobilenetv2", "vgg16", "resnet50")
+STACK_NAMES = ("single3x3", "resnet18", "mobilenetv2", "vgg16", "resnet50",
+               "mobilenetv1", "squeezenet", "googlenet")
 
 
 def _single() -> List[ConvLayer]:
@@ -133,8 +134,68 @@ def _resnet50() -> List[ConvLayer]:
     return L
 
 
+def _mobilenetv1() -> List[ConvLayer]:
+    # 3x3/2 stem to 32 channels, then 13 depthwise-separable blocks (output width, stride of
+    # the depthwise 3x3), as published for the width-1.0, 224x224 network of Table 4.
+    blocks = ((64, 1), (128, 2), (128, 1), (256, 2), (256, 1), (512, 2), (512, 1), (512, 1),
+              (512, 1), (512, 1), (512, 1), (1024, 2), (1024, 1))
+    L = [ConvLayer("stem3x3_s2", 3, 224, 224, 32, 3, 3, 2, 1)]
+    cin, hw = 32, 112
+    for b, (cout, st) in enumerate(blocks):
+        L.append(ConvLayer(f"b{b}_dw_s{st}", cin, hw, hw, cin, 3, 3, st, 1, groups=cin))
+        hw = (hw + 2 - 3) // st + 1
+        L.append(ConvLayer(f"b{b}_pw", cin, hw, hw, cout, 1, 1, 1, 0))
+        cin = cout
+    return L
+
+
+def _squeezenet() -> List[ConvLayer]:
+    # The first published version (7x7/2 stem to 96 channels, eight fire modules, 1x1 classifier
+    # conv), the one whose size matches Table 4's 1.4 M parameters; 3x3/2 max-pools (ceil mode)
+    # after the stem, fire4 and fire8.  fire = 1x1 squeeze, then 1x1 and 3x3 expand side by side.
+    fires = ((16, 64), (16, 64), (32, 128), None, (32, 128), (48, 192), (48, 192), (64, 256), None, (64, 256))
+    L = [ConvLayer("conv1_7x7_s2", 3, 224, 224, 96, 7, 7, 2, 0)]
+    hw = (224 - 7) // 2 + 1          # 109
+    hw = -(-(hw - 3) // 2) + 1       # 54
+    cin, f = 96, 2
+    for spec in fires:
+        if spec is None:
+            hw = -(-(hw - 3) // 2) + 1
+            continue
+        sq, ex = spec
+        L.append(ConvLayer(f"fire{f}_squeeze", cin, hw, hw, sq, 1, 1, 1, 0))
+        L.append(ConvLayer(f"fire{f}_expand1x1", sq, hw, hw, ex, 1, 1, 1, 0))
+        L.append(ConvLayer(f"fire{f}_expand3x3", sq, hw, hw, ex, 3, 3, 1, 1))
+        cin, f = 2 * ex, f + 1
+    L.append(ConvLayer("conv10_1x1", cin, hw, hw, 1000, 1, 1, 1, 0))
+    return L
+
+
+def _googlenet() -> List[ConvLayer]:
+    # Stem (7x7/2, 1x1, 3x3) and nine inception modules with their published widths
+    # (#1x1, #3x3 reduce, #3x3, #5x5 reduce, #5x5, pool projection); its 5x5 and 1x1 branches
+    # are the shapes Fig. 5's kernel tree distinguishes by filter size.
+    L = [ConvLayer("conv1_7x7_s2", 3, 224, 224, 64, 7, 7, 2, 3),
+         ConvLayer("conv2_reduce", 64, 56, 56, 64, 1, 1, 1, 0),
+         ConvLayer("conv2_3x3", 64, 56, 56, 192, 3, 3, 1, 1)]
+    mods = (("3a", 28, 192, (64, 96, 128, 16, 32, 32)), ("3b", 28, 256, (128, 128, 192, 32, 96, 64)),
+            ("4a", 14, 480, (192, 96, 208, 16, 48, 64)), ("4b", 14, 512, (160, 112, 224, 24, 64, 64)),
+            ("4c", 14, 512, (128, 128, 256, 24, 64, 64)), ("4d", 14, 512, (112, 144, 288, 32, 64, 64)),
+            ("4e", 14, 528, (256, 160, 320, 32, 128, 128)), ("5a", 7, 832, (256, 160, 320, 32, 128, 128)),
+            ("5b", 7, 832, (384, 192, 384, 48, 128, 128)))
+    for name, hw, cin, (n1, r3, n3, r5, n5, pp) in mods:
+        L.append(ConvLayer(f"i{name}_1x1", cin, hw, hw, n1, 1, 1, 1, 0))
+        L.append(ConvLayer(f"i{name}_3x3_reduce", cin, hw, hw, r3, 1, 1, 1, 0))
+        L.append(ConvLayer(f"i{name}_3x3", r3, hw, hw, n3, 3, 3, 1, 1))
+        L.append(ConvLayer(f"i{name}_5x5_reduce", cin, hw, hw, r5, 1, 1, 1, 0))
+        L.append(ConvLayer(f"i{name}_5x5", r5, hw, hw, n5, 5, 5, 1, 2))
+        L.append(ConvLayer(f"i{name}_pool_proj", cin, hw, hw, pp, 1, 1, 1, 0))
+    return L
+
+
 _BUILDERS = {"single3x3": _single, "resnet18": _resnet18, "mobilenetv2": _mobilenetv2,
-             "vgg16": _vgg16, "resnet50": _resnet50}
+             "vgg16": _vgg16, "resnet50": _resnet50, "mobilenetv1": _mobilenetv1,
+             "squeezenet": _squeezenet, "googlenet": _googlenet}
 
 
 def stack(name: str) -> List[ConvLayer]:

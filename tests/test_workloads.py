@@ -1,0 +1,43 @@
+"""Host checks of the workload shape lists against the sizes the paper's Table 4 quotes
+(parameters include the networks' classifier layers, which are not convolutions: the conv
+totals must sit below the quoted figure by about that much; FLOPs are quoted at 2 per MAC)."""
+import pytest
+
+from nnv_workloads import stack, STACK_NAMES
+
+#            conv params (M)  classifier (M)  Table 4 params (M)  Table 4 GFLOPs
+TABLE4 = {"resnet18": (11.17, 0.51, 12.7, 3.9), "resnet50": (23.45, 2.05, 25.7, 7.8),
+          "mobilenetv2": (2.19, 1.28, 3.7, 0.6), "mobilenetv1": (3.19, 1.03, 4.4, 1.1),
+          "squeezenet": (1.24, 0.0, 1.4, 1.7), "googlenet": (5.97, 1.03, 7.1, 3.2)}
+
+
+@pytest.mark.parametrize("name", sorted(TABLE4))
+def test_totals_match_table4(name):
+    conv_m, fc_m, quoted_m, quoted_gflops = TABLE4[name]
+    layers = stack(name)
+    params = sum(l.params for l in layers) / 1e6
+    gflops = 2 * sum(l.macs for l in layers) / 1e9
+    assert abs(params - conv_m) < 0.01
+    assert abs(params + fc_m - quoted_m) / quoted_m < 0.12          # batch-norm parameters and rounding aside
+    assert abs(gflops - quoted_gflops) / quoted_gflops < 0.12
+
+
+@pytest.mark.parametrize("name", STACK_NAMES)
+def test_layers_are_well_formed(name):
+    for l in stack(name):
+        assert l.p > 0 and l.q > 0 and l.c % l.groups == 0 and l.k % l.groups == 0, l
+
+
+def test_inception_branch_widths_chain():
+    g = {l.name: l for l in stack("googlenet")}
+    order = ["3a", "3b", "4a", "4b", "4c", "4d", "4e", "5a", "5b"]
+    for a, b in zip(order, order[1:]):
+        out = g[f"i{a}_1x1"].k + g[f"i{a}_3x3"].k + g[f"i{a}_5x5"].k + g[f"i{a}_pool_proj"].k
+        assert out == g[f"i{b}_1x1"].c, (a, b)
+
+
+def test_fire_modules_chain_and_sizes():
+    s = stack("squeezenet")
+    assert [l.h for l in s if l.name.endswith("squeeze")] == [54, 54, 54, 27, 27, 27, 27, 13]
+    for sq, e1, e3 in zip(s[1::3], s[2::3], s[3::3]):
+        assert e1.c == sq.k == e3.c and e1.k == e3.k
