@@ -148,7 +148,10 @@ int nnv_conv_forward(const nnv_conv_desc *desc, nnv_kind kind, const void *x, co
  * timed repetitions of the transformation and, separately, of the forward pass,
  * each bracketed by HIP events on `hip_stream`, and reports the medians.  If
  * flush is non-NULL, flush_bytes of it are overwritten before every timed
- * repetition so that weights and activations are not cache-resident ("cold").
+ * repetition so that weights and activations are not cache-resident ("cold")
+ * and a repetition is one launch; without a flush buffer a repetition is a
+ * queue of 8 back-to-back launches between one pair of events and its time
+ * is their mean (a batch-1 layer runs for less than a pair of events costs).
  * Synchronises the stream.  `out` is a HOST pointer. */
 int nnv_time_layer(const nnv_conv_desc *desc, nnv_kind kind, const float *w_raw, void *w_tx,
                    const void *x, void *y, void *workspace, size_t workspace_bytes,

@@ -213,6 +213,13 @@ def test_time_layer(env):
     # aliasing direct transform costs nothing
     t = nnv.nnv_time_layer(desc, 0, wd, wd, xd, y, None, warmup=0, reps=2)
     assert t.transform_ms == 0 and t.transform_bytes == 0
+    # warm timing (no flush buffer) averages queued launches: never slower than the cold figure,
+    # and still above the rooflines' floor
+    wt = torch.empty(nnv.nnv_transformed_bytes(desc, 1), dtype=torch.uint8, device=dev)
+    cold = nnv.nnv_time_layer(desc, 1, wd, wt, xd, y, None, flush=flush, warmup=1, reps=7)
+    warm = nnv.nnv_time_layer(desc, 1, wd, wt, xd, y, None, warmup=1, reps=7)
+    assert 0 < warm.forward_ms <= cold.forward_ms * 1.05
+    assert warm.forward_ms * 1e-3 >= warm.forward_flops / 157.3e12
 
 
 def _random_layers(count, seed):
