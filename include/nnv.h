@@ -101,7 +101,7 @@ const char *nnv_last_hip_error(void);
  *   WINO_F6      : the same, and dtype float32 (with U and V rounded to float16 its error
  *                  exceeds the float16 bound of this library, so that pairing is refused)
  *   DEPTHWISE    : groups = C = K, R = S = 3, stride_h = stride_w in {1,2}
- *   IM2COL_GEMM  : groups 1, R,S <= 32, R*S <= 64
+ *   IM2COL_GEMM  : groups 1, R,S <= 32, R*S <= 128 (float16: <= 64)
  *   DIRECT       : any groups dividing C and K
  * (the paper's engine keys the usable kernels on filter size, stride and channel
  * divisibility in the same way, Fig. 5). */

@@ -59,7 +59,7 @@ class ConvLayer:
 
 
 STACK_NAMES = ("single3x3", "resnet18", "mobilenetv2", "vgg16", "resnet50",
-               "mobilenetv1", "squeezenet", "googlenet")
+               "mobilenetv1", "squeezenet", "googlenet", "alexnet")
 
 
 def _single() -> List[ConvLayer]:
@@ -193,9 +193,20 @@ def _googlenet() -> List[ConvLayer]:
     return L
 
 
+def _alexnet() -> List[ConvLayer]:
+    # The single-tower variant (64, 192, 384, 256, 256 channels, no groups), the one whose size
+    # matches Table 4's 61.3 M parameters and 1.4 GFLOPs: an 11x11/4 stem, a 5x5, three 3x3;
+    # 3x3/2 max-pools after the first, second and fifth conv.
+    return [ConvLayer("conv1_11x11_s4", 3, 224, 224, 64, 11, 11, 4, 2),
+            ConvLayer("conv2_5x5", 64, 27, 27, 192, 5, 5, 1, 2),
+            ConvLayer("conv3_3x3", 192, 13, 13, 384, 3, 3, 1, 1),
+            ConvLayer("conv4_3x3", 384, 13, 13, 256, 3, 3, 1, 1),
+            ConvLayer("conv5_3x3", 256, 13, 13, 256, 3, 3, 1, 1)]
+
+
 _BUILDERS = {"single3x3": _single, "resnet18": _resnet18, "mobilenetv2": _mobilenetv2,
              "vgg16": _vgg16, "resnet50": _resnet50, "mobilenetv1": _mobilenetv1,
-             "squeezenet": _squeezenet, "googlenet": _googlenet}
+             "squeezenet": _squeezenet, "googlenet": _googlenet, "alexnet": _alexnet}
 
 
 def stack(name: str) -> List[ConvLayer]:

@@ -62,7 +62,8 @@ bool supported(const Geo &g, int kind) {
 bool kind_rules(const Geo &g, int kind) {
     switch (kind) {
         case NNV_DIRECT: return true;
-        case NNV_IM2COL_GEMM: return g.groups == 1 && g.r <= 32 && g.s <= 32 && g.r * g.s <= 64;
+        case NNV_IM2COL_GEMM:   // the pack stages 16 rows x one fragment column of taps in LDS
+            return g.groups == 1 && g.r <= 32 && g.s <= 32 && g.r * g.s <= (g.dtype == NNV_F16 ? 64 : 128);
         case NNV_WINO_F2:
         case NNV_WINO_F4: return g.groups == 1 && g.r == 3 && g.s == 3 && g.sh == 1 && g.sw == 1;
         case NNV_WINO_F6: return g.groups == 1 && g.r == 3 && g.s == 3 && g.sh == 1 && g.sw == 1 && g.dtype == NNV_F32;

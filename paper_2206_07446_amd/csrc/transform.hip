@@ -262,10 +262,12 @@ int fill_transform_job(const Geo &g, int kind, const float *src, void *dst, Tran
         job->type = JOB_GEMM;
         const int cpad = job->half ? ceil_div(g.cg, 32) * 32 : ceil_div(g.cg, 4) * 4;
         // about 18 KB of LDS per block (as many resident blocks as the Winograd jobs of the
-        // same launch allow): 288 floats per row, at least one 32-channel fragment column
-        // (float16 output: twice that, its fragments span 32 channels)
-        int cc = ((job->half ? 576 : 288) / job->RS) / 32 * 32;
-        if (cc < 32) cc = 32;
+        // same launch allow): about 288 floats per row, in whole fragments' worth of channels
+        // (float32: 4, so that even an 11x11 filter stages only 31 KB; float16: 32, twice the row)
+        const int unit = job->half ? 32 : 4;
+        int cc = ((job->half ? 576 : 288) / job->RS) / unit * unit;
+        if (cc < unit) cc = unit;
+        if (cc > 32 && !job->half) cc = cc / 32 * 32;
         job->cchunk = cc;
         job->nchunks = ceil_div(cpad, cc);
         job->nblocks = k16 * job->nchunks;

@@ -31,7 +31,8 @@ def applicable_kinds(layer, half=False):
     """Kernel kinds that can run the layer (F(6x6) exists in float32 only)."""
     kinds = [0]
     if layer.groups == 1:
-        kinds.append(1)
+        if layer.r * layer.s <= (64 if half else 128):
+            kinds.append(1)
         if layer.winograd_ok:
             kinds += [2, 3] if half else [2, 3, 5]
     if layer.is_depthwise and layer.r == 3 and layer.stride in (1, 2):

@@ -130,3 +130,11 @@ def test_cold_stack_argument_errors_need_no_gpu():
     assert lib.nnv_cold_stack(-1, None, None, None, None, None, None, None, 0, 1, None, None) == -7
     assert lib.nnv_cold_stack(0, None, None, None, None, None, None, None, 0, 1, None, None) == 0
     assert lib.nnv_cold_stack(1, None, None, None, None, None, None, None, 0, 1, None, None) == -1
+
+
+def test_filter_size_limits_of_the_gemm_kind():
+    """An 11x11 filter (121 taps) packs in float32; float16 fragments span 32 channels and stop at 64 taps."""
+    assert nnv.nnv_kind_supported(D(c=3, h=224, w=224, k=64, r=11, s=11, stride_h=4, stride_w=4, pad_h=2, pad_w=2), 1)
+    assert not nnv.nnv_kind_supported(D(c=3, h=224, w=224, k=64, r=11, s=11, stride_h=4, stride_w=4, pad_h=2, pad_w=2, dtype=1), 1)
+    assert nnv.nnv_kind_supported(D(r=8, s=8, pad_h=4, pad_w=4, dtype=1), 1)
+    assert not nnv.nnv_kind_supported(D(c=4, h=40, w=40, r=12, s=12), 1)

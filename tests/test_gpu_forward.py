@@ -159,11 +159,11 @@ def test_full_resnet50_stack_f32_f16(env):
     _run_stack(env, "resnet50", [False, True])
 
 
-@pytest.mark.parametrize("name", ["mobilenetv1", "squeezenet", "googlenet"])
+@pytest.mark.parametrize("name", ["mobilenetv1", "squeezenet", "googlenet", "alexnet"])
 def test_further_table4_shaped_stacks(env, name):
     """More of the paper's Table 4 networks: depthwise-separable blocks, fire modules (7x7/2 stem
     without padding, odd feature-map sizes 109/54/27/13) and inception modules (5x5 branches)."""
-    _run_stack(env, name, [False, True] if name == "googlenet" else [False])
+    _run_stack(env, name, [False, True] if name in ("googlenet", "alexnet") else [False])
 
 
 def test_error_paths_on_device(env):
