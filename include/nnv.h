@@ -143,6 +143,13 @@ int nnv_conv_forward(const nnv_conv_desc *desc, nnv_kind kind, const void *x, co
                      const float *bias, void *y, void *workspace, size_t workspace_bytes,
                      void *hip_stream);
 
+/* The same with the activation that follows almost every convolution of the paper's
+ * networks fused into the store: y = max(conv + bias, 0), clamped in float32 before the
+ * one rounding to desc.dtype.  Same arguments and errors as nnv_conv_forward. */
+int nnv_conv_forward_relu(const nnv_conv_desc *desc, nnv_kind kind, const void *x, const void *w_tx,
+                          const float *bias, void *y, void *workspace, size_t workspace_bytes,
+                          void *hip_stream);
+
 /* Per-operation profiling (the latency table Algorithm 1 consumes; Section 3.3
  * re-profiles operations while planning).  Runs `warmup` untimed and `reps`
  * timed repetitions of the transformation and, separately, of the forward pass,

@@ -37,6 +37,7 @@ int make_geo(const nnv_conv_desc *d, Geo *g) {
     g->q = (d->w + 2 * d->pad_w - d->s) / d->stride_w + 1;
     g->cg = d->c / d->groups;
     g->kg = d->k / d->groups;
+    g->relu = 0;
     const int64_t lim = (int64_t)1 << 30;   // element counts are indexed with 32-bit ints
     if ((int64_t)g->n * g->c * g->h * g->w >= lim || (int64_t)g->n * g->k * g->p * g->q >= lim) return NNV_E_BAD_DESC;
     if ((int64_t)g->n * g->h * g->w * (ceil_div(g->c, 32) * 32) >= lim) return NNV_E_BAD_DESC;
@@ -246,6 +247,15 @@ int nnv_conv_forward(const nnv_conv_desc *desc, nnv_kind kind, const void *x, co
     Geo g;
     int rc = forward_args(desc, kind, x, w_tx, bias, y, workspace, workspace_bytes, &g);
     if (rc) return rc;
+    return forward_checked(g, kind, x, w_tx, bias, y, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+int nnv_conv_forward_relu(const nnv_conv_desc *desc, nnv_kind kind, const void *x, const void *w_tx, const float *bias,
+                          void *y, void *workspace, size_t workspace_bytes, void *hip_stream) {
+    Geo g;
+    int rc = forward_args(desc, kind, x, w_tx, bias, y, workspace, workspace_bytes, &g);
+    if (rc) return rc;
+    g.relu = 1;
     return forward_checked(g, kind, x, w_tx, bias, y, workspace, static_cast<hipStream_t>(hip_stream));
 }
 

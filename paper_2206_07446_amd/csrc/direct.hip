@@ -17,7 +17,10 @@ struct DirectParams {
     int N, C, H, W, K, R, S, sh, sw, ph, pw, P, Q, Cg, Kg;
     int grid_nx, grid_ny;   // scalar-weight kernel: pixel groups, output-channel groups (logical grid)
     int k_major;            // 1: consecutive logical blocks walk the pixels first (an XCD keeps few filters)
+    int relu;               // outputs clamped at zero before the store
 };
+
+__device__ static inline float act(float v, int relu) { return relu ? fmaxf(v, 0.f) : v; }
 
 template <typename T> __device__ static inline float ld(const T *p, size_t i);
 template <> __device__ inline float ld<float>(const float *p, size_t i) { return p[i]; }
@@ -60,7 +63,7 @@ __global__ __launch_bounds__(256) void direct_conv_simple_kernel(const T *__rest
     }
     if (live) {
 #pragma unroll
-        for (int j = 0; j < KB; ++j) st<T>(y, ((size_t)img * d.K + k0 + j) * d.P * d.Q + pq, acc[j]);
+        for (int j = 0; j < KB; ++j) st<T>(y, ((size_t)img * d.K + k0 + j) * d.P * d.Q + pq, act(acc[j], d.relu));
     }
 }
 
@@ -158,7 +161,7 @@ __global__ __launch_bounds__(1024) void direct_conv_tiled_kernel(const T *__rest
                     if (tt == t && jj == j) v = acc[tt][jj];
         }
         const int pix = (blockIdx.x * 64 + lane) * TP + t;
-        if (pix < PQ) st<T>(y, ((size_t)img * d.K + k0 + j) * PQ + pix, v + (bias ? bias[k0 + j] : 0.f));
+        if (pix < PQ) st<T>(y, ((size_t)img * d.K + k0 + j) * PQ + pix, act(v + (bias ? bias[k0 + j] : 0.f), d.relu));
     }
 }
 
@@ -298,7 +301,7 @@ __global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__rest
             for (int jj = 0; jj < TK; ++jj)
                 if (jj == j) v = acc[jj];
         }
-        if (live) st<T>(y, ((size_t)img * d.K + k0 + j) * PQ + pix, v + (bias ? bias[k0 + j] : 0.f));
+        if (live) st<T>(y, ((size_t)img * d.K + k0 + j) * PQ + pix, act(v + (bias ? bias[k0 + j] : 0.f), d.relu));
     }
 }
 
@@ -395,7 +398,7 @@ static void launch_slane(const Geo &g, DirectParams d, const T *x, const float *
 
 template <typename T>
 static hipError_t launch_direct_t(const Geo &g, const T *x, const float *w, const float *bias, T *y, hipStream_t st_) {
-    DirectParams d{g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.sh, g.sw, g.ph, g.pw, g.p, g.q, g.cg, g.kg, 0, 0, 0};
+    DirectParams d{g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.sh, g.sw, g.ph, g.pw, g.p, g.q, g.cg, g.kg, 0, 0, 0, g.relu};
     if (slane_supported(g)) {
         launch_slane<T>(g, d, x, w, bias, y, st_);
         return hipGetLastError();
@@ -428,7 +431,7 @@ hipError_t launch_direct(const Geo &g, const void *x, const float *w, const floa
 // ------------------------------------------------------------------ depthwise 3x3
 
 struct DwParams {
-    int N, C, H, W, st, ph, pw, P, Q;
+    int N, C, H, W, st, ph, pw, P, Q, relu;
 };
 
 template <typename T>
@@ -455,12 +458,12 @@ __global__ __launch_bounds__(256) void depthwise_kernel(const T *__restrict__ x,
             acc = fmaf(xv, ld<T>(wc, (r * 3 + s) * 32), acc);
         }
     }
-    st<T>(y, ((size_t)img * d.C + c) * d.P * d.Q + pq, acc);
+    st<T>(y, ((size_t)img * d.C + c) * d.P * d.Q + pq, act(acc, d.relu));
 }
 
 hipError_t launch_depthwise(const Geo &g, const void *x, const void *w, const float *bias, void *y, hipStream_t st_) {
     if (g.c > 65535) return hipErrorInvalidValue;
-    DwParams d{g.n, g.c, g.h, g.w, g.sh, g.ph, g.pw, g.p, g.q};
+    DwParams d{g.n, g.c, g.h, g.w, g.sh, g.ph, g.pw, g.p, g.q, g.relu};
     dim3 grid(ceil_div(g.p * g.q, 256), g.c, g.n);
     if (g.dtype == NNV_F16)
         hipLaunchKernelGGL(depthwise_kernel<__half>, grid, dim3(256), 0, st_, static_cast<const __half *>(x),

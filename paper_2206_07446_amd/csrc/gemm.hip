@@ -48,6 +48,7 @@ struct GemmParams {
     uint32_t x_bytes, w_bytes;   // sizes of the x and wp buffers (range-checked loads)
     uint32_t cb_stride;  // bytes between channel blocks in x
     int half_out;
+    int relu;              // outputs clamped at zero before the store
     int grid_nx, grid_ny;  // logical grid: tile groups along n, along m
     int m_major;           // 1: consecutive logical tiles walk n first (an XCD keeps few weight panels),
                            // 0: they walk m first (an XCD keeps a pixel range of x)
@@ -284,7 +285,8 @@ __global__ __launch_bounds__(1024) void im2col_gemm_kernel(const GemmParams g) {
                 const int k = (mb0 + m) * 16 + slot * 4 + j;
                 if (k < g.K && pvalid[t]) {
                     const size_t o = ((size_t)pix_img[t] * g.K + k) * PQ + pix_pq[t];
-                    const float r = v + (g.bias ? g.bias[k] : 0.f);
+                    float r = v + (g.bias ? g.bias[k] : 0.f);
+                    if (g.relu) r = fmaxf(r, 0.f);
                     if (g.half_out) static_cast<__half *>(g.y)[o] = __float2half_rn(r);
                     else static_cast<float *>(g.y)[o] = r;
                 }
@@ -402,6 +404,7 @@ hipError_t launch_im2col(const Geo &g, const void *x, const void *w, const float
     gp.plane_bytes = (uint32_t)(g.h * g.w * 2);
     gp.ks_shift = pl.ks_shift;
     gp.half_out = half;
+    gp.relu = g.relu;
     gp.x_bytes = gather ? (uint32_t)((size_t)g.n * g.c * g.h * g.w * 2)
                  : half ? (uint32_t)((size_t)g.n * g.h * g.w * gp.cpad * 2) : (uint32_t)((size_t)g.n * g.c * g.h * g.w * 4);
     gp.w_bytes = (uint32_t)((size_t)gp.K16 * gp.cblocks * g.r * g.s * 64 * (half ? 16 : 4));

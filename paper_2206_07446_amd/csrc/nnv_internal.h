@@ -13,6 +13,7 @@ struct Geo {
     int n, c, h, w, k, r, s, sh, sw, ph, pw, groups, dtype;
     int p, q;      // output height / width
     int cg, kg;    // channels per group (input / output)
+    int relu;      // clamp the outputs at zero before the store (not part of the descriptor)
 };
 
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }

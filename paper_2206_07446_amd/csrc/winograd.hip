@@ -33,6 +33,7 @@ struct WinoParams {
     int ntb;                // tile-block groups per frequency: ceil(T16 / TN)
     uint32_t u_bytes, v_bytes;   // sizes of U and V (range-checked loads)
     uint32_t x_bytes;            // size of x
+    int relu;                    // outputs clamped at zero before the store
     int gemm_wgs_per_xi;         // workgroups per frequency in the tile GEMM
     int alpha2;                  // number of frequencies
 };
@@ -266,10 +267,17 @@ __global__ __launch_bounds__(256) void wino_output_kernel(const WinoParams w) {
     float tmp[M][A], Y[M][M];
     NNV_MATMUL_LEFT(Wm::AT, M, A, A, m, tmp)
     NNV_MATMUL_RIGHT_T(Wm::AT, M, A, M, tmp, Y)
+    const float bv = w.bias ? w.bias[k] : 0.f;
+#pragma unroll
+    for (int a = 0; a < M; ++a)
+#pragma unroll
+        for (int b = 0; b < M; ++b) {
+            Y[a][b] += bv;
+            if (w.relu) Y[a][b] = fmaxf(Y[a][b], 0.f);
+        }
     const int per = w.th * w.tw;
     const int img = t / per, rem = t - img * per;
     const int ti = rem / w.tw, tj = rem - ti * w.tw;
-    const float bv = w.bias ? w.bias[k] : 0.f;
     const size_t base = ((size_t)img * w.K + k) * w.P * w.Q;
     // Rows of a tile are stored VW elements at a time where Q is a multiple of VW (every group
     // of VW columns is then entirely inside the image and aligned): adjacent lanes hold
@@ -290,7 +298,7 @@ __global__ __launch_bounds__(256) void wino_output_kernel(const WinoParams w) {
                     uint32_t pk[VW / 2];
 #pragma unroll
                     for (int i = 0; i < VW / 2; ++i) {
-                        __half2 h = __floats2half2_rn(Y[a][b + 2 * i] + bv, Y[a][b + 2 * i + 1] + bv);
+                        __half2 h = __floats2half2_rn(Y[a][b + 2 * i], Y[a][b + 2 * i + 1]);
                         pk[i] = *reinterpret_cast<uint32_t *>(&h);
                     }
                     if constexpr (VW == 4) *reinterpret_cast<uint2 *>(static_cast<__half *>(w.y) + o) = make_uint2(pk[0], pk[1]);
@@ -298,9 +306,9 @@ __global__ __launch_bounds__(256) void wino_output_kernel(const WinoParams w) {
                 } else {
                     if constexpr (VW == 4)
                         *reinterpret_cast<float4 *>(static_cast<float *>(w.y) + o) =
-                            make_float4(Y[a][b] + bv, Y[a][b + 1] + bv, Y[a][b + 2] + bv, Y[a][b + 3] + bv);
+                            make_float4(Y[a][b], Y[a][b + 1], Y[a][b + 2], Y[a][b + 3]);
                     else
-                        *reinterpret_cast<float2 *>(static_cast<float *>(w.y) + o) = make_float2(Y[a][b] + bv, Y[a][b + 1] + bv);
+                        *reinterpret_cast<float2 *>(static_cast<float *>(w.y) + o) = make_float2(Y[a][b], Y[a][b + 1]);
                 }
             }
         } else {
@@ -308,7 +316,7 @@ __global__ __launch_bounds__(256) void wino_output_kernel(const WinoParams w) {
             for (int b = 0; b < M; ++b) {
                 const int q = tj * M + b;
                 if (q >= w.Q) continue;
-                const float v = Y[a][b] + bv;
+                const float v = Y[a][b];
                 if (HALF) static_cast<__half *>(w.y)[base + (size_t)p * w.Q + q] = __float2half_rn(v);
                 else static_cast<float *>(w.y)[base + (size_t)p * w.Q + q] = v;
             }
@@ -414,6 +422,7 @@ hipError_t launch_wino(const Geo &g, int kind, const void *x, const void *U, con
     w.M = reinterpret_cast<float *>(static_cast<char *>(ws) + p.v_bytes);
     w.N = g.n; w.C = g.c; w.H = g.h; w.W = g.w; w.K = g.k; w.ph = g.ph; w.pw = g.pw; w.P = g.p; w.Q = g.q;
     w.x_bytes = (uint32_t)((size_t)g.n * g.c * g.h * g.w * (g.dtype == NNV_F16 ? 2 : 4));
+    w.relu = g.relu;
     w.th = p.th; w.tw = p.tw; w.T = p.T; w.T16 = p.T16; w.K16 = p.K16; w.cpad = p.cpad; w.csteps = p.csteps;
     const int set = wino_set(kind, g.dtype);
     if (set == WS_F2) {

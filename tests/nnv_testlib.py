@@ -72,7 +72,7 @@ def gpu_transform(nnv, torch, layer, kind, half, w_np):
     return host[pad:pad + nbytes].view(dt).copy(), wt, wd, desc
 
 
-def gpu_forward(nnv, torch, layer, kind, half, w_np, x_np, bias_np=None):
+def gpu_forward(nnv, torch, layer, kind, half, w_np, x_np, bias_np=None, relu=False):
     """Transform + forward on the GPU; returns y as float64 numpy."""
     dev = torch.device("cuda:0")
     _, wt, _, desc = gpu_transform(nnv, torch, layer, kind, half, w_np)
@@ -88,7 +88,7 @@ def gpu_forward(nnv, torch, layer, kind, half, w_np, x_np, bias_np=None):
     esz = 2 if half else 4
     ybuf = torch.full((numel * esz + 2 * pad,), 0x7F, dtype=torch.uint8, device=dev)
     y = ybuf[pad:pad + numel * esz]
-    nnv.nnv_conv_forward(desc, kind, xt, wt, bias, y, ws, ws_bytes)
+    (nnv.nnv_conv_forward_relu if relu else nnv.nnv_conv_forward)(desc, kind, xt, wt, bias, y, ws, ws_bytes)
     torch.cuda.synchronize()
     yh = ybuf.cpu().numpy()
     assert (yh[:pad] == 0x7F).all() and (yh[pad + numel * esz:] == 0x7F).all(), "write outside y"

@@ -93,6 +93,29 @@ def test_bias(env, kind):
         check(env, SMALL[1], kind, True, seed=78, bias=True)
 
 
+RELU_CASES = [(SMALL[1], k) for k in (0, 1, 2, 3, 5)] + [(SMALL[13], 0), (SMALL[13], 4), (SMALL[16], 0), (SMALL[8], 1),
+                                                        (SMALL[11], 0), (SMALL[12], 0), (SMALL[12], 1),
+                                                        (Ly("grp2_wide", 16, 9, 9, 32, 3, 1, 1, groups=2), 0)]
+
+
+@pytest.mark.parametrize("layer,kind", RELU_CASES, ids=[f"{l.name}-{KIND_NAMES[k]}" for l, k in RELU_CASES])
+def test_fused_bias_relu(env, layer, kind):
+    """y = max(conv + bias, 0): every kernel family's epilogue (scalar-tap, lane-grid, tiled and
+    simple direct kernels, GEMM, Winograd output transform, depthwise), float32 and float16."""
+    nnv, torch = env
+    w, x = layer_tensors(layer, 31)
+    b = np.random.default_rng(32).standard_normal(layer.k)
+    for half in (False, True):
+        if half and kind == 5:
+            continue
+        got = gpu_forward(nnv, torch, layer, kind, half, w, x, b, relu=True)
+        ref = np.maximum(oracle_forward(layer, half, w, x, b), 0.0)
+        plain = oracle_forward(layer, half, w, x, b)
+        assert (got >= 0).all() and (got == 0).any()
+        tol = conv_tolerance(kind, half) * (2 if layer.c < 16 and half and kind == 3 else 1)
+        assert np.abs(got - ref).max() <= tol * np.abs(plain).max()
+
+
 def test_bias_depthwise(env):
     check(env, SMALL[13], 4, False, seed=79, bias=True)
 
