@@ -101,7 +101,8 @@ const char *nnv_last_hip_error(void);
  *   WINO_F6      : the same, and dtype float32 (with U and V rounded to float16 its error
  *                  exceeds the float16 bound of this library, so that pairing is refused)
  *   DEPTHWISE    : groups = C = K, R = S = 3, stride_h = stride_w in {1,2}
- *   IM2COL_GEMM  : groups 1, R,S <= 32, R*S <= 128 (float16: <= 64)
+ *   IM2COL_GEMM  : R,S <= 32, R*S <= 128 (float16: <= 64); groups 1, or up to 64 groups
+ *                  (float16 with a filter larger than 1x1: C/groups a multiple of 32)
  *   DIRECT       : any groups dividing C and K
  * (the paper's engine keys the usable kernels on filter size, stride and channel
  * divisibility in the same way, Fig. 5). */

@@ -59,7 +59,7 @@ class ConvLayer:
 
 
 STACK_NAMES = ("single3x3", "resnet18", "mobilenetv2", "vgg16", "resnet50",
-               "mobilenetv1", "squeezenet", "googlenet", "alexnet")
+               "mobilenetv1", "squeezenet", "googlenet", "alexnet", "shufflenet_g3")
 
 
 def _single() -> List[ConvLayer]:
@@ -204,9 +204,31 @@ def _alexnet() -> List[ConvLayer]:
             ConvLayer("conv5_3x3", 256, 13, 13, 256, 3, 3, 1, 1)]
 
 
+def _shufflenet_g3() -> List[ConvLayer]:
+    # The grouped-pointwise / depthwise units of the first ShuffleNet at width 1x with 3 groups:
+    # 3x3/2 stem to 24 channels, max-pool, then stages of 4, 8, 4 units with 240, 480, 960
+    # channels; a unit is 1x1 group conv to out/4 channels, 3x3 depthwise, 1x1 group conv; the
+    # first unit of a stage has stride 2 and its second 1x1 produces out - in channels (the
+    # rest comes from the pooled shortcut); the very first 1x1 is not grouped.
+    L = [ConvLayer("stem3x3_s2", 3, 224, 224, 24, 3, 3, 2, 1)]
+    cin, hw = 24, 56
+    for stage, (cout, units) in enumerate(((240, 4), (480, 8), (960, 4)), start=2):
+        mid = cout // 4
+        for u in range(units):
+            st = 2 if u == 0 else 1
+            g1 = 1 if (stage == 2 and u == 0) else 3
+            L.append(ConvLayer(f"s{stage}u{u}_pw1_g{g1}", cin, hw, hw, mid, 1, 1, 1, 0, groups=g1))
+            L.append(ConvLayer(f"s{stage}u{u}_dw_s{st}", mid, hw, hw, mid, 3, 3, st, 1, groups=mid))
+            hw = (hw + 2 - 3) // st + 1
+            L.append(ConvLayer(f"s{stage}u{u}_pw2_g3", mid, hw, hw, cout - cin if u == 0 else cout, 1, 1, 1, 0, groups=3))
+            cin = cout
+    return L
+
+
 _BUILDERS = {"single3x3": _single, "resnet18": _resnet18, "mobilenetv2": _mobilenetv2,
              "vgg16": _vgg16, "resnet50": _resnet50, "mobilenetv1": _mobilenetv1,
-             "squeezenet": _squeezenet, "googlenet": _googlenet, "alexnet": _alexnet}
+             "squeezenet": _squeezenet, "googlenet": _googlenet, "alexnet": _alexnet,
+             "shufflenet_g3": _shufflenet_g3}
 
 
 def stack(name: str) -> List[ConvLayer]:

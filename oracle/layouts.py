@@ -14,6 +14,8 @@ zero-initialised buffer; padding positions stay +0.
     off(k,c,r,s) = ((k//16 * C32 + c//32) * R*S + r*S + s) * 512
                    + ((c%32)//8)*128 + (k%16)*8 + c%8
     size = ceil(K/16) * C32 * R*S * 512,  C32 = ceil(C/32)
+  Grouped convolution (K output channels in G groups of Kg = K/G, C channels per group):
+    one such block per group, concatenated: off = (k // Kg) * size(Kg, C) + off(k % Kg, c, r, s)
   Winograd U[xi,k,c], xi = u*alpha + v: the same two formulas with (r,s) dropped
     and xi as the outermost index:
     float32: off = ((xi*K16 + k//16) * C4  + c//4 ) * 64  + (c%4)*16 + k%16
@@ -33,8 +35,14 @@ def _ceil_div(a: int, b: int) -> int:
     return -(-a // b)
 
 
-def gemm_offsets(K: int, C: int, R: int, S: int, half: bool):
-    """(size, off) with off an int64 array of shape (K, C, R, S)."""
+def gemm_offsets(K: int, C: int, R: int, S: int, half: bool, groups: int = 1):
+    """(size, off) with off an int64 array of shape (K, C, R, S); C = channels per group."""
+    if groups > 1:
+        assert K % groups == 0
+        kg = K // groups
+        gsize, goff = gemm_offsets(kg, C, R, S, half)
+        off = np.concatenate([goff + g * gsize for g in range(groups)], axis=0)
+        return int(groups * gsize), off
     k, c, r, s = np.meshgrid(np.arange(K), np.arange(C), np.arange(R), np.arange(S), indexing="ij")
     if not half:
         cb = _ceil_div(C, 4)
@@ -76,15 +84,16 @@ def _scatter(values, size, off, dtype):
     return out
 
 
-def pack_gemm(w, half: bool):
-    """OIHW weights -> flat GEMM-panel buffer (float32, or float16 rounded to nearest even)."""
+def pack_gemm(w, half: bool, groups: int = 1):
+    """OIHW weights (K, C/groups, R, S) -> flat GEMM-panel buffer (float32, or float16 rounded to
+    nearest even)."""
     K, C, R, S = w.shape
-    size, off = gemm_offsets(K, C, R, S, half)
+    size, off = gemm_offsets(K, C, R, S, half, groups)
     return _scatter(w, size, off, np.float16 if half else np.float32)
 
 
-def unpack_gemm(buf, K, C, R, S, half: bool):
-    _, off = gemm_offsets(K, C, R, S, half)
+def unpack_gemm(buf, K, C, R, S, half: bool, groups: int = 1):
+    _, off = gemm_offsets(K, C, R, S, half, groups)
     return np.asarray(buf)[off]
 
 
@@ -116,13 +125,13 @@ def unpack_depthwise(buf, C):
     return np.asarray(buf)[off].reshape(C, 1, 3, 3)
 
 
-def transformed_bytes(kind: str, K: int, Cg: int, R: int, S: int, half: bool) -> int:
+def transformed_bytes(kind: str, K: int, Cg: int, R: int, S: int, half: bool, groups: int = 1) -> int:
     """Size of the transformed-weight buffer in bytes, per kernel kind."""
     e = 2 if half else 4
     if kind == "direct":
         return K * Cg * R * S * 4
     if kind == "im2col_gemm":
-        return gemm_offsets(K, Cg, R, S, half)[0] * e
+        return gemm_offsets(K, Cg, R, S, half, groups)[0] * e
     if kind == "wino_f2":
         return wino_offsets(4, K, Cg, half)[0] * e
     if kind == "wino_f4":

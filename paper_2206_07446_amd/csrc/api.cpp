@@ -63,8 +63,15 @@ bool supported(const Geo &g, int kind) {
 bool kind_rules(const Geo &g, int kind) {
     switch (kind) {
         case NNV_DIRECT: return true;
-        case NNV_IM2COL_GEMM:   // the pack stages 16 rows x one fragment column of taps in LDS
-            return g.groups == 1 && g.r <= 32 && g.s <= 32 && g.r * g.s <= (g.dtype == NNV_F16 ? 64 : 128);
+        case NNV_IM2COL_GEMM: {
+            // the pack stages 16 rows x one fragment column of taps in LDS
+            if (g.r > 32 || g.s > 32 || g.r * g.s > (g.dtype == NNV_F16 ? 64 : 128)) return false;
+            if (g.groups == 1) return true;
+            // groups: one panel block and one transformation job per group; the float16
+            // channel-last copy needs each group's channels on a fragment boundary
+            if (g.groups > kMaxJobs) return false;
+            return g.dtype == NNV_F32 || (g.r == 1 && g.s == 1) || g.cg % 32 == 0;
+        }
         case NNV_WINO_F2:
         case NNV_WINO_F4: return g.groups == 1 && g.r == 3 && g.s == 3 && g.sh == 1 && g.sw == 1;
         case NNV_WINO_F6: return g.groups == 1 && g.r == 3 && g.s == 3 && g.sh == 1 && g.sw == 1 && g.dtype == NNV_F32;
@@ -80,7 +87,7 @@ size_t tx_bytes(const Geo &g, int kind) {
     const size_t k16 = ceil_div(g.k, 16);
     switch (kind) {
         case NNV_DIRECT: return (size_t)g.k * g.cg * g.r * g.s * sizeof(float);
-        case NNV_IM2COL_GEMM: return k16 * frag * g.r * g.s;
+        case NNV_IM2COL_GEMM: return (size_t)g.groups * ceil_div(g.kg, 16) * frag * g.r * g.s;
         case NNV_WINO_F2: return 16 * k16 * frag;
         case NNV_WINO_F4: return 36 * k16 * frag;
         case NNV_WINO_F6: return 64 * k16 * frag;
@@ -134,14 +141,24 @@ int transform_many(int n, const nnv_conv_desc *descs, const nnv_kind *kinds, con
             }
             continue;
         }
-        TransformJob &job = tbl.job[tbl.njobs];
-        if (fill_transform_job(geos[i], kinds[i], w_raw[i], w_tx[i], &job)) return NNV_E_UNSUPPORTED;
-        job.block0 = blocks;
-        blocks += job.nblocks;
-        lds = std::max(lds, transform_job_lds_bytes(job));
-        if (++tbl.njobs == kMaxJobs) {
-            hipError_t e = flush();
-            if (e != hipSuccess) return hip_fail(e);
+        // a grouped GEMM layer is one pack job per group: rows [g * Kg, (g + 1) * Kg) of the raw
+        // tensor into the g-th panel block
+        const bool grouped = kinds[i] == NNV_IM2COL_GEMM && geos[i].groups > 1;
+        Geo one = geos[i];
+        if (grouped) { one.k = one.kg; one.c = one.cg; one.groups = 1; }
+        const size_t src_step = (size_t)one.k * one.cg * one.r * one.s;
+        const size_t dst_step = grouped ? tx_bytes(one, NNV_IM2COL_GEMM) : 0;
+        for (int gi = 0; gi < (grouped ? geos[i].groups : 1); ++gi) {
+            TransformJob &job = tbl.job[tbl.njobs];
+            if (fill_transform_job(one, kinds[i], w_raw[i] + gi * src_step, static_cast<char *>(w_tx[i]) + gi * dst_step, &job))
+                return NNV_E_UNSUPPORTED;
+            job.block0 = blocks;
+            blocks += job.nblocks;
+            lds = std::max(lds, transform_job_lds_bytes(job));
+            if (++tbl.njobs == kMaxJobs) {
+                hipError_t e = flush();
+                if (e != hipSuccess) return hip_fail(e);
+            }
         }
     }
     hipError_t e = flush();

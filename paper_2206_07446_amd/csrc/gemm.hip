@@ -39,8 +39,9 @@ struct GemmParams {
     void *y;
     int N, C, H, W, K, R, S, sh, sw, ph, pw, P, Q;
     int npix;            // N*P*Q
-    int K16;
-    int cblocks;         // channel blocks (of 4 float32 / 32 half channels)
+    int K16;             // 16-row panels in all: groups * kg16
+    int kg16, Kg, Cg;    // per group: 16-row panels, output channels, input channels (groups == 1: the whole layer)
+    int cblocks;         // channel blocks (of 4 float32 / 32 half channels) of one group
     int c_rem;           // float32: C % 4, float16 1x1: C % 32 (channels of the last, partial block; 0 = full)
     uint32_t plane_bytes;   // float16 1x1: bytes of one channel plane of x (H*W*2)
     int ks_shift;        // wavefronts sharing one output tile = 1 << ks_shift
@@ -90,7 +91,9 @@ __global__ __launch_bounds__(1024) void im2col_gemm_kernel(const GemmParams g) {
     if (ltile < 0) return;                                               // whole workgroup: grid padding
     const int bx = g.m_major ? ltile % g.grid_nx : ltile / g.grid_ny;
     const int by = g.m_major ? ltile / g.grid_nx : ltile % g.grid_ny;
-    const int mb0 = by * TM;
+    const int mb0 = by * TM;                              // panel index over all groups; TM panels stay in one group
+    const int grp = mb0 / g.kg16, mbl = mb0 - grp * g.kg16;
+    const int cbase = grp * g.Cg;                         // first input channel of the group
     const int nb0 = (bx * tiles_per_wg + nt) * TN;
     const int PQ = g.P * g.Q, RS = g.R * g.S;
 
@@ -108,9 +111,9 @@ __global__ __launch_bounds__(1024) void im2col_gemm_kernel(const GemmParams g) {
         pix_img[t] = img; pix_pq[t] = pq;
         ih0[t] = p * g.sh - g.ph;
         iw0[t] = q * g.sw - g.pw;
-        if (HALF && MODE == 1) xbase[t] = (((img * g.C + slot * 8) * g.H + ih0[t]) * g.W + iw0[t]) * 2;   // NCHW
-        else if (HALF) xbase[t] = (((img * g.H + ih0[t]) * g.W + iw0[t]) * g.cpad + slot * 8) * 2;
-        else xbase[t] = (((img * g.C + slot) * g.H + ih0[t]) * g.W + iw0[t]) * 4;
+        if (HALF && MODE == 1) xbase[t] = (((img * g.C + cbase + slot * 8) * g.H + ih0[t]) * g.W + iw0[t]) * 2;   // NCHW
+        else if (HALF) xbase[t] = (((img * g.H + ih0[t]) * g.W + iw0[t]) * g.cpad + cbase + slot * 8) * 2;
+        else xbase[t] = (((img * g.C + cbase + slot) * g.H + ih0[t]) * g.W + iw0[t]) * 4;
     }
     const int tap_w = HALF ? g.cpad * 2 : 4;             // bytes per step along s
     const int tap_h = g.W * tap_w;                       // bytes per step along r
@@ -282,8 +285,9 @@ __global__ __launch_bounds__(1024) void im2col_gemm_kernel(const GemmParams g) {
                     v = 0.f;
                     for (int z = 0; z < KS; ++z) v += red[((nt * KS + z) * NREG + reg) * 64 + lane];
                 }
-                const int k = (mb0 + m) * 16 + slot * 4 + j;
-                if (k < g.K && pvalid[t]) {
+                const int kl = (mbl + m) * 16 + slot * 4 + j;         // row within the group
+                const int k = grp * g.Kg + kl;
+                if (kl < g.Kg && mbl + m < g.kg16 && pvalid[t]) {
                     const size_t o = ((size_t)pix_img[t] * g.K + k) * PQ + pix_pq[t];
                     float r = v + (g.bias ? g.bias[k] : 0.f);
                     if (g.relu) r = fmaxf(r, 0.f);
@@ -320,10 +324,11 @@ struct GemmPlan {
 static GemmPlan plan_im2col(const Geo &g) {
     GemmPlan pl{};
     const bool half = g.dtype == NNV_F16;
-    const int K16 = ceil_div(g.k, 16);
+    const int kg16 = ceil_div(g.kg, 16);
+    const int K16 = g.groups * kg16;
     const int npix16 = ceil_div(g.n * g.p * g.q, 16);
-    const int cblocks = half ? ceil_div(g.c, 32) : ceil_div(g.c, 4);
-    const bool partial = !half && (g.c % 4) != 0;
+    const int cblocks = half ? ceil_div(g.cg, 32) : ceil_div(g.cg, 4);
+    const bool partial = !half && (g.cg % 4) != 0;
     if (g.r == 1 && g.s == 1 && !partial) pl.mode = 1;
     else if (g.r == 3 && g.s == 3) pl.mode = 3;
     else if (g.s == 7 && !half) pl.mode = 7;
@@ -349,6 +354,10 @@ static GemmPlan plan_im2col(const Geo &g) {
     if (tiles(2, 2) >= 4096 && !(half && pl.mode == 1)) { pl.tm = 2; pl.tn = 2; pl.ks_shift = 0; }
     else if (tiles(2, 1) >= 160) { pl.tm = 2; pl.tn = 1; pl.ks_shift = split_for(tiles(2, 1), 2048); }
     else { pl.tm = 1; pl.tn = 1; pl.ks_shift = split_for(tiles(1, 1), 768); }
+    if (g.groups > 1 && kg16 % pl.tm != 0) {       // a wavefront's panels must belong to one group
+        pl.tm = 1; pl.tn = 1;
+        pl.ks_shift = split_for(tiles(1, 1), 2048);
+    }
     // depth of the register ring: never more sets than the wavefront has chunks to load
     const int units_per_wave = ceil_div(nunits, 1 << pl.ks_shift);
     const int chunk_units = pl.mode == 1 ? (half ? 2 : 8) : 1;
@@ -396,11 +405,13 @@ hipError_t launch_im2col(const Geo &g, const void *x, const void *w, const float
     gp.N = g.n; gp.C = g.c; gp.H = g.h; gp.W = g.w; gp.K = g.k; gp.R = g.r; gp.S = g.s;
     gp.sh = g.sh; gp.sw = g.sw; gp.ph = g.ph; gp.pw = g.pw; gp.P = g.p; gp.Q = g.q;
     gp.npix = g.n * g.p * g.q;
-    gp.K16 = ceil_div(g.k, 16);
+    gp.kg16 = ceil_div(g.kg, 16);
+    gp.K16 = g.groups * gp.kg16;
+    gp.Kg = g.kg; gp.Cg = g.cg;
     gp.cpad = ceil_div(g.c, 32) * 32;
-    gp.cblocks = half ? ceil_div(g.c, 32) : ceil_div(g.c, 4);
+    gp.cblocks = half ? ceil_div(g.cg, 32) : ceil_div(g.cg, 4);
     const bool gather = half && pl.mode == 1;      // float16 1x1: B fragments gathered from NCHW
-    gp.c_rem = gather ? g.c % 32 : half ? 0 : g.c % 4;
+    gp.c_rem = gather ? g.cg % 32 : half ? 0 : g.cg % 4;
     gp.plane_bytes = (uint32_t)(g.h * g.w * 2);
     gp.ks_shift = pl.ks_shift;
     gp.half_out = half;

@@ -30,8 +30,11 @@ def conv_tolerance(kind: int, half: bool) -> float:
 def applicable_kinds(layer, half=False):
     """Kernel kinds that can run the layer (F(6x6) exists in float32 only)."""
     kinds = [0]
+    taps_ok = layer.r * layer.s <= (64 if half else 128)
+    if layer.groups > 1 and taps_ok and layer.groups <= 64 and (not half or layer.r * layer.s == 1 or layer.cg % 32 == 0):
+        kinds.append(1)          # grouped convolution on the matrix cores: one panel block per group
     if layer.groups == 1:
-        if layer.r * layer.s <= (64 if half else 128):
+        if taps_ok:
             kinds.append(1)
         if layer.winograd_ok:
             kinds += [2, 3] if half else [2, 3, 5]
@@ -40,12 +43,12 @@ def applicable_kinds(layer, half=False):
     return kinds
 
 
-def oracle_transformed(w: np.ndarray, kind: int, half: bool):
+def oracle_transformed(w: np.ndarray, kind: int, half: bool, groups: int = 1):
     """Expected transformed-weight buffer (and, for Winograd, the float64 values + abs bound)."""
     if kind == 0:
         return w.reshape(-1).copy(), None
     if kind == 1:
-        return OL.pack_gemm(w, half), None
+        return OL.pack_gemm(w, half, groups), None
     if kind == 4:
         return OL.pack_depthwise(w, half), None
     var = wino_variant(kind, half)

@@ -41,14 +41,19 @@ def test_kind_supported_rules():
     assert [nnv.nnv_kind_supported(d, k) for k in range(5)] == [True, True, True, True, False]
     d = D(stride_h=2, stride_w=2)
     assert [nnv.nnv_kind_supported(d, k) for k in range(5)] == [True, True, False, False, False]
-    d = D(groups=16)
-    assert [nnv.nnv_kind_supported(d, k) for k in range(5)] == [True, False, False, False, True]
+    d = D(groups=16)      # depthwise; also a (wasteful) grouped GEMM: one 16-row panel per channel
+    assert [nnv.nnv_kind_supported(d, k) for k in range(5)] == [True, True, False, False, True]
     d = D(groups=16, stride_h=2, stride_w=2)
     assert nnv.nnv_kind_supported(d, nnv.DEPTHWISE)
     d = D(r=7, s=7, pad_h=3, pad_w=3, stride_h=2, stride_w=2, c=3)
     assert [nnv.nnv_kind_supported(d, k) for k in range(5)] == [True, True, False, False, False]
     d = D(groups=2)
-    assert [nnv.nnv_kind_supported(d, k) for k in range(5)] == [True, False, False, False, False]
+    assert [nnv.nnv_kind_supported(d, k) for k in range(5)] == [True, True, False, False, False]
+    # grouped GEMM: at most 64 groups; float16 with a 3x3 filter needs 32-channel-aligned groups
+    assert not nnv.nnv_kind_supported(D(c=128, k=128, groups=128), 1)
+    assert not nnv.nnv_kind_supported(D(groups=2, dtype=1), 1)
+    assert nnv.nnv_kind_supported(D(c=64, k=64, groups=2, dtype=1), 1)
+    assert nnv.nnv_kind_supported(D(groups=2, dtype=1, r=1, s=1, pad_h=0, pad_w=0), 1)
 
 
 @pytest.mark.parametrize("bad", [dict(n=0), dict(c=-1), dict(groups=3), dict(stride_h=0), dict(pad_w=-1),
@@ -93,7 +98,7 @@ def test_transformed_bytes_match_oracle_layout_sizes(name):
                 if not nnv.nnv_kind_supported(d, kind):
                     assert nnv.nnv_transformed_bytes(d, kind) == 0
                     continue
-                exp = OL.transformed_bytes(KNAME[kind], layer.k, layer.cg, layer.r, layer.s, half)
+                exp = OL.transformed_bytes(KNAME[kind], layer.k, layer.cg, layer.r, layer.s, half, layer.groups)
                 assert nnv.nnv_transformed_bytes(d, kind) == exp, (layer.name, kind, half)
 
 

@@ -75,6 +75,13 @@ SMALL = [
     ConvLayer("plane5x7", 9, 5, 7, 8, 3, 3, 1, 1),          # whole plane in one wavefront, not square
     Ly("plane7_pad0", 9, 7, 7, 8, 3, 1, 0),
     Ly("plane8", 9, 8, 8, 8, 3, 1, 1),                       # one more than the lane grid takes
+    # grouped convolutions (one GEMM panel block per group on the matrix cores)
+    Ly("g3_pw", 240, 14, 14, 240, 1, 1, 0, groups=3),        # grouped pointwise, Kg = Cg = 80
+    Ly("g3_pw_in", 24, 14, 14, 60, 1, 1, 0, groups=3),       # Kg = 20: panels padded per group
+    Ly("g32_3x3", 128, 14, 14, 128, 3, 1, 1, groups=32),     # Kg = Cg = 4
+    Ly("g2_5x5", 96, 13, 13, 64, 5, 1, 2, groups=2),
+    Ly("g2_3x3_aligned", 64, 12, 12, 96, 3, 1, 1, groups=2), # Cg = 32: float16 channel-last copy applies
+    Ly("g4_s2_n2", 32, 11, 11, 48, 3, 2, 1, groups=4, n=2),
 ]
 CASES = [(l, k, h) for h in (False, True) for l in SMALL for k in applicable_kinds(l, h)]
 
@@ -182,11 +189,11 @@ def test_full_resnet50_stack_f32_f16(env):
     _run_stack(env, "resnet50", [False, True])
 
 
-@pytest.mark.parametrize("name", ["mobilenetv1", "squeezenet", "googlenet", "alexnet"])
+@pytest.mark.parametrize("name", ["mobilenetv1", "squeezenet", "googlenet", "alexnet", "shufflenet_g3"])
 def test_further_table4_shaped_stacks(env, name):
     """More of the paper's Table 4 networks: depthwise-separable blocks, fire modules (7x7/2 stem
     without padding, odd feature-map sizes 109/54/27/13) and inception modules (5x5 branches)."""
-    _run_stack(env, name, [False, True] if name in ("googlenet", "alexnet") else [False])
+    _run_stack(env, name, [False, True] if name in ("googlenet", "alexnet", "shufflenet_g3") else [False])
 
 
 def test_error_paths_on_device(env):

@@ -23,7 +23,9 @@ def L(c, k, r=3, hw=8, stride=1, pad=1, groups=1):
 
 GEMM_LAYERS = [L(16, 16), L(37, 20), L(3, 64, r=7, hw=16, stride=2, pad=3), L(144, 24, r=1, pad=0),
                L(1100, 40, r=1, pad=0), L(130, 33), L(5, 3, r=5, pad=2), L(64, 128, stride=2),
-               L(3, 64, r=11, hw=24, stride=4, pad=2), L(21, 24, r=11, hw=12, pad=5), L(40, 20, r=8, hw=10, pad=4)]
+               L(3, 64, r=11, hw=24, stride=4, pad=2), L(21, 24, r=11, hw=12, pad=5), L(40, 20, r=8, hw=10, pad=4),
+               # grouped: one panel block per group (Kg = 20, 6, 80; channels per group 12, 64, 80)
+               L(36, 60, groups=3), L(128, 12, groups=2), L(240, 240, r=1, pad=0, groups=3)]
 WINO_LAYERS = [L(16, 16), L(37, 20), L(64, 64), L(3, 64), L(130, 33), L(200, 17)]
 DW_LAYERS = [L(32, 32, groups=32), L(144, 144, groups=144), L(5, 5, groups=5), L(960, 960, groups=960)]
 
@@ -41,13 +43,15 @@ def _index_coded(layer, half):
 @pytest.mark.parametrize("layer", GEMM_LAYERS, ids=lambda l: l.name)
 def test_gemm_pack_bit_exact(env, layer, half):
     nnv, torch = env
-    if half and layer.r * layer.s > 64:       # float16 fragments span 32 channels: 64 taps at most
-        desc = nnv.make_desc(layer, nnv.F16)
-        assert not nnv.nnv_kind_supported(desc, nnv.IM2COL_GEMM)
+    # float16 fragments span 32 channels: 64 taps at most, and groups must start on a fragment
+    # boundary unless the filter is 1x1
+    refused = half and (layer.r * layer.s > 64 or (layer.groups > 1 and layer.r * layer.s > 1 and layer.cg % 32))
+    if refused:
+        assert not nnv.nnv_kind_supported(nnv.make_desc(layer, nnv.F16), nnv.IM2COL_GEMM)
         return
     for w in (_index_coded(layer, half), layer_tensors(layer, 5)[0]):
         got, *_ = gpu_transform(nnv, torch, layer, nnv.IM2COL_GEMM, half, w)
-        exp, _ = oracle_transformed(w, nnv.IM2COL_GEMM, half)
+        exp, _ = oracle_transformed(w, nnv.IM2COL_GEMM, half, layer.groups)
         assert got.dtype == exp.dtype and got.shape == exp.shape
         assert np.array_equal(got.view(np.uint16 if half else np.uint32), exp.view(np.uint16 if half else np.uint32))
 

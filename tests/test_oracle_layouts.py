@@ -115,3 +115,25 @@ def test_transformed_size_ratios():
     assert L.transformed_bytes("wino_f4", K, C, 3, 3, True) * 9 == raw * 18
     assert L.wino_offsets(8, K, C, False)[0] * 4 * 9 == raw * 64
     assert L.transformed_bytes("depthwise", 64, 1, 3, 3, False) == 64 * 9 * 4
+
+
+def test_grouped_gemm_map_by_hand_and_by_properties():
+    """Two groups of two output channels, one channel each, 1x1, float32: each group is one
+    64-float fragment, rows at k % 16 -> offsets 0, 1 | 64, 65 (worked out by hand)."""
+    size, off = L.gemm_offsets(4, 1, 1, 1, False, groups=2)
+    assert size == 128 and off.ravel().tolist() == [0, 1, 64, 65]
+    # float16, 3 groups of 5 output channels, 40 channels per group, 3x3: injective, in range,
+    # group g confined to its own block, round trip, padding zero
+    K, C, G = 15, 40, 3
+    size, off = L.gemm_offsets(K, C, 3, 3, True, groups=G)
+    gsize = L.gemm_offsets(K // G, C, 3, 3, True)[0]
+    assert size == G * gsize and len(np.unique(off)) == off.size and off.min() >= 0 and off.max() < size
+    for g in range(G):
+        blk = off[g * 5:(g + 1) * 5]
+        assert blk.min() >= g * gsize and blk.max() < (g + 1) * gsize
+    w = np.random.default_rng(4).standard_normal((K, C, 3, 3)).astype(np.float32)
+    buf = L.pack_gemm(w, True, groups=G)
+    np.testing.assert_array_equal(L.unpack_gemm(buf, K, C, 3, 3, True, groups=G), w.astype(np.float16))
+    mask = np.ones(size, bool); mask[off.ravel()] = False
+    assert (buf[mask] == 0).all()
+    assert L.transformed_bytes("im2col_gemm", K, C, 3, 3, True, groups=G) == size * 2

@@ -42,3 +42,16 @@ def test_fire_modules_chain_and_sizes():
     assert [l.h for l in s if l.name.endswith("squeeze")] == [54, 54, 54, 27, 27, 27, 27, 13]
     for sq, e1, e3 in zip(s[1::3], s[2::3], s[3::3]):
         assert e1.c == sq.k == e3.c and e1.k == e3.k
+
+
+def test_shufflenet_units():
+    """Width 1x, 3 groups: the architecture's own paper quotes 140 M multiply-adds for it (the
+    classifier's 0.96 M included); Table 4's figure for "ShuffleNet" (3.6 M parameters, 1.9 GFLOPs)
+    matches none of that paper's widths, so it is not asserted."""
+    s = stack("shufflenet_g3")
+    assert len(s) == 1 + 3 * 16
+    assert abs(sum(l.macs for l in s) / 1e6 + 0.96 - 140) < 3
+    grouped = [l for l in s if l.groups == 3]
+    assert len(grouped) == 31 and all(l.r == 1 and l.c % 3 == 0 and l.k % 3 == 0 for l in grouped)
+    assert s[1].groups == 1                                   # the first pointwise conv is not grouped
+    assert [l.k for l in s if l.name.endswith("u0_pw2_g3")] == [216, 240, 480]
