@@ -42,7 +42,7 @@ typedef enum {
     NNV_IM2COL_GEMM = 1, /* implicit im2col GEMM from matrix-instruction-ordered weight panels */
     NNV_WINO_F2 = 2,     /* Winograd F(2x2,3x3): 4x4 tiles                                     */
     NNV_WINO_F4 = 3,     /* Winograd F(4x4,3x3): 6x6 tiles                                     */
-    NNV_DEPTHWISE = 4,   /* 3x3 depthwise (groups = C = K) from channel-blocked tap-major weights */
+    NNV_DEPTHWISE = 4,   /* 3x3 or 5x5 depthwise (groups = C = K) from channel-blocked tap-major weights */
     NNV_WINO_F6 = 5,     /* Winograd F(6x6,3x3): 8x8 tiles, the tile size of Fig. 3; float32 only */
     NNV_KIND_COUNT = 6
 } nnv_kind;
@@ -100,7 +100,7 @@ const char *nnv_last_hip_error(void);
  *   WINO_F2/F4   : R = S = 3, stride 1, groups 1
  *   WINO_F6      : the same, and dtype float32 (with U and V rounded to float16 its error
  *                  exceeds the float16 bound of this library, so that pairing is refused)
- *   DEPTHWISE    : groups = C = K, R = S = 3, stride_h = stride_w in {1,2}
+ *   DEPTHWISE    : groups = C = K, R = S in {3,5}, stride_h = stride_w in {1,2}
  *   IM2COL_GEMM  : R,S <= 32, R*S <= 128 (float16: <= 64); groups 1, or up to 64 groups
  *                  (float16 with a filter larger than 1x1: C/groups a multiple of 32)
  *   DIRECT       : any groups dividing C and K

@@ -59,7 +59,7 @@ class ConvLayer:
 
 
 STACK_NAMES = ("single3x3", "resnet18", "mobilenetv2", "vgg16", "resnet50",
-               "mobilenetv1", "squeezenet", "googlenet", "alexnet", "shufflenet_g3")
+               "mobilenetv1", "squeezenet", "googlenet", "alexnet", "shufflenet_g3", "efficientnet_b0")
 
 
 def _single() -> List[ConvLayer]:
@@ -225,10 +225,36 @@ def _shufflenet_g3() -> List[ConvLayer]:
     return L
 
 
+def _efficientnet_b0() -> List[ConvLayer]:
+    # Published B0 schedule (expansion, depthwise filter, stride, output width, repeats); every
+    # block is [1x1 expand], k x k depthwise, squeeze-and-excitation (two 1x1 convs on the pooled
+    # 1x1 map, squeezed to a quarter of the block's input width), 1x1 project; 1x1 head to 1280.
+    sched = ((1, 3, 1, 16, 1), (6, 3, 2, 24, 2), (6, 5, 2, 40, 2), (6, 3, 2, 80, 3),
+             (6, 5, 1, 112, 3), (6, 5, 2, 192, 4), (6, 3, 1, 320, 1))
+    L = [ConvLayer("stem3x3_s2", 3, 224, 224, 32, 3, 3, 2, 1)]
+    cin, hw, b = 32, 112, 0
+    for t, k, s0, cout, reps in sched:
+        for i in range(reps):
+            st = s0 if i == 0 else 1
+            hid = cin * t
+            if t != 1:
+                L.append(ConvLayer(f"b{b}_expand", cin, hw, hw, hid, 1, 1, 1, 0))
+            L.append(ConvLayer(f"b{b}_dw{k}x{k}_s{st}", hid, hw, hw, hid, k, k, st, k // 2, groups=hid))
+            hw = (hw + 2 * (k // 2) - k) // st + 1
+            se = max(1, cin // 4)
+            L.append(ConvLayer(f"b{b}_se_reduce", hid, 1, 1, se, 1, 1, 1, 0))
+            L.append(ConvLayer(f"b{b}_se_expand", se, 1, 1, hid, 1, 1, 1, 0))
+            L.append(ConvLayer(f"b{b}_project", hid, hw, hw, cout, 1, 1, 1, 0))
+            cin = cout
+            b += 1
+    L.append(ConvLayer("head1x1", cin, hw, hw, 1280, 1, 1, 1, 0))
+    return L
+
+
 _BUILDERS = {"single3x3": _single, "resnet18": _resnet18, "mobilenetv2": _mobilenetv2,
              "vgg16": _vgg16, "resnet50": _resnet50, "mobilenetv1": _mobilenetv1,
              "squeezenet": _squeezenet, "googlenet": _googlenet, "alexnet": _alexnet,
-             "shufflenet_g3": _shufflenet_g3}
+             "shufflenet_g3": _shufflenet_g3, "efficientnet_b0": _efficientnet_b0}
 
 
 def stack(name: str) -> List[ConvLayer]:

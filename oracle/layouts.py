@@ -20,7 +20,8 @@ zero-initialised buffer; padding positions stay +0.
     and xi as the outermost index:
     float32: off = ((xi*K16 + k//16) * C4  + c//4 ) * 64  + (c%4)*16 + k%16
     float16: off = ((xi*K16 + k//16) * C32 + c//32) * 512 + ((c%32)//8)*128 + (k%16)*8 + c%8
-  Depthwise (C,1,3,3): off(c,r,s) = (c//32)*288 + (r*3+s)*32 + c%32,  size = ceil(C/32)*288
+  Depthwise (C,1,R,S), R = S = 3 or 5: off(c,r,s) = (c//32)*R*S*32 + (r*S+s)*32 + c%32,
+    size = ceil(C/32)*R*S*32   (3x3: 288 per 32 channels)
 
 Pins (tests/test_oracle_layouts.py): every map is injective and in range, the
 unpack of a pack is the identity, sizes follow the formulas, padding is zero,
@@ -71,11 +72,11 @@ def wino_offsets(alpha: int, K: int, C: int, half: bool):
     return int(size), off.astype(np.int64)
 
 
-def depthwise_offsets(C: int):
-    """(size, off) with off of shape (C, 3, 3)."""
-    c, r, s = np.meshgrid(np.arange(C), np.arange(3), np.arange(3), indexing="ij")
-    off = (c // 32) * 288 + (r * 3 + s) * 32 + c % 32
-    return int(_ceil_div(C, 32) * 288), off.astype(np.int64)
+def depthwise_offsets(C: int, R: int = 3, S: int = 3):
+    """(size, off) with off of shape (C, R, S)."""
+    c, r, s = np.meshgrid(np.arange(C), np.arange(R), np.arange(S), indexing="ij")
+    off = (c // 32) * (R * S * 32) + (r * S + s) * 32 + c % 32
+    return int(_ceil_div(C, 32) * R * S * 32), off.astype(np.int64)
 
 
 def _scatter(values, size, off, dtype):
@@ -114,15 +115,15 @@ def unpack_wino(buf, alpha, K, C, half: bool):
 
 
 def pack_depthwise(w, half: bool):
-    C = w.shape[0]
-    assert w.shape[1:] == (1, 3, 3)
-    size, off = depthwise_offsets(C)
-    return _scatter(w.reshape(C, 3, 3), size, off, np.float16 if half else np.float32)
+    C, one, R, S = w.shape
+    assert one == 1 and R == S and R in (3, 5)
+    size, off = depthwise_offsets(C, R, S)
+    return _scatter(w.reshape(C, R, S), size, off, np.float16 if half else np.float32)
 
 
-def unpack_depthwise(buf, C):
-    _, off = depthwise_offsets(C)
-    return np.asarray(buf)[off].reshape(C, 1, 3, 3)
+def unpack_depthwise(buf, C, R: int = 3, S: int = 3):
+    _, off = depthwise_offsets(C, R, S)
+    return np.asarray(buf)[off].reshape(C, 1, R, S)
 
 
 def transformed_bytes(kind: str, K: int, Cg: int, R: int, S: int, half: bool, groups: int = 1) -> int:
@@ -139,5 +140,5 @@ def transformed_bytes(kind: str, K: int, Cg: int, R: int, S: int, half: bool, gr
     if kind == "wino_f6":
         return wino_offsets(8, K, Cg, half)[0] * e
     if kind == "depthwise":
-        return depthwise_offsets(K)[0] * e
+        return depthwise_offsets(K, R, S)[0] * e
     raise ValueError(kind)

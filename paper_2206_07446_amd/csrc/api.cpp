@@ -76,7 +76,7 @@ bool kind_rules(const Geo &g, int kind) {
         case NNV_WINO_F4: return g.groups == 1 && g.r == 3 && g.s == 3 && g.sh == 1 && g.sw == 1;
         case NNV_WINO_F6: return g.groups == 1 && g.r == 3 && g.s == 3 && g.sh == 1 && g.sw == 1 && g.dtype == NNV_F32;
         case NNV_DEPTHWISE:
-            return g.groups == g.c && g.c == g.k && g.r == 3 && g.s == 3 && g.sh == g.sw && (g.sh == 1 || g.sh == 2);
+            return g.groups == g.c && g.c == g.k && g.r == g.s && (g.r == 3 || g.r == 5) && g.sh == g.sw && (g.sh == 1 || g.sh == 2);
         default: return false;
     }
 }
@@ -91,7 +91,7 @@ size_t tx_bytes(const Geo &g, int kind) {
         case NNV_WINO_F2: return 16 * k16 * frag;
         case NNV_WINO_F4: return 36 * k16 * frag;
         case NNV_WINO_F6: return 64 * k16 * frag;
-        case NNV_DEPTHWISE: return (size_t)ceil_div(g.c, 32) * 288 * (half ? 2 : 4);
+        case NNV_DEPTHWISE: return (size_t)ceil_div(g.c, 32) * g.r * g.s * 32 * (half ? 2 : 4);
         default: return 0;
     }
 }

@@ -428,13 +428,13 @@ hipError_t launch_direct(const Geo &g, const void *x, const float *w, const floa
     return launch_direct_t<float>(g, static_cast<const float *>(x), w, bias, static_cast<float *>(y), st_);
 }
 
-// ------------------------------------------------------------------ depthwise 3x3
+// ------------------------------------------------------------------ depthwise 3x3 / 5x5
 
 struct DwParams {
     int N, C, H, W, st, ph, pw, P, Q, relu;
 };
 
-template <typename T>
+template <typename T, int FS>
 __global__ __launch_bounds__(256) void depthwise_kernel(const T *__restrict__ x, const T *__restrict__ wp,
                                                         const float *__restrict__ bias, T *__restrict__ y,
                                                         const DwParams d) {
@@ -442,20 +442,20 @@ __global__ __launch_bounds__(256) void depthwise_kernel(const T *__restrict__ x,
     const int c = blockIdx.y, img = blockIdx.z;
     if (pq >= d.P * d.Q) return;
     const int p = pq / d.Q, q = pq - p * d.Q;
-    const T *wc = wp + (size_t)(c >> 5) * 288 + (c & 31);
+    const T *wc = wp + (size_t)(c >> 5) * (FS * FS * 32) + (c & 31);
     const T *xc = x + ((size_t)img * d.C + c) * d.H * d.W;
     const int ih0 = p * d.st - d.ph, iw0 = q * d.st - d.pw;
     float acc = bias ? bias[c] : 0.f;
 #pragma unroll
-    for (int r = 0; r < 3; ++r) {
+    for (int r = 0; r < FS; ++r) {
         const int ih = ih0 + r;
         const bool rok = ih >= 0 && ih < d.H;
 #pragma unroll
-        for (int s = 0; s < 3; ++s) {
+        for (int s = 0; s < FS; ++s) {
             const int iw = iw0 + s;
             const bool ok = rok && iw >= 0 && iw < d.W;
             const float xv = ok ? ld<T>(xc, (size_t)ih * d.W + iw) : 0.f;
-            acc = fmaf(xv, ld<T>(wc, (r * 3 + s) * 32), acc);
+            acc = fmaf(xv, ld<T>(wc, (r * FS + s) * 32), acc);
         }
     }
     st<T>(y, ((size_t)img * d.C + c) * d.P * d.Q + pq, act(acc, d.relu));
@@ -465,12 +465,16 @@ hipError_t launch_depthwise(const Geo &g, const void *x, const void *w, const fl
     if (g.c > 65535) return hipErrorInvalidValue;
     DwParams d{g.n, g.c, g.h, g.w, g.sh, g.ph, g.pw, g.p, g.q, g.relu};
     dim3 grid(ceil_div(g.p * g.q, 256), g.c, g.n);
-    if (g.dtype == NNV_F16)
-        hipLaunchKernelGGL(depthwise_kernel<__half>, grid, dim3(256), 0, st_, static_cast<const __half *>(x),
-                           static_cast<const __half *>(w), bias, static_cast<__half *>(y), d);
-    else
-        hipLaunchKernelGGL(depthwise_kernel<float>, grid, dim3(256), 0, st_, static_cast<const float *>(x),
-                           static_cast<const float *>(w), bias, static_cast<float *>(y), d);
+    const bool five = g.r == 5;
+    if (g.dtype == NNV_F16) {
+        auto k = five ? depthwise_kernel<__half, 5> : depthwise_kernel<__half, 3>;
+        hipLaunchKernelGGL(k, grid, dim3(256), 0, st_, static_cast<const __half *>(x), static_cast<const __half *>(w), bias,
+                           static_cast<__half *>(y), d);
+    } else {
+        auto k = five ? depthwise_kernel<float, 5> : depthwise_kernel<float, 3>;
+        hipLaunchKernelGGL(k, grid, dim3(256), 0, st_, static_cast<const float *>(x), static_cast<const float *>(w), bias,
+                           static_cast<float *>(y), d);
+    }
     return hipGetLastError();
 }
 

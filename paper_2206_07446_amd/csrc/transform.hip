@@ -198,15 +198,16 @@ __device__ static inline void gemm_block(const TransformJob &job, int local_bloc
     }
 }
 
-// Depthwise repack (C,1,3,3) -> [C/32][9 taps][32 channels]; 256 outputs per block.
+// Depthwise repack (C,1,R,S) -> [C/32][R*S taps][32 channels]; 256 outputs per block.
 template <bool HALF>
 __device__ static inline void dw_block(const TransformJob &job, int local_block) {
-    const int total = ((job.C + 31) / 32) * 288;
+    const int per = job.RS * 32;
+    const int total = ((job.C + 31) / 32) * per;
     const int o = local_block * 256 + threadIdx.x;
     if (o >= total) return;
-    const int cb = o / 288, rem = o - cb * 288, tap = rem >> 5, ci = rem & 31;
+    const int cb = o / per, rem = o - cb * per, tap = rem >> 5, ci = rem & 31;
     const int c = cb * 32 + ci;
-    const float v = (c < job.C) ? job.src[(size_t)c * 9 + tap] : 0.f;
+    const float v = (c < job.C) ? job.src[(size_t)c * job.RS + tap] : 0.f;
     if (HALF) static_cast<__half *>(job.dst)[o] = __float2half_rn(v);
     else static_cast<float *>(job.dst)[o] = v;
 }
@@ -275,7 +276,7 @@ int fill_transform_job(const Geo &g, int kind, const float *src, void *dst, Tran
         job->type = JOB_DW;
         job->cchunk = 32;
         job->nchunks = 1;
-        job->nblocks = ceil_div(ceil_div(g.c, 32) * 288, 256);
+        job->nblocks = ceil_div(ceil_div(g.c, 32) * g.r * g.s * 32, 256);
         job->C = g.c;
     } else {
         return -1;

@@ -38,7 +38,7 @@ def applicable_kinds(layer, half=False):
             kinds.append(1)
         if layer.winograd_ok:
             kinds += [2, 3] if half else [2, 3, 5]
-    if layer.is_depthwise and layer.r == 3 and layer.stride in (1, 2):
+    if layer.is_depthwise and layer.r == layer.s and layer.r in (3, 5) and layer.stride in (1, 2):
         kinds.append(4)
     return kinds
 

@@ -67,6 +67,8 @@ SMALL = [
     Ly("dw_s1", 32, 14, 14, 32, 3, 1, 1, groups=32),
     Ly("dw_s2", 48, 15, 15, 48, 3, 2, 1, groups=48),
     Ly("dw_n2", 5, 7, 7, 5, 3, 1, 1, groups=5, n=2),
+    Ly("dw5_s1", 40, 14, 14, 40, 5, 1, 2, groups=40),
+    Ly("dw5_s2", 72, 15, 13, 72, 5, 2, 2, groups=72, n=2),
     Ly("grp2", 8, 9, 9, 12, 3, 1, 1, groups=2),
     Ly("batch3", 20, 11, 13, 40, 3, 1, 1, n=3),
     Ly("batch3_pw", 24, 9, 7, 72, 1, 1, 0, n=3),
@@ -100,8 +102,11 @@ def test_bias(env, kind):
         check(env, SMALL[1], kind, True, seed=78, bias=True)
 
 
-RELU_CASES = [(SMALL[1], k) for k in (0, 1, 2, 3, 5)] + [(SMALL[13], 0), (SMALL[13], 4), (SMALL[16], 0), (SMALL[8], 1),
-                                                        (SMALL[11], 0), (SMALL[12], 0), (SMALL[12], 1),
+_BY_NAME = {l.name: l for l in SMALL}
+RELU_CASES = [(_BY_NAME["ragged"], k) for k in (0, 1, 2, 3, 5)] + [(_BY_NAME["dw_s1"], 0), (_BY_NAME["dw_s1"], 4),
+                                                                 (_BY_NAME["dw5_s2"], 4), (_BY_NAME["grp2"], 0),
+                                                                 (_BY_NAME["grp2"], 1), (_BY_NAME["pw"], 1),
+                                                                 (_BY_NAME["deep"], 0), (_BY_NAME["k5"], 0), (_BY_NAME["k5"], 1),
                                                         (Ly("grp2_wide", 16, 9, 9, 32, 3, 1, 1, groups=2), 0)]
 
 
@@ -113,7 +118,7 @@ def test_fused_bias_relu(env, layer, kind):
     w, x = layer_tensors(layer, 31)
     b = np.random.default_rng(32).standard_normal(layer.k)
     for half in (False, True):
-        if half and kind == 5:
+        if kind not in applicable_kinds(layer, half):
             continue
         got = gpu_forward(nnv, torch, layer, kind, half, w, x, b, relu=True)
         ref = np.maximum(oracle_forward(layer, half, w, x, b), 0.0)
@@ -189,11 +194,11 @@ def test_full_resnet50_stack_f32_f16(env):
     _run_stack(env, "resnet50", [False, True])
 
 
-@pytest.mark.parametrize("name", ["mobilenetv1", "squeezenet", "googlenet", "alexnet", "shufflenet_g3"])
+@pytest.mark.parametrize("name", ["mobilenetv1", "squeezenet", "googlenet", "alexnet", "shufflenet_g3", "efficientnet_b0"])
 def test_further_table4_shaped_stacks(env, name):
     """More of the paper's Table 4 networks: depthwise-separable blocks, fire modules (7x7/2 stem
     without padding, odd feature-map sizes 109/54/27/13) and inception modules (5x5 branches)."""
-    _run_stack(env, name, [False, True] if name in ("googlenet", "alexnet", "shufflenet_g3") else [False])
+    _run_stack(env, name, [False, True] if name in ("googlenet", "alexnet", "shufflenet_g3", "efficientnet_b0") else [False])
 
 
 def test_error_paths_on_device(env):

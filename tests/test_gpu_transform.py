@@ -27,7 +27,8 @@ GEMM_LAYERS = [L(16, 16), L(37, 20), L(3, 64, r=7, hw=16, stride=2, pad=3), L(14
                # grouped: one panel block per group (Kg = 20, 6, 80; channels per group 12, 64, 80)
                L(36, 60, groups=3), L(128, 12, groups=2), L(240, 240, r=1, pad=0, groups=3)]
 WINO_LAYERS = [L(16, 16), L(37, 20), L(64, 64), L(3, 64), L(130, 33), L(200, 17)]
-DW_LAYERS = [L(32, 32, groups=32), L(144, 144, groups=144), L(5, 5, groups=5), L(960, 960, groups=960)]
+DW_LAYERS = [L(32, 32, groups=32), L(144, 144, groups=144), L(5, 5, groups=5), L(960, 960, groups=960),
+             L(40, 40, r=5, pad=2, groups=40), L(672, 672, r=5, pad=2, stride=2, groups=672)]
 
 
 def _index_coded(layer, half):

@@ -137,3 +137,16 @@ def test_grouped_gemm_map_by_hand_and_by_properties():
     mask = np.ones(size, bool); mask[off.ravel()] = False
     assert (buf[mask] == 0).all()
     assert L.transformed_bytes("im2col_gemm", K, C, 3, 3, True, groups=G) == size * 2
+
+
+def test_depthwise_5x5_map():
+    """5x5 taps: 25 x 32 floats per 32 channels; channel 33, tap (1, 2) of 40 channels sits in the
+    second block at tap 7, lane 1: 800 + 7 * 32 + 1 = 1025 (worked out by hand)."""
+    size, off = L.depthwise_offsets(40, 5, 5)
+    assert size == 2 * 800 and off[33, 1, 2] == 1025 and off[0, 0, 0] == 0 and off[31, 4, 4] == 24 * 32 + 31
+    flat = off.ravel()
+    assert flat.min() >= 0 and flat.max() < size and len(np.unique(flat)) == flat.size
+    w = np.arange(40 * 25, dtype=np.float32).reshape(40, 1, 5, 5)
+    buf = L.pack_depthwise(w, False)
+    np.testing.assert_array_equal(L.unpack_depthwise(buf, 40, 5, 5), w)
+    assert L.transformed_bytes("depthwise", 40, 1, 5, 5, True) == size * 2

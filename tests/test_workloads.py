@@ -9,7 +9,7 @@ from nnv_workloads import stack, STACK_NAMES
 TABLE4 = {"resnet18": (11.17, 0.51, 12.7, 3.9), "resnet50": (23.45, 2.05, 25.7, 7.8),
           "mobilenetv2": (2.19, 1.28, 3.7, 0.6), "mobilenetv1": (3.19, 1.03, 4.4, 1.1),
           "squeezenet": (1.24, 0.0, 1.4, 1.7), "googlenet": (5.97, 1.03, 7.1, 3.2),
-          "alexnet": (2.47, 58.63, 61.3, 1.4)}
+          "alexnet": (2.47, 58.63, 61.3, 1.4), "efficientnet_b0": (3.96, 1.28, 5.4, 0.8)}
 
 
 @pytest.mark.parametrize("name", sorted(TABLE4))
