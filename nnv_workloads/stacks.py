@@ -59,7 +59,7 @@ class ConvLayer:
 
 
 STACK_NAMES = ("single3x3", "resnet18", "mobilenetv2", "vgg16", "resnet50",
-               "mobilenetv1", "squeezenet", "googlenet", "alexnet", "shufflenet_g3", "efficientnet_b0")
+               "mobilenetv1", "squeezenet", "googlenet", "alexnet", "shufflenet_g3", "efficientnet_b0", "shufflenetv2_x1_5")
 
 
 def _single() -> List[ConvLayer]:
@@ -251,10 +251,36 @@ def _efficientnet_b0() -> List[ConvLayer]:
     return L
 
 
+def _shufflenetv2_x1_5() -> List[ConvLayer]:
+    # Second ShuffleNet at width 1.5x (the width whose size is closest to Table 4's 3.4 M
+    # parameters): 3x3/2 stem to 24, max-pool, stages of 4, 8, 4 units with 176, 352, 704
+    # channels, 1x1 conv to 1024.  A stride-1 unit splits the channels in two and runs
+    # 1x1, 3x3 depthwise, 1x1 on one half; a stride-2 unit runs (3x3/2 depthwise, 1x1) on the
+    # input and (1x1, 3x3/2 depthwise, 1x1) on the input again, each to half the output width.
+    L = [ConvLayer("stem3x3_s2", 3, 224, 224, 24, 3, 3, 2, 1)]
+    cin, hw = 24, 56
+    for stage, (cout, units) in enumerate(((176, 4), (352, 8), (704, 4)), start=2):
+        half = cout // 2
+        L.append(ConvLayer(f"s{stage}u0_left_dw_s2", cin, hw, hw, cin, 3, 3, 2, 1, groups=cin))
+        L.append(ConvLayer(f"s{stage}u0_left_pw", cin, hw // 2, hw // 2, half, 1, 1, 1, 0))
+        L.append(ConvLayer(f"s{stage}u0_right_pw1", cin, hw, hw, half, 1, 1, 1, 0))
+        L.append(ConvLayer(f"s{stage}u0_right_dw_s2", half, hw, hw, half, 3, 3, 2, 1, groups=half))
+        hw //= 2
+        L.append(ConvLayer(f"s{stage}u0_right_pw2", half, hw, hw, half, 1, 1, 1, 0))
+        for u in range(1, units):
+            L.append(ConvLayer(f"s{stage}u{u}_pw1", half, hw, hw, half, 1, 1, 1, 0))
+            L.append(ConvLayer(f"s{stage}u{u}_dw", half, hw, hw, half, 3, 3, 1, 1, groups=half))
+            L.append(ConvLayer(f"s{stage}u{u}_pw2", half, hw, hw, half, 1, 1, 1, 0))
+        cin = cout
+    L.append(ConvLayer("conv5_1x1", cin, hw, hw, 1024, 1, 1, 1, 0))
+    return L
+
+
 _BUILDERS = {"single3x3": _single, "resnet18": _resnet18, "mobilenetv2": _mobilenetv2,
              "vgg16": _vgg16, "resnet50": _resnet50, "mobilenetv1": _mobilenetv1,
              "squeezenet": _squeezenet, "googlenet": _googlenet, "alexnet": _alexnet,
-             "shufflenet_g3": _shufflenet_g3, "efficientnet_b0": _efficientnet_b0}
+             "shufflenet_g3": _shufflenet_g3, "efficientnet_b0": _efficientnet_b0,
+             "shufflenetv2_x1_5": _shufflenetv2_x1_5}
 
 
 def stack(name: str) -> List[ConvLayer]:

@@ -194,7 +194,8 @@ def test_full_resnet50_stack_f32_f16(env):
     _run_stack(env, "resnet50", [False, True])
 
 
-@pytest.mark.parametrize("name", ["mobilenetv1", "squeezenet", "googlenet", "alexnet", "shufflenet_g3", "efficientnet_b0"])
+@pytest.mark.parametrize("name", ["mobilenetv1", "squeezenet", "googlenet", "alexnet", "shufflenet_g3", "efficientnet_b0",
+                                  "shufflenetv2_x1_5"])
 def test_further_table4_shaped_stacks(env, name):
     """More of the paper's Table 4 networks: depthwise-separable blocks, fire modules (7x7/2 stem
     without padding, odd feature-map sizes 109/54/27/13) and inception modules (5x5 branches)."""

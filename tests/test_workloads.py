@@ -55,3 +55,14 @@ def test_shufflenet_units():
     assert len(grouped) == 31 and all(l.r == 1 and l.c % 3 == 0 and l.k % 3 == 0 for l in grouped)
     assert s[1].groups == 1                                   # the first pointwise conv is not grouped
     assert [l.k for l in s if l.name.endswith("u0_pw2_g3")] == [216, 240, 480]
+
+
+def test_shufflenetv2_width():
+    """Width 1.5x is the published width whose size is closest to Table 4's "ShuffleNetV2" row
+    (3.4 M parameters, 0.5 GFLOPs): 2.46 M conv + 1.02 M classifier parameters, 0.295 GMAC (that
+    architecture's own paper: 3.5 M, 299 M multiply-adds)."""
+    s = stack("shufflenetv2_x1_5")
+    params = sum(l.params for l in s) / 1e6
+    assert abs(params - 2.455) < 0.01 and abs(params + 1.025 - 3.4) / 3.4 < 0.05
+    assert abs(sum(l.macs for l in s) / 1e6 + 1.0 - 299) < 6
+    assert sum(l.is_depthwise for l in s) == 3 + 16 and all(l.groups in (1, l.c) for l in s)
