@@ -73,11 +73,34 @@ def rows(stack_name: str, half: bool):
                    "transform_GBps": (t.transform_bytes / (t.transform_ms * 1e-3) / 1e9) if t.transform_ms > 0 else 0.0}
 
 
+def summary(half: bool):
+    """One line per workload: layers, GMAC, and per kind the summed forward time of the layers it
+    can run (and how many), then the sum over layers of the fastest kind of each."""
+    from nnv_workloads import STACK_NAMES, stack
+    kinds = [KIND_NAMES[k] for k in sorted(KIND_NAMES)]
+    print("| stack | layers | GMAC | " + " | ".join(f"{k} us (layers)" for k in kinds) + " | best kind per layer, us |")
+    print("|---|---:|---:|" + "---:|" * (len(kinds) + 1))
+    for name in STACK_NAMES:
+        per_kind, best = {}, {}
+        for r in rows(name, half):
+            a = per_kind.setdefault(r["kind"], [0.0, 0])
+            a[0] += r["us"]; a[1] += 1
+            best[r["layer"]] = min(best.get(r["layer"], float("inf")), r["us"])
+        layers = stack(name)
+        cells = [f"{per_kind[k][0]:.1f} ({per_kind[k][1]})" if k in per_kind else "-" for k in kinds]
+        print(f"| {name} | {len(layers)} | {sum(l.macs for l in layers) / 1e9:.3f} | " + " | ".join(cells) +
+              f" | {sum(best.values()):.1f} |", flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__.split("\n")[0])
     ap.add_argument("--stack", default="resnet18")
     ap.add_argument("--half", action="store_true")
+    ap.add_argument("--summary", action="store_true", help="totals of every workload instead of one per-layer table")
     args = ap.parse_args()
+    if args.summary:
+        summary(args.half)
+        return
     print(f"| layer | kind | forward us | GB/s | TFLOP/s executed | TFLOP/s direct-equivalent | bound us | bound by | "
           f"bound/time | transform us | transform GB/s |")
     print("|---|---|---:|---:|---:|---:|---:|---|---:|---:|---:|")
