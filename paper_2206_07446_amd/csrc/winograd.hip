@@ -247,26 +247,9 @@ __global__ __launch_bounds__(1024) void wino_gemm_kernel(const WinoParams w) {
     }
 }
 
-// ---- 3. output transform.  Block = 16 tiles x blockDim/16 output channels.
-template <int SET, bool HALF>
-__global__ __launch_bounds__(256) void wino_output_kernel(const WinoParams w) {
-    using Wm = WinoMat<SET>;
-    constexpr int A = Wm::A, M = Wm::M;
-    const int t_in = threadIdx.x & 15;
-    const int tb = blockIdx.x;
-    const int k = (blockIdx.y * blockDim.x + threadIdx.x) >> 4, kb = k >> 4, k_in = k & 15;
-    const int t = tb * 16 + t_in;
-    if (t >= w.T || k >= w.K) return;
-    const float *mp = w.M + ((size_t)kb * w.T16 + tb) * 256 + k_in * 16 + t_in;
-    const size_t xs = (size_t)w.K16 * w.T16 * 256;
-    float m[A][A];
-#pragma unroll
-    for (int u = 0; u < A; ++u)
-#pragma unroll
-        for (int v = 0; v < A; ++v) m[u][v] = mp[(u * A + v) * xs];
-    float tmp[M][A], Y[M][M];
-    NNV_MATMUL_LEFT(Wm::AT, M, A, A, m, tmp)
-    NNV_MATMUL_RIGHT_T(Wm::AT, M, A, M, tmp, Y)
+// Bias, optional clamp at zero and store of the M x M outputs of tile t, channel k, clipped to P x Q.
+template <int M, bool HALF>
+__device__ __forceinline__ void wino_store_tile(const WinoParams &w, float (&Y)[M][M], int t, int k) {
     const float bv = w.bias ? w.bias[k] : 0.f;
 #pragma unroll
     for (int a = 0; a < M; ++a)
@@ -324,6 +307,158 @@ __global__ __launch_bounds__(256) void wino_output_kernel(const WinoParams w) {
     }
 }
 
+// ---- 3. output transform.  Block = 16 tiles x blockDim/16 output channels.
+template <int SET, bool HALF>
+__global__ __launch_bounds__(256) void wino_output_kernel(const WinoParams w) {
+    using Wm = WinoMat<SET>;
+    constexpr int A = Wm::A, M = Wm::M;
+    const int t_in = threadIdx.x & 15;
+    const int tb = blockIdx.x;
+    const int k = (blockIdx.y * blockDim.x + threadIdx.x) >> 4, kb = k >> 4, k_in = k & 15;
+    const int t = tb * 16 + t_in;
+    if (t >= w.T || k >= w.K) return;
+    const float *mp = w.M + ((size_t)kb * w.T16 + tb) * 256 + k_in * 16 + t_in;
+    const size_t xs = (size_t)w.K16 * w.T16 * 256;
+    float m[A][A];
+#pragma unroll
+    for (int u = 0; u < A; ++u)
+#pragma unroll
+        for (int v = 0; v < A; ++v) m[u][v] = mp[(u * A + v) * xs];
+    float tmp[M][A], Y[M][M];
+    NNV_MATMUL_LEFT(Wm::AT, M, A, A, m, tmp)
+    NNV_MATMUL_RIGHT_T(Wm::AT, M, A, M, tmp, Y)
+    wino_store_tile<M, HALF>(w, Y, t, k);
+}
+
+// ---- fused variant (float32, F(2x2) and F(4x4)): all three steps in one kernel, no workspace.
+// On layers with many tiles and few output channels the three-kernel route spends most of its
+// time writing and re-reading V and M.  Here a wavefront owns 16 tiles x 16 output channels.
+// Per step of 4 input channels every lane transforms the patch of one (tile, channel) pair in
+// registers: lane (tile l%16, channel l/16) then holds, for every frequency, exactly its element
+// of the B operand of the 16x16x4 MFMA.  The alpha^2 accumulators stay in registers and the
+// output transform is applied to them in place (accumulator register j of lane l is output
+// channel 4*(l/16)+j of tile l%16).  The input transform is repeated by every 16-channel block
+// of K, which is what restricts this route to layers with few output channels.
+template <int SET>
+__global__ __launch_bounds__(256) void wino_fused_kernel(const WinoParams w) {
+    using Wm = WinoMat<SET>;
+    constexpr int A = Wm::A, M = Wm::M, AA = A * A;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // logical order: tile blocks fastest, so neighbouring workgroups share U; the four
+    // wavefronts of a workgroup share the patches (same tiles, four blocks of output channels)
+    const int lwg = xcd_logical_tile(w.gemm_wgs_per_xi);
+    if (lwg < 0) return;
+    const int kbg = lwg / w.T16, tb = lwg - kbg * w.T16;
+    const int kb = kbg * 4 + wave;
+    if (kb >= w.K16) return;
+    const int col = lane & 15, slot = lane >> 4;
+    const int t = tb * 16 + col;
+    const bool live = t < w.T;
+    const __amdgpu_buffer_rsrc_t xres = make_rsrc(w.x, w.x_bytes);
+    const __amdgpu_buffer_rsrc_t ures = make_rsrc(w.U, w.u_bytes);
+    const uint32_t plane4 = (uint32_t)(w.H * w.W) * 16u;     // bytes of 4 channel planes
+    // per-lane byte offsets of the patch rows and columns in channel `slot`; a step adds its
+    // channel base as the scalar offset.  Rows and columns in the zero padding (and every row of
+    // a surplus tile) carry 2^30 instead, which puts the sum beyond the end of x (x is smaller
+    // than 2^30 bytes on this route), so those elements read as zero.
+    constexpr uint32_t kOut = 0x40000000u;
+    uint32_t rowoff[A], coloff[A];
+    {
+        const int tt = live ? t : 0;
+        const int per = w.th * w.tw;
+        const int img = tt / per, rem = tt - img * per;
+        const int ti = rem / w.tw, tj = rem - ti * w.tw;
+        const int ih0 = ti * M - w.ph, iw0 = tj * M - w.pw;
+        const int base = (img * w.C + slot) * w.H * w.W;
+#pragma unroll
+        for (int u = 0; u < A; ++u) {
+            const int ih = ih0 + u;
+            rowoff[u] = (live && (unsigned)ih < (unsigned)w.H) ? (uint32_t)(base + ih * w.W) * 4u : kOut;
+        }
+#pragma unroll
+        for (int v = 0; v < A; ++v) {
+            const int iw = iw0 + v;
+            coloff[v] = (unsigned)iw < (unsigned)w.W ? (uint32_t)iw * 4u : kOut;
+        }
+    }
+    const uint32_t a_voff = lane * 4u;
+    const uint32_t a_base = (uint32_t)kb * w.csteps;          // fragment index at frequency 0, step 0
+    const uint32_t a_xi = (uint32_t)w.K16 * w.csteps;         // fragments per frequency
+    floatx4 acc[AA];
+#pragma unroll
+    for (int i = 0; i < AA; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+    // Everything a step needs is requested one step earlier.  Patches alternate between two
+    // register sets; the U fragment of frequency i is re-requested for the next step right
+    // after the MFMA that consumed it, into the same register.  Loads complete in order, and
+    // the order of issue is patch(s), U(s), patch(s+1), U(s+1), ..., so waiting for one of
+    // them never waits for anything requested later.  The scheduling barriers keep that order.
+    float d[2][A][A], a[AA];
+    const int full = w.C >> 2;                                // steps whose 4 channels all exist
+    const int last = w.csteps - 1;
+    auto load_patch = [&](int buf, int s) __attribute__((always_inline)) {
+        const uint32_t soff = (uint32_t)s * plane4;
+#pragma unroll
+        for (int u = 0; u < A; ++u)
+#pragma unroll
+            for (int v = 0; v < A; ++v) d[buf][u][v] = buf_load<float>(xres, rowoff[u] + coloff[v], soff);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto load_a = [&](int i, int s) __attribute__((always_inline)) {
+        a[i] = buf_load<float>(ures, a_voff, (a_base + (uint32_t)i * a_xi + s) * 256u);
+    };
+    auto step = [&](int buf, int s) __attribute__((always_inline)) {
+        float tmp[A][A], V[A][A];
+        NNV_MATMUL_LEFT(Wm::BT, A, A, A, d[buf], tmp)
+        NNV_MATMUL_RIGHT_T(Wm::BT, A, A, A, tmp, V)
+        const int sn = min(s + 1, last);
+#pragma unroll
+        for (int i = 0; i < AA; ++i) {
+            acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[i], V[i / A][i % A], acc[i], 0, 0, 0);
+            load_a(i, sn);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    if (full > 0) load_patch(0, 0);
+#pragma unroll
+    for (int i = 0; i < AA; ++i) load_a(i, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (full > 0) {
+        int s = 0;
+        for (; s + 2 <= full; s += 2) {
+            load_patch(1, s + 1);
+            step(0, s);
+            load_patch(0, min(s + 2, full - 1));
+            step(1, s + 1);
+        }
+        if (s < full) step(0, s);
+    }
+    if (w.C & 3) {
+        // last step of a channel count that is not a multiple of 4: lanes of missing channels read zero
+        const bool cok = full * 4 + slot < w.C;
+        const uint32_t soff = (uint32_t)full * plane4;
+#pragma unroll
+        for (int u = 0; u < A; ++u)
+#pragma unroll
+            for (int v = 0; v < A; ++v) d[0][u][v] = buf_load<float>(xres, cok ? rowoff[u] + coloff[v] : kOobOffset, soff);
+        __builtin_amdgcn_sched_barrier(0);
+        step(0, full);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int k = kb * 16 + slot * 4 + j;
+        if (!live || k >= w.K) continue;
+        float m[A][A], tmp[M][A], Y[M][M];
+#pragma unroll
+        for (int u = 0; u < A; ++u)
+#pragma unroll
+            for (int v = 0; v < A; ++v) m[u][v] = acc[u * A + v][j];
+        NNV_MATMUL_LEFT(Wm::AT, M, A, A, m, tmp)
+        NNV_MATMUL_RIGHT_T(Wm::AT, M, A, M, tmp, Y)
+        wino_store_tile<M, false>(w, Y, t, k);
+    }
+}
+
 // ---------------------------------------------------------------- host side
 
 struct WinoPlan {
@@ -350,9 +485,31 @@ static WinoPlan plan_wino(const Geo &g, int kind) {
     return p;
 }
 
+// The fused kernel repeats the input transform (and the strided patch loads, which dominate its
+// time) once per 16 output channels and runs one wavefront per SIMD, so it only pays where the
+// three-kernel route is dominated by its V and M traffic: many tiles, few output channels and
+// few input channels.  Measured on 224x224 and 112x112 planes: it is ahead up to about 32 input
+// channels for F(4x4) (3 channels: 11 us against 32 us) and up to 64 for F(2x2) with 64 output
+// channels; beyond that the three kernels win (128 -> 128 channels at 112x112: 117 us against 37 us).
+static bool wino_fused(const Geo &g, int kind, const WinoPlan &p) {
+    if (g.dtype != NNV_F32 || (kind != NNV_WINO_F2 && kind != NNV_WINO_F4)) return false;
+    const size_t x_bytes = (size_t)g.n * g.c * g.h * g.w * 4;
+    if (p.T16 < 32 || p.K16 > 8 || x_bytes >= ((size_t)1 << 30)) return false;
+    return kind == NNV_WINO_F2 ? p.csteps * p.K16 <= 64 : p.csteps <= 8;
+}
+
 size_t wino_workspace_bytes(const Geo &g, int kind) {
     const WinoPlan p = plan_wino(g, kind);
+    if (wino_fused(g, kind, p)) return 0;
     return p.v_bytes + p.m_bytes;
+}
+
+template <int SET>
+static hipError_t launch_wino_fused(const WinoPlan &p, WinoParams &w, hipStream_t st) {
+    w.u_bytes = (uint32_t)((size_t)p.alpha * p.alpha * p.K16 * p.csteps * 256);
+    w.gemm_wgs_per_xi = p.T16 * ceil_div(p.K16, 4);
+    hipLaunchKernelGGL((wino_fused_kernel<SET>), dim3(xcd_grid(w.gemm_wgs_per_xi)), dim3(256), 0, st, w);
+    return hipGetLastError();
 }
 
 template <int SET, bool HALF>
@@ -425,6 +582,10 @@ hipError_t launch_wino(const Geo &g, int kind, const void *x, const void *U, con
     w.relu = g.relu;
     w.th = p.th; w.tw = p.tw; w.T = p.T; w.T16 = p.T16; w.K16 = p.K16; w.cpad = p.cpad; w.csteps = p.csteps;
     const int set = wino_set(kind, g.dtype);
+    if (wino_fused(g, kind, p)) {
+        if (set == WS_F2) return launch_wino_fused<0>(p, w, st);
+        return launch_wino_fused<1>(p, w, st);
+    }
     if (set == WS_F2) {
         if (g.dtype == NNV_F16) return launch_wino_t<0, true>(g, p, w, st);
         return launch_wino_t<0, false>(g, p, w, st);

@@ -128,6 +128,33 @@ def test_fused_bias_relu(env, layer, kind):
         assert np.abs(got - ref).max() <= tol * np.abs(plain).max()
 
 
+# Many tiles, few output channels: float32 F(2x2) / F(4x4) take the single-kernel route (no workspace).
+FUSED = [
+    Ly("fz_ragged", 6, 90, 90, 24, 3, 1, 1),                 # C % 4 = 2, K % 16 = 8
+    Ly("fz_two_groups", 8, 92, 92, 72, 3, 1, 1),             # K/16 = 5: second workgroup row partly empty
+    Ly("fz_rgb", 3, 96, 96, 16, 3, 1, 1),                    # only the masked last channel step
+    Ly("fz_one", 1, 91, 93, 3, 3, 1, 1),                     # odd Q: scalar stores
+    Ly("fz_batch2", 12, 64, 64, 32, 3, 1, 1, n=2),           # tiles of two images in one block of 16
+    Ly("fz_pad0", 5, 94, 94, 128, 3, 1, 0),                  # K/16 = 8, no padding
+    ConvLayer("fz_wide", 16, 40, 230, 20, 3, 3, 1, 1),       # not square; an even number of full channel steps
+    Ly("fz_odd_steps", 22, 90, 90, 16, 3, 1, 1),             # five full channel steps and a masked one
+]
+FUSED_CASES = [(l, k) for l in FUSED for k in (2, 3)]
+
+
+@pytest.mark.parametrize("layer,kind", FUSED_CASES, ids=[f"{l.name}-{KIND_NAMES[k]}" for l, k in FUSED_CASES])
+def test_fused_winograd(env, layer, kind):
+    nnv, torch = env
+    assert nnv.nnv_workspace_bytes(nnv.make_desc(layer, nnv.F32), kind) == 0       # the fused route
+    assert nnv.nnv_workspace_bytes(nnv.make_desc(layer, nnv.F16), kind) > 0        # float16: three kernels
+    check(env, layer, kind, False, seed=500 + len(layer.name))
+    w, x = layer_tensors(layer, 41)
+    b = np.random.default_rng(42).standard_normal(layer.k)
+    got = gpu_forward(nnv, torch, layer, kind, False, w, x, b, relu=True)
+    plain = oracle_forward(layer, False, w, x, b)
+    assert np.abs(got - np.maximum(plain, 0.0)).max() <= conv_tolerance(kind, False) * np.abs(plain).max()
+
+
 def test_bias_depthwise(env):
     check(env, SMALL[13], 4, False, seed=79, bias=True)
 
