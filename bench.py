@@ -328,7 +328,9 @@ def main():
                                   MFMA_F32_PEAK_TFLOPS, "TFLOP/s", ms, len(sel)))
         else:
             roof_all.append(entry(f"{kname}: wino_input + wino_gemm (float32 MFMA) + wino_output", "mfma", fl, 1e12,
-                                  MFMA_F32_PEAK_TFLOPS, "TFLOP/s", ms, 3 * len(sel)))
+                                  MFMA_F32_PEAK_TFLOPS, "TFLOP/s", ms,
+                                  # three launches per layer; one where the fused kernel is chosen (no workspace)
+                                  sum(3 if p.ws_bytes else 1 for p in sel)))
     # the dominant kernel of the step = the class with the largest share of the step time
     roofline = max(roof_all, key=lambda r: r["phase_ms"])
 

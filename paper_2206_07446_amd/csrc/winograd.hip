@@ -486,16 +486,28 @@ static WinoPlan plan_wino(const Geo &g, int kind) {
 }
 
 // The fused kernel repeats the input transform (and the strided patch loads, which dominate its
-// time) once per 16 output channels and runs one wavefront per SIMD, so it only pays where the
-// three-kernel route is dominated by its V and M traffic: many tiles, few output channels and
-// few input channels.  Measured on 224x224 and 112x112 planes: it is ahead up to about 32 input
-// channels for F(4x4) (3 channels: 11 us against 32 us) and up to 64 for F(2x2) with 64 output
-// channels; beyond that the three kernels win (128 -> 128 channels at 112x112: 117 us against 37 us).
+// time) once per 16 output channels and runs one or two wavefronts per SIMD, so it pays only
+// where the three-kernel route is dominated by launch floors and by its V and M round trips.
+// The choice compares two estimates fitted to a sweep over 48..224-pixel planes, 4..64 input
+// and 16..128 output channels (they pick the faster route, or one within 5 %, at every point):
+//   fused = 4 us + y / 2.3 TB/s + channel steps x time per step x max(1, workgroups / 256);
+//           a step takes 0.47 us (F(2x2)) or 1.9 us (F(4x4)) for a lone wavefront on a CU and
+//           0.16 / 0.5 us more for each further wavefront of the workgroup
+//   three = 8 us + 2 (V + M) / 3 TB/s
+// e.g. 3 -> 64 channels at 224x224, F(4x4): 11 us fused against 32 us; 64 -> 64 at 56x56,
+// F(2x2): 21 us fused against 13 us.  Outside the swept range the three kernels are kept.
 static bool wino_fused(const Geo &g, int kind, const WinoPlan &p) {
     if (g.dtype != NNV_F32 || (kind != NNV_WINO_F2 && kind != NNV_WINO_F4)) return false;
     const size_t x_bytes = (size_t)g.n * g.c * g.h * g.w * 4;
-    if (p.T16 < 32 || p.K16 > 8 || x_bytes >= ((size_t)1 << 30)) return false;
-    return kind == NNV_WINO_F2 ? p.csteps * p.K16 <= 64 : p.csteps <= 8;
+    if (p.T16 < 32 || p.K16 > 8 || p.csteps > 16 || x_bytes >= ((size_t)1 << 30)) return false;
+    const double wgs = (double)p.T16 * ceil_div(p.K16, 4);
+    const double rounds = wgs > 256.0 ? wgs / 256.0 : 1.0;
+    const int waves = p.K16 < 4 ? p.K16 : 4;
+    const double step_us = kind == NNV_WINO_F2 ? 0.47 + 0.16 * (waves - 1) : 1.9 + 0.5 * (waves - 1);
+    const double y_mb = (double)g.n * g.k * g.p * g.q * 4e-6;
+    const double fused_us = 4.0 + y_mb / 2.3 + p.csteps * step_us * rounds;
+    const double three_us = 8.0 + 2.0 * (double)(p.v_bytes + p.m_bytes) * 1e-6 / 3.0;
+    return fused_us < three_us;
 }
 
 size_t wino_workspace_bytes(const Geo &g, int kind) {

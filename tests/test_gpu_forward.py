@@ -128,18 +128,20 @@ def test_fused_bias_relu(env, layer, kind):
         assert np.abs(got - ref).max() <= tol * np.abs(plain).max()
 
 
-# Many tiles, few output channels: float32 F(2x2) / F(4x4) take the single-kernel route (no workspace).
+# Layers on which float32 F(2x2) / F(4x4) take the single-kernel route (no workspace): many tiles,
+# few channels.  The host chooses by a cost estimate; each entry lists the kinds that take it.
 FUSED = [
-    Ly("fz_ragged", 6, 90, 90, 24, 3, 1, 1),                 # C % 4 = 2, K % 16 = 8
-    Ly("fz_two_groups", 8, 92, 92, 72, 3, 1, 1),             # K/16 = 5: second workgroup row partly empty
-    Ly("fz_rgb", 3, 96, 96, 16, 3, 1, 1),                    # only the masked last channel step
-    Ly("fz_one", 1, 91, 93, 3, 3, 1, 1),                     # odd Q: scalar stores
-    Ly("fz_batch2", 12, 64, 64, 32, 3, 1, 1, n=2),           # tiles of two images in one block of 16
-    Ly("fz_pad0", 5, 94, 94, 128, 3, 1, 0),                  # K/16 = 8, no padding
-    ConvLayer("fz_wide", 16, 40, 230, 20, 3, 3, 1, 1),       # not square; an even number of full channel steps
-    Ly("fz_odd_steps", 22, 90, 90, 16, 3, 1, 1),             # five full channel steps and a masked one
+    (Ly("fz_ragged", 6, 90, 90, 24, 3, 1, 1), (2, 3)),             # C % 4 = 2, K % 16 = 8
+    (Ly("fz_two_groups", 8, 92, 92, 72, 3, 1, 1), (2, 3)),         # K/16 = 5: second workgroup row partly empty
+    (Ly("fz_rgb", 3, 96, 96, 16, 3, 1, 1), (2, 3)),                # only the masked last channel step
+    (Ly("fz_one", 1, 91, 93, 3, 3, 1, 1), (2, 3)),                 # odd Q: scalar stores
+    (Ly("fz_batch2", 12, 64, 64, 32, 3, 1, 1, n=2), (2,)),         # tiles of two images in one block of 16
+    (Ly("fz_pad0", 5, 94, 94, 128, 3, 1, 0), (2, 3)),              # K/16 = 8, no padding
+    (ConvLayer("fz_wide", 16, 40, 230, 20, 3, 3, 1, 1), (2,)),     # not square; an even number of full channel steps
+    (Ly("fz_odd_steps", 22, 90, 90, 16, 3, 1, 1), (2,)),           # five full channel steps and a masked one
+    (Ly("fz_large", 22, 224, 224, 64, 3, 1, 1), (2, 3)),           # the same through F(4x4): a large plane
 ]
-FUSED_CASES = [(l, k) for l in FUSED for k in (2, 3)]
+FUSED_CASES = [(l, k) for l, ks in FUSED for k in ks]
 
 
 @pytest.mark.parametrize("layer,kind", FUSED_CASES, ids=[f"{l.name}-{KIND_NAMES[k]}" for l, k in FUSED_CASES])
