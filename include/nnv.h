@@ -113,7 +113,9 @@ int nnv_kind_supported(const nnv_conv_desc *desc, nnv_kind kind);
  * (Section 3.1.2): alpha^2/9 of the raw size for Winograd up to padding. */
 size_t nnv_transformed_bytes(const nnv_conv_desc *desc, nnv_kind kind);
 
-/* Bytes of scratch nnv_conv_forward needs for `kind` (may be 0). */
+/* Bytes of scratch nnv_conv_forward needs for `kind` (may be 0: DIRECT, DEPTHWISE, float32
+ * IM2COL_GEMM, and float32 WINO_F2/F4 on layers that run as one fused kernel; the other
+ * Winograd layers keep their transformed input V and the tile products M there). */
 size_t nnv_workspace_bytes(const nnv_conv_desc *desc, nnv_kind kind);
 
 /* Weight transformation w_i (Section 2 "weights transformation", Fig. 3, Table 2

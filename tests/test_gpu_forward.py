@@ -151,6 +151,17 @@ def test_fused_winograd(env, layer, kind):
     assert nnv.nnv_workspace_bytes(nnv.make_desc(layer, nnv.F16), kind) > 0        # float16: three kernels
     check(env, layer, kind, False, seed=500 + len(layer.name))
     w, x = layer_tensors(layer, 41)
+    if layer.name == "fz_ragged":       # no workspace needed, so none has to be passed
+        dev = torch.device("cuda:0")
+        desc = nnv.make_desc(layer, nnv.F32)
+        wd, xd = torch.from_numpy(w).to(dev), torch.from_numpy(x).to(dev)
+        wt = torch.empty(nnv.nnv_transformed_bytes(desc, kind), dtype=torch.uint8, device=dev)
+        y = torch.empty(layer.n * layer.k * layer.p * layer.q, dtype=torch.float32, device=dev)
+        nnv.nnv_transform_weights(desc, kind, wd, wt)
+        nnv.nnv_conv_forward(desc, kind, xd, wt, None, y, None)
+        torch.cuda.synchronize()
+        ref = oracle_forward(layer, False, w, x)
+        assert np.abs(y.cpu().numpy().reshape(ref.shape) - ref).max() <= conv_tolerance(kind, False) * np.abs(ref).max()
     b = np.random.default_rng(42).standard_normal(layer.k)
     got = gpu_forward(nnv, torch, layer, kind, False, w, x, b, relu=True)
     plain = oracle_forward(layer, False, w, x, b)
