@@ -73,6 +73,34 @@ def rows(stack_name: str, half: bool):
                    "transform_GBps": (t.transform_bytes / (t.transform_ms * 1e-3) / 1e9) if t.transform_ms > 0 else 0.0}
 
 
+def counter_pass(stack_name: str, half: bool):
+    """Every (layer, kind) of the stack, transformed once and run three times eagerly, nothing
+    timed: the program to put under `rocprofv3 --pmc <counter> --kernel-trace`.  Dispatches
+    appear in the order of the printed lines, three forward passes per line."""
+    import torch
+    from nnv_workloads import stack, layer_tensors
+    from . import binding as nnv
+    dev = torch.device("cuda:0")
+    dtype = nnv.F16 if half else nnv.F32
+    for i, layer in enumerate(stack(stack_name)):
+        desc = nnv.make_desc(layer, dtype)
+        w, x = layer_tensors(layer, 220607446 + i)
+        wd, xd = torch.from_numpy(w).to(dev), torch.from_numpy(x).to(dev)
+        if half:
+            xd = xd.half()
+        y = torch.empty(layer.n * layer.k * layer.p * layer.q, dtype=xd.dtype, device=dev)
+        for kind in range(6):
+            if not nnv.nnv_kind_supported(desc, kind):
+                continue
+            wt = wd if kind == nnv.DIRECT else torch.empty(nnv.nnv_transformed_bytes(desc, kind), dtype=torch.uint8, device=dev)
+            ws = torch.empty(max(16, nnv.nnv_workspace_bytes(desc, kind)), dtype=torch.uint8, device=dev)
+            nnv.nnv_transform_weights(desc, kind, wd, wt)
+            for _ in range(3):
+                nnv.nnv_conv_forward(desc, kind, xd, wt, None, y, ws)
+            torch.cuda.synchronize()
+            print(f"{i:02d} {layer.name} {KIND_NAMES[kind]}", flush=True)
+
+
 def summary(half: bool):
     """One line per workload: layers, GMAC, and per kind the summed forward time of the layers it
     can run (and how many), then the sum over layers of the fastest kind of each."""
@@ -97,7 +125,12 @@ def main():
     ap.add_argument("--stack", default="resnet18")
     ap.add_argument("--half", action="store_true")
     ap.add_argument("--summary", action="store_true", help="totals of every workload instead of one per-layer table")
+    ap.add_argument("--counter-pass", action="store_true",
+                    help="run every (layer, kind) three times eagerly, nothing timed (for rocprofv3 --pmc)")
     args = ap.parse_args()
+    if args.counter_pass:
+        counter_pass(args.stack, args.half)
+        return
     if args.summary:
         summary(args.half)
         return
