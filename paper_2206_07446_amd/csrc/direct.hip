@@ -5,9 +5,8 @@
 // Both are plain vector-ALU kernels.  direct: one thread owns one output pixel and KB
 // output channels; the filter taps it needs are wave-uniform, so they come through
 // scalar loads, and x is read along W (coalesced).  depthwise: HBM-bound, one thread per
-// output pixel of one channel plane, taps of the channel from the packed
-// [C/32][9][32] layout.
-#include <cstdlib>
+// output pixel of one channel plane, taps of the channel (3x3 or 5x5) from the packed
+// [C/32][taps][32] layout.
 #include "nnv_internal.h"
 #include "buf.h"
 

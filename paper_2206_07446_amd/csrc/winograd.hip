@@ -9,6 +9,8 @@
 //   3. output transform  Y = A^T M A, clipped to P x Q, plus bias        (vector ALU)
 // V and M live in the caller's workspace.  float16 storage keeps U, V and y in half
 // precision; the transforms and the accumulation are float32.
+// float32 F(2x2) / F(4x4) layers with many tiles and few channels run instead as ONE kernel
+// (wino_fused_kernel below) that keeps V and M in registers and needs no workspace.
 #include <type_traits>
 #include "nnv_internal.h"
 #include "buf.h"
