@@ -97,7 +97,9 @@ const char *nnv_status_string(int status);
 const char *nnv_last_hip_error(void);
 
 /* 1 if `kind` can run the layer, 0 if not, NNV_E_* if the descriptor is invalid.
- *   WINO_F2/F4   : R = S = 3, stride 1, groups 1
+ *   WINO_F2/F4   : R = S = 3, stride 1, groups 1; with dtype float16 also C >= 16 (with a
+ *                  handful of channels the roundings of U and V to float16 put the error
+ *                  above the float16 bound of this library, 5e-3 * max|y|: refused)
  *   WINO_F6      : the same, and dtype float32 (with U and V rounded to float16 its error
  *                  exceeds the float16 bound of this library, so that pairing is refused)
  *   DEPTHWISE    : groups = C = K, R = S in {3,5}, stride_h = stride_w in {1,2}

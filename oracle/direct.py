@@ -15,7 +15,10 @@ Pins (tests/test_oracle_direct.py): conv2d_direct against the 7-loop
 conv2d_bruteforce on tiny layers; both against closed forms (centre-delta
 filter gives y = x; all-ones tensors count the valid taps), against a plain
 matrix product for 1x1 filters, against scipy.signal.correlate2d per channel,
-and against brute-force values worked by hand in tests/golden/.
+and against brute-force values worked by hand in tests/golden/.  conv2d_at
+(single output positions of layers too large to evaluate whole) against
+conv2d_bruteforce at every position of tiny layers, and against a hand-worked
+golden value.
 """
 from __future__ import annotations
 
@@ -81,3 +84,29 @@ def conv2d_direct(x, w, stride=1, pad=0, groups=1, bias=None):
     if bias is not None:
         y = y + np.asarray(bias, dtype=np.float64).reshape(1, K, 1, 1)
     return y
+
+
+def conv2d_at(x, w, positions, stride=1, pad=0, groups=1, bias=None):
+    """The same definition evaluated at single output positions (n, k, p, q) only, for
+    layers whose whole output the CPU cannot afford: per position, the sum over the filter
+    taps that fall inside the image of the dot product over the group's channels."""
+    N, C, H, W = x.shape
+    K, Cg, R, S = w.shape
+    assert C == Cg * groups and K % groups == 0
+    kg = K // groups
+    out = np.empty(len(positions), dtype=np.float64)
+    for i, (n, k, p, q) in enumerate(positions):
+        c0 = (k // kg) * Cg
+        acc = 0.0 if bias is None else float(bias[k])
+        for r in range(R):
+            ih = p * stride - pad + r
+            if ih < 0 or ih >= H:
+                continue
+            for s in range(S):
+                iw = q * stride - pad + s
+                if iw < 0 or iw >= W:
+                    continue
+                acc += float(np.dot(np.asarray(x[n, c0:c0 + Cg, ih, iw], dtype=np.float64),
+                                    np.asarray(w[k, :, r, s], dtype=np.float64)))
+        out[i] = acc
+    return out

@@ -339,6 +339,9 @@ static DirectPlan plan_direct(const Geo &g) {
     const size_t wbytes = (size_t)cc * RS * pl.tk * sizeof(float);
     const size_t rbytes = pl.cs > 1 ? (size_t)pl.cs * pl.tp * pl.tk * 64 * sizeof(float) : 0;
     pl.lds = wbytes > rbytes ? wbytes : rbytes;
+    // a large filter (e.g. 15x15) does not fit its staged taps into the 64 KiB a workgroup gets
+    // without opting in to more: such layers take the plain kernel
+    if (pl.lds > 64 * 1024) pl = DirectPlan{0, 1, 1, 0, 0};
     return pl;
 }
 

@@ -21,6 +21,9 @@ static inline bool is_wino(int kind) { return kind == NNV_WINO_F2 || kind == NNV
 static inline int wino_m(int kind) { return kind == NNV_WINO_F2 ? 2 : kind == NNV_WINO_F4 ? 4 : 6; }
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// Fewest input channels for which Winograd runs with float16 storage (see nnv_kind_supported).
+constexpr int kWinoHalfMinChannels = 16;
+
 // Winograd matrix sets (see wino_consts.h)
 enum WinoSet { WS_F2 = 0, WS_F4 = 1, WS_F4H = 2, WS_F6 = 3 };
 static inline int wino_set(int kind, int dtype) {

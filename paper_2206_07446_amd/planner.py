@@ -90,10 +90,17 @@ def _median_read_ms(nnv, path, desc, kind, dst, reps=3):
     return times[len(times) // 2]
 
 
-def profile_stack(stack_name: str, dtype: int = 0, reps: int = 10, flush_mb: int = 0,
+COLD_FLUSH_MB = 512      # twice the 256 MB last-level cache: nothing of a layer survives the overwrite
+
+
+def profile_stack(stack_name: str, dtype: int = 0, reps: int = 10, flush_mb: int = COLD_FLUSH_MB,
                   cache_dir: Optional[str] = None) -> Dict[str, List[Candidate]]:
     """Time every applicable kind of every layer of a workload on the GPU; with cache_dir also
-    write each candidate's weights there and time reading them back."""
+    write each candidate's weights there and time reading them back.  The kernel selection
+    prices the operations of a cold inference (Section 3.1.1, Table 2), so by default a flush
+    buffer larger than the last-level cache is overwritten before every timed repetition and a
+    repetition is one launch; flush_mb=0 gives warm timings (cache-resident operands, queued
+    launches) instead."""
     import os
     import torch
     from nnv_workloads import stack, layer_tensors
@@ -137,8 +144,8 @@ def profile_stack(stack_name: str, dtype: int = 0, reps: int = 10, flush_mb: int
     return table
 
 
-def report(table: Dict[str, List[Candidate]], read_gbps: float) -> dict:
-    out = {"read_GBps": read_gbps, "layers": {}, "plans": {}}
+def report(table: Dict[str, List[Candidate]], read_gbps: float, timing: str = "cold") -> dict:
+    out = {"read_GBps": read_gbps, "timing": timing, "layers": {}, "plans": {}}
     for name, cands in table.items():
         kept = {c.kind for c in pareto_filter(cands)}
         out["layers"][name] = [dict(asdict(c), kept=c.kind in kept) for c in cands]
@@ -155,7 +162,8 @@ def report(table: Dict[str, List[Candidate]], read_gbps: float) -> dict:
 
 def markdown(rep: dict) -> str:
     """The report as two tables: candidates per layer (Table 2's columns) and the plans."""
-    out = ["| layer | kind | kept | read raw ms | transform ms | read cache ms | execute ms | raw+transform+execute | cache+execute |",
+    out = [f"Operation timings: {rep.get('timing', 'cold')}.", "",
+           "| layer | kind | kept | read raw ms | transform ms | read cache ms | execute ms | raw+transform+execute | cache+execute |",
            "|---|---|---|---:|---:|---:|---:|---:|---:|"]
     gbps = rep["read_GBps"]
     for name, cands in rep["layers"].items():
@@ -181,12 +189,13 @@ def main():
     ap.add_argument("--read-gbps", type=float, default=2.0, help="weight read bandwidth (storage), GB/s")
     ap.add_argument("--half", action="store_true")
     ap.add_argument("--reps", type=int, default=10)
-    ap.add_argument("--flush-mb", type=int, default=0)
+    ap.add_argument("--flush-mb", type=int, default=COLD_FLUSH_MB,
+                    help="flush buffer overwritten before each timed repetition (cold timing); 0 = warm timing")
     ap.add_argument("--cache-dir", default=None, help="measure weight reads through cache files written here")
     ap.add_argument("--markdown", action="store_true", help="print tables instead of JSON")
     args = ap.parse_args()
     table = profile_stack(args.stack, 1 if args.half else 0, args.reps, args.flush_mb, args.cache_dir)
-    rep = report(table, args.read_gbps)
+    rep = report(table, args.read_gbps, "cold" if args.flush_mb else "warm (operands cache-resident)")
     print(markdown(rep) if args.markdown else json.dumps(rep, indent=1))
 
 

@@ -37,7 +37,8 @@ def applicable_kinds(layer, half=False):
         if taps_ok:
             kinds.append(1)
         if layer.winograd_ok:
-            kinds += [2, 3] if half else [2, 3, 5]
+            # float16 Winograd is offered from 16 input channels up; F(6x6) in float32 only
+            kinds += ([2, 3] if layer.c >= 16 else []) if half else [2, 3, 5]
     if layer.is_depthwise and layer.r == layer.s and layer.r in (3, 5) and layer.stride in (1, 2):
         kinds.append(4)
     return kinds

@@ -54,10 +54,16 @@ def test_kind_supported_rules():
     assert not nnv.nnv_kind_supported(D(groups=2, dtype=1), 1)
     assert nnv.nnv_kind_supported(D(c=64, k=64, groups=2, dtype=1), 1)
     assert nnv.nnv_kind_supported(D(groups=2, dtype=1, r=1, s=1, pad_h=0, pad_w=0), 1)
+    # float16 Winograd needs at least 16 input channels (accuracy), F(6x6) is float32 only
+    assert [nnv.nnv_kind_supported(D(dtype=1), k) for k in (2, 3, 5)] == [True, True, False]
+    assert [nnv.nnv_kind_supported(D(c=15, dtype=1), k) for k in (2, 3, 5)] == [False, False, False]
+    assert [nnv.nnv_kind_supported(D(c=15), k) for k in (2, 3, 5)] == [True, True, True]
+    assert nnv.nnv_transformed_bytes(D(c=15, dtype=1), 3) == 0 and nnv.nnv_workspace_bytes(D(c=15, dtype=1), 3) == 0
 
 
 @pytest.mark.parametrize("bad", [dict(n=0), dict(c=-1), dict(groups=3), dict(stride_h=0), dict(pad_w=-1),
-                                 dict(dtype=2), dict(h=1, w=1, pad_h=0, pad_w=0), dict(k=70000)])
+                                 dict(dtype=2), dict(h=1, w=1, pad_h=0, pad_w=0), dict(k=70000),
+                                 dict(pad_h=2 ** 30), dict(pad_w=2 ** 31 - 1), dict(pad_h=2 ** 29, pad_w=2 ** 29)])
 def test_bad_descriptors(bad):
     d = D(**bad)
     with pytest.raises(nnv.NnvError) as e:

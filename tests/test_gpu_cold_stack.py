@@ -5,6 +5,8 @@ import numpy as np
 import pytest
 
 from nnv_workloads import stack, layer_tensors
+from nnv_testlib import conv_tolerance, KIND_NAMES
+from oracle import cdirect
 
 pytestmark = pytest.mark.gpu
 
@@ -88,6 +90,31 @@ def test_captured_pass_replays(env):
         torch.cuda.synchronize()
         for a, b in zip(wt + ys, wt0 + ys0):
             assert torch.equal(a, b), rep
+    # the outputs of the last replay (two streams, graph replay) against the float64 definition
+    for i, (layer, kind, y) in enumerate(zip(stack("resnet18"), kinds, ys)):
+        w, x = layer_tensors(layer, 4000 + i)
+        ref = cdirect.conv2d_direct_c(x, w, layer.stride, layer.pad, layer.groups)
+        got = y.cpu().numpy().astype(np.float64).reshape(ref.shape)
+        err = np.abs(got - ref).max() / np.abs(ref).max()
+        assert err <= conv_tolerance(kind, False), f"{layer.name} {KIND_NAMES[kind]}: rel err {err:.3e}"
+
+
+def test_pipelined_mobilenetv2_against_the_oracle(env):
+    """Two-stream pass over the MobileNetV2-shaped stack (depthwise, pointwise GEMM, direct stem),
+    stage size 3, every output against the float64 definition."""
+    nnv, torch = env
+    descs, kinds, raw, xs, ws, outputs = build_stack(nnv, torch, "mobilenetv2", mixed)
+    wt, ys = outputs()
+    s_exec, s_tx = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    nnv.nnv_cold_stack(descs, kinds, raw, wt, xs, ys, ws, 3, s_exec, s_tx)
+    s_exec.synchronize()
+    for i, (layer, kind, y) in enumerate(zip(stack("mobilenetv2"), kinds, ys)):
+        w, x = layer_tensors(layer, 4000 + i)
+        ref = cdirect.conv2d_direct_c(x, w, layer.stride, layer.pad, layer.groups)
+        got = y.cpu().numpy().astype(np.float64).reshape(ref.shape)
+        err = np.abs(got - ref).max() / np.abs(ref).max()
+        assert err <= conv_tolerance(kind, False), f"{layer.name} {KIND_NAMES[kind]}: rel err {err:.3e}"
 
 
 def test_argument_errors(env):

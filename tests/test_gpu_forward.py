@@ -37,11 +37,6 @@ def check(env, layer, kind, half, seed, bias=False, w_std=None):
         ref16 = oracle_forward_stored(layer, kind, w, x, b)
         e16 = np.abs(got - ref16).max() / np.abs(ref).max()
         assert e16 <= 1.5e-3, f"{layer.name} {KIND_NAMES[kind]}: vs rounded Winograd oracle {e16:.3e}"
-        if layer.c < 16:
-            # the 5e-3 bound is quoted for CNN-sized layers; with a handful of channels the
-            # max-error / max-output ratio of F(4x4) has a heavy tail (the rounded oracle shows
-            # the same excess), so tiny layers get twice the bound
-            tol = 2 * tol
     assert err <= tol, f"{layer.name} {KIND_NAMES[kind]} half={half}: rel err {err:.3e}"
     return err
 
@@ -84,6 +79,7 @@ SMALL = [
     Ly("g2_5x5", 96, 13, 13, 64, 5, 1, 2, groups=2),
     Ly("g2_3x3_aligned", 64, 12, 12, 96, 3, 1, 1, groups=2), # Cg = 32: float16 channel-last copy applies
     Ly("g4_s2_n2", 32, 11, 11, 48, 3, 2, 1, groups=4, n=2),
+    Ly("g2_15x15", 16, 20, 20, 32, 15, 1, 7, groups=2),      # direct: staged taps would exceed 64 KiB of LDS -> plain kernel
 ]
 CASES = [(l, k, h) for h in (False, True) for l in SMALL for k in applicable_kinds(l, h)]
 
@@ -124,7 +120,7 @@ def test_fused_bias_relu(env, layer, kind):
         ref = np.maximum(oracle_forward(layer, half, w, x, b), 0.0)
         plain = oracle_forward(layer, half, w, x, b)
         assert (got >= 0).all() and (got == 0).any()
-        tol = conv_tolerance(kind, half) * (2 if layer.c < 16 and half and kind == 3 else 1)
+        tol = conv_tolerance(kind, half)
         assert np.abs(got - ref).max() <= tol * np.abs(plain).max()
 
 

@@ -7,6 +7,7 @@ import pytest
 
 from nnv_workloads import ConvLayer
 from nnv_testlib import conv_tolerance, KIND_NAMES
+from oracle.direct import conv2d_at
 
 pytestmark = pytest.mark.gpu
 
@@ -29,25 +30,6 @@ def sample_positions(layer, rng, n_random=1500):
     return pos
 
 
-def oracle_at(layer, x, w, pos):
-    """y[0, k, p, q] of the zero-padded cross-correlation in float64, one position at a time."""
-    out = np.empty(len(pos))
-    cg, kg = layer.c // layer.groups, layer.k // layer.groups
-    for i, (k, p, q) in enumerate(pos):
-        c0 = (k // kg) * cg
-        acc = 0.0
-        for r in range(layer.r):
-            ih = p * layer.stride - layer.pad + r
-            if not 0 <= ih < layer.h:
-                continue
-            for s in range(layer.s):
-                iw = q * layer.stride - layer.pad + s
-                if 0 <= iw < layer.w:
-                    acc += float(np.dot(x[0, c0:c0 + cg, ih, iw].astype(np.float64), w[k, :, r, s].astype(np.float64)))
-        out[i] = acc
-    return out
-
-
 def run_and_check(nnv, torch, layer, kinds, seed):
     dev = torch.device("cuda:0")
     rng = np.random.default_rng(seed)
@@ -55,7 +37,7 @@ def run_and_check(nnv, torch, layer, kinds, seed):
     w = (rng.standard_normal((layer.k, layer.c // layer.groups, layer.r, layer.s)) *
          np.sqrt(2.0 / (layer.c // layer.groups * layer.r * layer.s))).astype(np.float32)
     pos = sample_positions(layer, rng)
-    ref = oracle_at(layer, x, w, pos)
+    ref = conv2d_at(x, w, [(0, k, p, q) for k, p, q in pos], layer.stride, layer.pad, layer.groups)
     scale = np.abs(ref).max()
     xd, wd = torch.from_numpy(x).to(dev), torch.from_numpy(w).to(dev)
     desc = nnv.make_desc(layer, nnv.F32)

@@ -102,7 +102,7 @@ def check_wino_u(got, exp64, bound, half):
 @pytest.mark.parametrize("layer", WINO_LAYERS, ids=lambda l: l.name)
 def test_wino_weight_transform(env, layer, kind, half):
     nnv, torch = env
-    if half and kind == 5:
+    if half and (kind == 5 or layer.c < 16):     # refused pairings: F(6x6) in float16, float16 Winograd below 16 channels
         desc = nnv.make_desc(layer, nnv.F16)
         assert nnv.nnv_kind_supported(desc, kind) == 0 and nnv.nnv_transformed_bytes(desc, kind) == 0
         return

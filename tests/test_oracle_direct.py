@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 import scipy.signal
 
-from oracle.direct import conv2d_bruteforce, conv2d_direct, out_size
+from oracle.direct import conv2d_at, conv2d_bruteforce, conv2d_direct, out_size
 from oracle.cdirect import conv2d_direct_c
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
@@ -132,3 +132,29 @@ def test_c_oracle_matches_numpy_on_single3x3_workload():
     a = conv2d_direct(x, w, layer.stride, layer.pad)
     b = conv2d_direct_c(x, w, layer.stride, layer.pad)
     np.testing.assert_allclose(a, b, rtol=0, atol=1e-13 * np.abs(a).max())
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_single_positions_match_bruteforce(case):
+    """conv2d_at at every output position of the tiny layers = the 7-loop definition."""
+    N, C, H, W, K, R, st, pad, g = case
+    rng = np.random.default_rng(7 + sum(case))
+    x = rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32)
+    w = rng.standard_normal((K, C // g, R, R)).astype(np.float32)
+    b = rng.standard_normal(K)
+    ref = conv2d_bruteforce(x, w, st, pad, g, b)
+    pos = list(itertools.product(*[range(d) for d in ref.shape]))
+    got = conv2d_at(x, w, pos, st, pad, g, b)
+    np.testing.assert_allclose(got, ref.ravel(), rtol=0, atol=1e-13)
+    np.testing.assert_allclose(conv2d_at(x, w, pos[::3], st, pad, g), (ref - b.reshape(1, K, 1, 1)).ravel()[::3],
+                               rtol=0, atol=1e-13)
+
+
+def test_single_positions_hand_worked():
+    """The hand-worked 3x3 examples, one position at a time (catches a flip or a transposition
+    of the taps and a wrong stride or padding origin)."""
+    x = np.arange(1, 10, dtype=np.float64).reshape(1, 1, 3, 3)
+    for name, stride, w, y in _read_sobel():
+        n = out_size(3, 3, stride, 1)
+        pos = [(0, 0, p, q) for p in range(n) for q in range(n)]
+        assert conv2d_at(x, w, pos, stride, 1).tolist() == y.tolist(), name
