@@ -155,6 +155,21 @@ int nnv_conv_forward_relu(const nnv_conv_desc *desc, nnv_kind kind, const void *
                           const float *bias, void *y, void *workspace, size_t workspace_bytes,
                           void *hip_stream);
 
+/* nnv_conv_forward for callers that cannot allocate or pass device scratch (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation): the workspace is
+ * a static device array of NNV_STATIC_SCRATCH_BYTES that is part of the library's code
+ * object (each GPU the library runs on holds its own copy until the process ends).  The
+ * call allocates nothing.  The first call on a device looks the array's address up once
+ * (make that call before starting a capture).  A layer whose nnv_workspace_bytes exceeds
+ * NNV_STATIC_SCRATCH_BYTES is refused with NNV_E_WORKSPACE.  Every call on one GPU uses the
+ * same array: nothing in it has to start at zero (each kernel overwrites what the next one
+ * reads), but two calls that overlap in time on one GPU (different streams) race -- keep
+ * them on one stream or order them with events.  Other arguments, results and errors as
+ * nnv_conv_forward. */
+#define NNV_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+int nnv_conv_forward_static(const nnv_conv_desc *desc, nnv_kind kind, const void *x, const void *w_tx,
+                            const float *bias, void *y, void *hip_stream);
+
 /* Per-operation profiling (the latency table Algorithm 1 consumes; Section 3.3
  * re-profiles operations while planning).  Runs `warmup` untimed and `reps`
  * timed repetitions of the transformation and, separately, of the forward pass,

@@ -16,7 +16,7 @@ F32, F16 = 0, 1
 
 EXPORTS = ("nnv_layout_version", "nnv_status_string", "nnv_last_hip_error", "nnv_kind_supported",
            "nnv_transformed_bytes", "nnv_workspace_bytes", "nnv_transform_weights",
-           "nnv_transform_weights_grouped", "nnv_conv_forward", "nnv_conv_forward_relu", "nnv_time_layer", "nnv_cold_stack", "nnv_cache_write",
+           "nnv_transform_weights_grouped", "nnv_conv_forward", "nnv_conv_forward_relu", "nnv_conv_forward_static", "nnv_time_layer", "nnv_cold_stack", "nnv_cache_write",
            "nnv_cache_read")
 
 
@@ -79,6 +79,8 @@ def load():
                                      c_size_t, c_void_p]
     lib.nnv_conv_forward_relu.restype = c_int
     lib.nnv_conv_forward_relu.argtypes = lib.nnv_conv_forward.argtypes
+    lib.nnv_conv_forward_static.restype = c_int
+    lib.nnv_conv_forward_static.argtypes = [POINTER(ConvDesc), c_int, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.nnv_time_layer.restype = c_int
     lib.nnv_time_layer.argtypes = [POINTER(ConvDesc), c_int, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                    c_size_t, c_void_p, c_size_t, c_int, c_int, c_void_p, POINTER(Timing)]
@@ -172,6 +174,14 @@ def nnv_conv_forward_relu(desc: ConvDesc, kind: int, x, w_tx, bias, y, workspace
         workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().nnv_conv_forward_relu(byref(desc), kind, _ptr(x), _ptr(w_tx), _ptr(bias), _ptr(y), _ptr(workspace),
                                         workspace_bytes, _stream(stream)), "nnv_conv_forward_relu")
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def nnv_conv_forward_static(desc: ConvDesc, kind: int, x, w_tx, bias, y, stream=None) -> None:
+    _check(load().nnv_conv_forward_static(byref(desc), kind, _ptr(x), _ptr(w_tx), _ptr(bias), _ptr(y), _stream(stream)),
+           "nnv_conv_forward_static")
 
 
 def nnv_time_layer(desc: ConvDesc, kind: int, w_raw, w_tx, x, y, workspace, flush=None, warmup=2, reps=10,

@@ -2,11 +2,17 @@
 // dispatch by kernel kind and the per-operation timing.
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 #include "nnv_internal.h"
 
 using namespace nnv;
+
+// Scratch of nnv_conv_forward_static: one array per GPU, part of the loaded code object, so no
+// call ever allocates it.  In host code this name is only a handle for hipGetSymbolAddress; the
+// device address it yields (per device) is what kernels and copies get.
+static __device__ __align__(256) unsigned char nnv_static_scratch[NNV_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -206,6 +212,28 @@ int forward_args(const nnv_conv_desc *desc, nnv_kind kind, const void *x, const 
     return NNV_OK;
 }
 
+// Device address of nnv_static_scratch on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void **out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kMaxDevices) return NNV_E_ARG;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(nnv_static_scratch));
+        if (e != hipSuccess) return hip_fail(e);
+        if (!p || misaligned(p)) return NNV_E_ALIGN;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return NNV_OK;
+}
+
 double median(std::vector<float> v) {
     std::sort(v.begin(), v.end());
     const size_t n = v.size();
@@ -283,6 +311,20 @@ int nnv_conv_forward_relu(const nnv_conv_desc *desc, nnv_kind kind, const void *
     if (rc) return rc;
     g.relu = 1;
     return forward_checked(g, kind, x, w_tx, bias, y, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+int nnv_conv_forward_static(const nnv_conv_desc *desc, nnv_kind kind, const void *x, const void *w_tx,
+                            const float *bias, void *y, void *hip_stream) {
+    Geo g;
+    // argument checks as in nnv_conv_forward, against a workspace of the static size; the
+    // address only has to be non-NULL and aligned here
+    void *probe = reinterpret_cast<void *>(static_cast<uintptr_t>(256));
+    int rc = forward_args(desc, kind, x, w_tx, bias, y, probe, NNV_STATIC_SCRATCH_BYTES, &g);
+    if (rc) return rc;
+    void *ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc) return rc;
+    return forward_checked(g, kind, x, w_tx, bias, y, ws, static_cast<hipStream_t>(hip_stream));
 }
 
 int nnv_cold_stack(int n_layers, const nnv_conv_desc *descs, const nnv_kind *kinds, const float *const *w_raw,
