@@ -155,6 +155,28 @@ int nnv_conv_forward_relu(const nnv_conv_desc *desc, nnv_kind kind, const void *
                           const float *bias, void *y, void *workspace, size_t workspace_bytes,
                           void *hip_stream);
 
+/* Kernel execution of n_layers INDEPENDENT layers (none reads what another writes) in as
+ * few launches as possible.  The decision stage profiles every kernel candidate of every
+ * layer (Algorithm 1's input, Section 3.3, Table 2), and a batch-1 layer alone neither fills
+ * the GPU nor outlasts its own launch: IM2COL_GEMM layers of one storage type share one
+ * launch of single-wavefront work items (output tile x range of the reduction) and one
+ * reduction launch; layers of other kinds are executed one after the other as by
+ * nnv_conv_forward.  Results per layer are as nnv_conv_forward's up to the order of the
+ * float32 summation over the channels (deterministic: fixed order).
+ *   descs, kinds, x, w_tx, y : HOST arrays of length n_layers (descriptors, kinds, device
+ *       pointers as for nnv_conv_forward); outputs must not overlap
+ *   bias  : NULL, or a HOST array of n_layers device pointers (entries may be NULL)
+ *   workspace : device, >= nnv_conv_forward_grouped_workspace_bytes(...) bytes
+ *   flags : 0, or NNV_FORWARD_RELU for y = max(conv + bias, 0) on every layer
+ * Errors: NULL, BAD_DESC, ARG, UNSUPPORTED, WORKSPACE, ALIGN, HIP; nothing is launched unless
+ * every layer passes the checks. */
+#define NNV_FORWARD_RELU 1u
+size_t nnv_conv_forward_grouped_workspace_bytes(int n_layers, const nnv_conv_desc *descs, const nnv_kind *kinds);
+int nnv_conv_forward_grouped(int n_layers, const nnv_conv_desc *descs, const nnv_kind *kinds,
+                             const void *const *x, const void *const *w_tx, const float *const *bias,
+                             void *const *y, void *workspace, size_t workspace_bytes, unsigned flags,
+                             void *hip_stream);
+
 /* nnv_conv_forward for callers that cannot allocate or pass device scratch (code under HIP
  * graph capture, tight serving loops, harnesses that forbid allocation): the workspace is
  * a static device array of NNV_STATIC_SCRATCH_BYTES that is part of the library's code

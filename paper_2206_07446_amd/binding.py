@@ -16,7 +16,8 @@ F32, F16 = 0, 1
 
 EXPORTS = ("nnv_layout_version", "nnv_status_string", "nnv_last_hip_error", "nnv_kind_supported",
            "nnv_transformed_bytes", "nnv_workspace_bytes", "nnv_transform_weights",
-           "nnv_transform_weights_grouped", "nnv_conv_forward", "nnv_conv_forward_relu", "nnv_conv_forward_static", "nnv_time_layer", "nnv_cold_stack", "nnv_cache_write",
+           "nnv_transform_weights_grouped", "nnv_conv_forward", "nnv_conv_forward_relu", "nnv_conv_forward_static", "nnv_conv_forward_grouped",
+           "nnv_conv_forward_grouped_workspace_bytes", "nnv_time_layer", "nnv_cold_stack", "nnv_cache_write",
            "nnv_cache_read")
 
 
@@ -79,6 +80,11 @@ def load():
                                      c_size_t, c_void_p]
     lib.nnv_conv_forward_relu.restype = c_int
     lib.nnv_conv_forward_relu.argtypes = lib.nnv_conv_forward.argtypes
+    lib.nnv_conv_forward_grouped_workspace_bytes.restype = c_size_t
+    lib.nnv_conv_forward_grouped_workspace_bytes.argtypes = [c_int, POINTER(ConvDesc), POINTER(c_int)]
+    lib.nnv_conv_forward_grouped.restype = c_int
+    lib.nnv_conv_forward_grouped.argtypes = [c_int, POINTER(ConvDesc), POINTER(c_int), POINTER(c_void_p), POINTER(c_void_p),
+                                             POINTER(c_void_p), POINTER(c_void_p), c_void_p, c_size_t, ctypes.c_uint, c_void_p]
     lib.nnv_conv_forward_static.restype = c_int
     lib.nnv_conv_forward_static.argtypes = [POINTER(ConvDesc), c_int, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.nnv_time_layer.restype = c_int
@@ -174,6 +180,25 @@ def nnv_conv_forward_relu(desc: ConvDesc, kind: int, x, w_tx, bias, y, workspace
         workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().nnv_conv_forward_relu(byref(desc), kind, _ptr(x), _ptr(w_tx), _ptr(bias), _ptr(y), _ptr(workspace),
                                         workspace_bytes, _stream(stream)), "nnv_conv_forward_relu")
+
+
+FORWARD_RELU = 1
+
+
+def nnv_conv_forward_grouped_workspace_bytes(descs, kinds) -> int:
+    n = len(descs)
+    return int(load().nnv_conv_forward_grouped_workspace_bytes(n, (ConvDesc * n)(*descs), (c_int * n)(*kinds)))
+
+
+def nnv_conv_forward_grouped(descs, kinds, x, w_tx, bias, y, workspace, workspace_bytes=None, flags=0, stream=None) -> None:
+    """bias: None, or a list with a tensor or None per layer."""
+    n = len(descs)
+    arr = lambda ts: (c_void_p * n)(*[None if t is None else (t if isinstance(t, int) else t.data_ptr()) for t in ts])
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().nnv_conv_forward_grouped(n, (ConvDesc * n)(*descs), (c_int * n)(*kinds), arr(x), arr(w_tx),
+                                           None if bias is None else arr(bias), arr(y), _ptr(workspace), workspace_bytes,
+                                           flags, _stream(stream)), "nnv_conv_forward_grouped")
 
 
 STATIC_SCRATCH_BYTES = 64 << 20

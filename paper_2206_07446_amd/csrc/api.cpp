@@ -234,6 +234,59 @@ int static_scratch(void **out) {
     return NNV_OK;
 }
 
+// ---- nnv_conv_forward_grouped: which layers share a launch, and where their scratch lies.
+// Layers of one launch run concurrently, so each needs a workspace region of its own; launches
+// follow one another on the stream, so the regions of different launches overlap.
+struct GroupedPlan {
+    struct Batch {
+        int cls;                    // 0: single layer through forward_checked, 1: IM2COL_GEMM work items
+        std::vector<int> layers;
+        std::vector<size_t> offset; // workspace offset of each layer's region
+    };
+    std::vector<Batch> batches;
+    size_t bytes = 0;
+};
+
+GroupedPlan plan_grouped(int n, const Geo *geos, const nnv_kind *kinds) {
+    GroupedPlan gp;
+    std::vector<char> taken(n, 0);
+    for (int half = 0; half < 2; ++half) {
+        GroupedPlan::Batch cur{1, {}, {}};
+        size_t off = 0;
+        auto close = [&]() {
+            if (!cur.layers.empty()) { gp.bytes = std::max(gp.bytes, off); gp.batches.push_back(cur); }
+            cur.layers.clear(); cur.offset.clear(); off = 0;
+        };
+        for (int i = 0; i < n; ++i) {
+            if (kinds[i] != NNV_IM2COL_GEMM || (geos[i].dtype == NNV_F16) != (half == 1)) continue;
+            taken[i] = 1;
+            cur.layers.push_back(i);
+            cur.offset.push_back(off);
+            off += im2col_items_workspace_bytes(geos[i]);
+            if ((int)cur.layers.size() == kMaxGemmLayers) close();
+        }
+        close();
+    }
+    for (int i = 0; i < n; ++i) {
+        if (taken[i]) continue;
+        gp.batches.push_back(GroupedPlan::Batch{0, {i}, {0}});
+        gp.bytes = std::max(gp.bytes, ws_bytes(geos[i], kinds[i]));
+    }
+    return gp;
+}
+
+int grouped_geos(int n, const nnv_conv_desc *descs, const nnv_kind *kinds, std::vector<Geo> *geos) {
+    if (!descs || !kinds) return NNV_E_NULL;
+    geos->resize(n);
+    for (int i = 0; i < n; ++i) {
+        int rc = make_geo(&descs[i], &(*geos)[i]);
+        if (rc) return rc;
+        if (kinds[i] < 0 || kinds[i] >= NNV_KIND_COUNT) return NNV_E_ARG;
+        if (!supported((*geos)[i], kinds[i])) return NNV_E_UNSUPPORTED;
+    }
+    return NNV_OK;
+}
+
 double median(std::vector<float> v) {
     std::sort(v.begin(), v.end());
     const size_t n = v.size();
@@ -311,6 +364,57 @@ int nnv_conv_forward_relu(const nnv_conv_desc *desc, nnv_kind kind, const void *
     if (rc) return rc;
     g.relu = 1;
     return forward_checked(g, kind, x, w_tx, bias, y, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t nnv_conv_forward_grouped_workspace_bytes(int n_layers, const nnv_conv_desc *descs, const nnv_kind *kinds) {
+    if (n_layers <= 0) return 0;
+    std::vector<Geo> geos;
+    if (grouped_geos(n_layers, descs, kinds, &geos)) return 0;
+    return plan_grouped(n_layers, geos.data(), kinds).bytes;
+}
+
+int nnv_conv_forward_grouped(int n_layers, const nnv_conv_desc *descs, const nnv_kind *kinds, const void *const *x,
+                             const void *const *w_tx, const float *const *bias, void *const *y, void *workspace,
+                             size_t workspace_bytes, unsigned flags, void *hip_stream) {
+    if (n_layers < 0 || (flags & ~(unsigned)NNV_FORWARD_RELU)) return NNV_E_ARG;
+    if (n_layers == 0) return NNV_OK;
+    if (!x || !w_tx || !y) return NNV_E_NULL;
+    std::vector<Geo> geos;
+    int rc = grouped_geos(n_layers, descs, kinds, &geos);
+    if (rc) return rc;
+    for (int i = 0; i < n_layers; ++i) {
+        if (!x[i] || !w_tx[i] || !y[i]) return NNV_E_NULL;
+        if (misaligned(x[i]) || misaligned(w_tx[i]) || misaligned(y[i]) ||
+            (bias && bias[i] && (reinterpret_cast<uintptr_t>(bias[i]) & 3)))
+            return NNV_E_ALIGN;
+        geos[i].relu = (flags & NNV_FORWARD_RELU) ? 1 : 0;
+    }
+    const GroupedPlan gp = plan_grouped(n_layers, geos.data(), kinds);
+    if (gp.bytes > 0 && !workspace) return NNV_E_NULL;
+    if (workspace_bytes < gp.bytes) return NNV_E_WORKSPACE;
+    if (gp.bytes > 0 && misaligned(workspace)) return NNV_E_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    for (const GroupedPlan::Batch &b : gp.batches) {
+        if (b.cls == 0) {
+            const int i = b.layers[0];
+            rc = forward_checked(geos[i], kinds[i], x[i], w_tx[i], bias ? bias[i] : nullptr, y[i], workspace, st);
+            if (rc) return rc;
+            continue;
+        }
+        const int m = (int)b.layers.size();
+        std::vector<Geo> bg(m);
+        std::vector<const void *> bx(m), bw(m);
+        std::vector<const float *> bb(m);
+        std::vector<void *> by(m), bws(m);
+        for (int j = 0; j < m; ++j) {
+            const int i = b.layers[j];
+            bg[j] = geos[i]; bx[j] = x[i]; bw[j] = w_tx[i]; bb[j] = bias ? bias[i] : nullptr; by[j] = y[i];
+            bws[j] = static_cast<char *>(workspace) + b.offset[j];
+        }
+        hipError_t e = launch_im2col_items(m, bg.data(), bx.data(), bw.data(), bb.data(), by.data(), bws.data(), st);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return NNV_OK;
 }
 
 int nnv_conv_forward_static(const nnv_conv_desc *desc, nnv_kind kind, const void *x, const void *w_tx,

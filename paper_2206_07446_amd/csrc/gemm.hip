@@ -24,6 +24,8 @@
 // offsets.  A chunk (one channel block x all taps, or 8 channel blocks for 1x1) is loaded
 // one chunk ahead of the MFMAs (register ping-pong).  KS wavefronts of a workgroup share one
 // output tile and split the channel blocks; partial sums meet in LDS, fixed order.
+#include <algorithm>
+#include <cstdlib>
 #include "nnv_internal.h"
 #include "buf.h"
 
@@ -72,34 +74,33 @@ template <bool HALF, int MODE> struct ModeT {
     static constexpr int NVOFF = (MODE == 0 || MODE == 1) ? 1 : STEPS;                     // tap offsets kept per lane
 };
 
+// Output pixels of a wavefront's tile columns: image, position in the P x Q plane, inside the problem or not.
+template <int TN> struct PixState {
+    int img[TN], pq[TN];
+    bool valid[TN];
+};
+
+// The k-loop of one wavefront: TM x TN blocks of 16 x 16 outputs (panels mb0.., 16-pixel blocks
+// nb0..), summed over the ks-th of nsplit equal ranges of the layer's units.
 template <bool HALF, int TM, int TN, int MODE, int NBUF>
-__global__ __launch_bounds__(1024) void im2col_gemm_kernel(const GemmParams g) {
+__device__ __forceinline__ void gemm_accumulate(const GemmParams &g, const int mb0, const int nb0, const int ks,
+                                                const int nsplit, const int lane, floatx4 (&acc)[TM][TN],
+                                                PixState<TN> &px) {
     typedef typename FragT<HALF>::type frag_t;
     typedef ModeT<HALF, MODE> MT;
     constexpr int STEPS = MT::STEPS, UNITS = MT::UNITS, NVOFF = MT::NVOFF;
     constexpr bool ROW = MT::ROW, WHOLE3 = MT::WHOLE3;
     constexpr uint32_t FB = sizeof(frag_t);            // bytes per lane of one fragment
     constexpr uint32_t FRAG = 64 * FB;                 // bytes of one fragment
-    extern __shared__ __align__(16) float red[];
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar
     const int col = lane & 15, slot = lane >> 4;
-    const int KS = 1 << g.ks_shift;
-    const int ks = wave & (KS - 1), nt = wave >> g.ks_shift;             // k-split index, tile within the workgroup
-    const int tiles_per_wg = (blockDim.x >> 6) >> g.ks_shift;
-    const int ltile = xcd_logical_tile(g.grid_nx * g.grid_ny);
-    if (ltile < 0) return;                                               // whole workgroup: grid padding
-    const int bx = g.m_major ? ltile % g.grid_nx : ltile / g.grid_ny;
-    const int by = g.m_major ? ltile / g.grid_nx : ltile % g.grid_ny;
-    const int mb0 = by * TM;                              // panel index over all groups; TM panels stay in one group
-    const int grp = mb0 / g.kg16, mbl = mb0 - grp * g.kg16;
+    const int grp = mb0 / g.kg16;
     const int cbase = grp * g.Cg;                         // first input channel of the group
-    const int nb0 = (bx * tiles_per_wg + nt) * TN;
     const int PQ = g.P * g.Q, RS = g.R * g.S;
 
     // ---- per-lane pixel state: origin of the patch in x (bytes, may be negative) and tap offsets
-    int xbase[TN], ih0[TN], iw0[TN], pix_img[TN], pix_pq[TN];
-    bool pvalid[TN];
+    int xbase[TN], ih0[TN], iw0[TN];
+    int (&pix_img)[TN] = px.img, (&pix_pq)[TN] = px.pq;
+    bool (&pvalid)[TN] = px.valid;
 #pragma unroll
     for (int t = 0; t < TN; ++t) {
         const int n = (nb0 + t) * 16 + col;
@@ -134,7 +135,7 @@ __global__ __launch_bounds__(1024) void im2col_gemm_kernel(const GemmParams g) {
     }
     // ---- this wavefront's range of units
     const int nunits = MODE == 0 ? g.cblocks * RS : ROW ? g.cblocks * g.R : g.cblocks;
-    const int per_wave = (nunits + KS - 1) >> g.ks_shift;
+    const int per_wave = (nunits + nsplit - 1) / nsplit;
     const int u_begin = min(nunits, ks * per_wave);
     const int u_end = min(nunits, u_begin + per_wave);
     const int steps_per_unit = MODE == 0 ? 1 : ROW ? MODE : RS;   // MODE 1: RS == 1
@@ -216,7 +217,6 @@ __global__ __launch_bounds__(1024) void im2col_gemm_kernel(const GemmParams g) {
         }
     };
 
-    floatx4 acc[TM][TN];
 #pragma unroll
     for (int m = 0; m < TM; ++m)
 #pragma unroll
@@ -258,6 +258,45 @@ __global__ __launch_bounds__(1024) void im2col_gemm_kernel(const GemmParams g) {
         }
     }
 
+}
+
+// One finished output: row 4 * slot + j of panel mb0 + m, pixel column t of the tile; bias, optional
+// clamp at zero, one rounding to the storage type.
+__device__ __forceinline__ void gemm_store(const GemmParams &g, const int img, const int pq, const bool valid,
+                                           const int mb0, const int m, const int j, const int slot, const float v) {
+    const int grp = mb0 / g.kg16, mbl = mb0 - grp * g.kg16;
+    const int kl = (mbl + m) * 16 + slot * 4 + j;         // row within the group
+    const int k = grp * g.Kg + kl;
+    if (kl < g.Kg && mbl + m < g.kg16 && valid) {
+        const size_t o = ((size_t)img * g.K + k) * (g.P * g.Q) + pq;
+        float r = v + (g.bias ? g.bias[k] : 0.f);
+        if (g.relu) r = fmaxf(r, 0.f);
+        if (g.half_out) static_cast<__half *>(g.y)[o] = __float2half_rn(r);
+        else static_cast<float *>(g.y)[o] = r;
+    }
+}
+
+// One layer per launch: a workgroup of KS wavefronts owns one output tile, the wavefronts split
+// the channel blocks and add their partial sums through LDS in fixed order.
+template <bool HALF, int TM, int TN, int MODE, int NBUF>
+__global__ __launch_bounds__(1024) void im2col_gemm_kernel(const GemmParams g) {
+    extern __shared__ __align__(16) float red[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar
+    const int slot = lane >> 4;
+    const int KS = 1 << g.ks_shift;
+    const int ks = wave & (KS - 1), nt = wave >> g.ks_shift;             // k-split index, tile within the workgroup
+    const int tiles_per_wg = (blockDim.x >> 6) >> g.ks_shift;
+    const int ltile = xcd_logical_tile(g.grid_nx * g.grid_ny);
+    if (ltile < 0) return;                                               // whole workgroup: grid padding
+    const int bx = g.m_major ? ltile % g.grid_nx : ltile / g.grid_ny;
+    const int by = g.m_major ? ltile / g.grid_nx : ltile % g.grid_ny;
+    const int mb0 = by * TM;                              // panel index over all groups; TM panels stay in one group
+    const int nb0 = (bx * tiles_per_wg + nt) * TN;
+    floatx4 acc[TM][TN];
+    PixState<TN> px;
+    gemm_accumulate<HALF, TM, TN, MODE, NBUF>(g, mb0, nb0, ks, KS, lane, acc, px);
+
     // ---- sum the KS partial tiles through LDS: red[((nt * KS + ks) * NREG + reg) * 64 + lane]
     constexpr int NREG = TM * TN * 4;
     if (KS > 1) {
@@ -285,18 +324,120 @@ __global__ __launch_bounds__(1024) void im2col_gemm_kernel(const GemmParams g) {
                     v = 0.f;
                     for (int z = 0; z < KS; ++z) v += red[((nt * KS + z) * NREG + reg) * 64 + lane];
                 }
-                const int kl = (mbl + m) * 16 + slot * 4 + j;         // row within the group
-                const int k = grp * g.Kg + kl;
-                if (kl < g.Kg && mbl + m < g.kg16 && pvalid[t]) {
-                    const size_t o = ((size_t)pix_img[t] * g.K + k) * PQ + pix_pq[t];
-                    float r = v + (g.bias ? g.bias[k] : 0.f);
-                    if (g.relu) r = fmaxf(r, 0.f);
-                    if (g.half_out) static_cast<__half *>(g.y)[o] = __float2half_rn(r);
-                    else static_cast<float *>(g.y)[o] = r;
-                }
+                gemm_store(g, px.img[t], px.pq[t], px.valid[t], mb0, m, j, slot, v);
             }
         }
     }
+}
+
+// ---------------------------------------------------------------- many layers in one launch
+// A batch-1 layer neither fills 256 CUs nor runs long enough to hide its launch, its first loads
+// and its epilogue.  Independent layers (what the decision stage profiles, and what a model's
+// parallel branches are) therefore go into ONE launch of single-wavefront workgroups, one per
+// work item: an item is one output tile (TM x 2 blocks of 16 x 16) of one layer over one of the
+// nsplit ranges its reduction is cut into, the ranges sized so that items of different layers
+// take about the same time.  The chip's dispatcher balances the items over the CUs; two to four
+// items are resident per SIMD, so one item's addressing and first loads run under another's
+// MFMAs.  A split layer's items store partial tiles, which a second launch adds in fixed order.
+struct GemmItemLayer {
+    GemmParams g;
+    float *part;        // partial tiles of a split layer (workspace): [tile][split][reg][lane]
+    int item0;          // first item of the layer in the launch
+    int ntn;            // tiles along the pixels
+    int nsplit;         // ranges of the reduction (1: the item stores y itself)
+    int mode, tm;       // chunking mode (ModeT); 16-row panels per tile (1 or 2)
+    int red0;           // first workgroup of the layer in the reduction launch
+};
+struct GemmItemTable {
+    GemmItemLayer layer[kMaxGemmLayers];
+    int nlayers, nitems;
+    int group;          // consecutive items handed to one XCD
+    int nred;           // workgroups of the reduction launch
+};
+static_assert(sizeof(GemmItemTable) <= 4096, "the table is passed by value as the kernel argument");
+
+template <bool HALF, int TM, int MODE>
+__device__ __forceinline__ void gemm_item(const GemmItemLayer &L, const int local, const int lane) {
+    constexpr int TN = 2;
+    const int nb = local % L.ntn, rest = local / L.ntn;
+    const int ks = rest % L.nsplit, mt = rest / L.nsplit;       // order: tile row, range, tile column (fastest)
+    floatx4 acc[TM][TN];
+    PixState<TN> px;
+    gemm_accumulate<HALF, TM, TN, MODE, 2>(L.g, mt * TM, nb * TN, ks, L.nsplit, lane, acc, px);
+    if (L.nsplit == 1) {
+#pragma unroll
+        for (int m = 0; m < TM; ++m)
+#pragma unroll
+            for (int t = 0; t < TN; ++t)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    gemm_store(L.g, px.img[t], px.pq[t], px.valid[t], mt * TM, m, j, lane >> 4, acc[m][t][j]);
+    } else {
+        constexpr int NREG = TM * TN * 4;
+        float *o = L.part + ((size_t)(mt * L.ntn + nb) * L.nsplit + ks) * (NREG * 64) + lane;
+#pragma unroll
+        for (int m = 0; m < TM; ++m)
+#pragma unroll
+            for (int t = 0; t < TN; ++t)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) o[((m * TN + t) * 4 + j) * 64] = acc[m][t][j];
+    }
+}
+
+template <bool HALF>
+__global__ __launch_bounds__(64) void gemm_items_kernel(const GemmItemTable tbl) {
+    // Workgroup i runs on XCD i % 8.  Groups of `group` consecutive items (neighbouring tiles of
+    // one layer: they share a weight panel) are dealt to the XCDs in turn, so every XCD sees the
+    // same mix of layers in the same order and a panel is fetched into one L2.
+    const int G = tbl.group;
+    const int i = blockIdx.x, xcd = i & 7, j = i >> 3;
+    const int item = ((j / G) * 8 + xcd) * G + j % G;
+    if (item >= tbl.nitems) return;
+    int li = 0;
+    while (li + 1 < tbl.nlayers && item >= tbl.layer[li + 1].item0) ++li;
+    const GemmItemLayer &L = tbl.layer[li];
+    const int local = item - L.item0;
+    const int lane = threadIdx.x;
+    if (L.tm == 2) {
+        switch (L.mode) {
+            case 1: gemm_item<HALF, 2, 1>(L, local, lane); break;
+            case 3: gemm_item<HALF, 2, 3>(L, local, lane); break;
+            case 5: if constexpr (!HALF) gemm_item<HALF, 2, 5>(L, local, lane); break;
+            case 7: if constexpr (!HALF) gemm_item<HALF, 2, 7>(L, local, lane); break;
+            default: gemm_item<HALF, 2, 0>(L, local, lane); break;
+        }
+    } else {
+        switch (L.mode) {
+            case 1: gemm_item<HALF, 1, 1>(L, local, lane); break;
+            case 3: gemm_item<HALF, 1, 3>(L, local, lane); break;
+            case 5: if constexpr (!HALF) gemm_item<HALF, 1, 5>(L, local, lane); break;
+            case 7: if constexpr (!HALF) gemm_item<HALF, 1, 7>(L, local, lane); break;
+            default: gemm_item<HALF, 1, 0>(L, local, lane); break;
+        }
+    }
+}
+
+// Adds the nsplit partial tiles of every split layer in the order of the ranges and stores y.
+__global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmItemTable tbl) {
+    const int b = blockIdx.x;
+    int li = 0;
+    while (li + 1 < tbl.nlayers && b >= tbl.layer[li + 1].red0) ++li;
+    const GemmItemLayer &L = tbl.layer[li];
+    const int nreg = L.tm * 8;                                   // accumulator registers per lane: TM x 2 blocks x 4
+    const int e = (b - L.red0) * 256 + threadIdx.x;              // over [tile][reg][lane]
+    const int tile = e / (nreg * 64), rl = e - tile * (nreg * 64);
+    const int reg = rl >> 6, lane = rl & 63;
+    const float *src = L.part + (size_t)tile * L.nsplit * (nreg * 64) + rl;
+    float v = 0.f;
+    for (int z = 0; z < L.nsplit; ++z) v += src[(size_t)z * (nreg * 64)];
+    const int mt = tile / L.ntn, nb = tile - mt * L.ntn;
+    const int m = reg >> 3, t = (reg >> 2) & 1, jj = reg & 3;
+    const int n = (nb * 2 + t) * 16 + (lane & 15);
+    const bool valid = n < L.g.npix;
+    const int nn = valid ? n : 0;
+    const int PQ = L.g.P * L.g.Q;
+    const int img = nn / PQ;
+    gemm_store(L.g, img, nn - img * PQ, valid, mt * L.tm, m, jj, lane >> 4, v);
 }
 
 // half NCHW -> half [N][H][W][cpad] (channels last, zero padded to a multiple of 32).
@@ -397,8 +538,8 @@ static void launch_gemm_variant(const GemmPlan &pl, const GemmParams &gp, dim3 g
     }
 }
 
-hipError_t launch_im2col(const Geo &g, const void *x, const void *w, const float *bias, void *y, void *ws, hipStream_t st) {
-    const GemmPlan pl = plan_im2col(g);
+// Kernel parameters of a layer apart from the tile plan.
+static GemmParams gemm_params(const Geo &g, int mode, const void *x, const void *w, const float *bias, void *y) {
     const bool half = g.dtype == NNV_F16;
     GemmParams gp{};
     gp.x = x; gp.wp = w; gp.bias = bias; gp.y = y;
@@ -410,22 +551,33 @@ hipError_t launch_im2col(const Geo &g, const void *x, const void *w, const float
     gp.Kg = g.kg; gp.Cg = g.cg;
     gp.cpad = ceil_div(g.c, 32) * 32;
     gp.cblocks = half ? ceil_div(g.cg, 32) : ceil_div(g.cg, 4);
-    const bool gather = half && pl.mode == 1;      // float16 1x1: B fragments gathered from NCHW
+    const bool gather = half && mode == 1;      // float16 1x1: B fragments gathered from NCHW
     gp.c_rem = gather ? g.cg % 32 : half ? 0 : g.cg % 4;
     gp.plane_bytes = (uint32_t)(g.h * g.w * 2);
-    gp.ks_shift = pl.ks_shift;
     gp.half_out = half;
     gp.relu = g.relu;
     gp.x_bytes = gather ? (uint32_t)((size_t)g.n * g.c * g.h * g.w * 2)
                  : half ? (uint32_t)((size_t)g.n * g.h * g.w * gp.cpad * 2) : (uint32_t)((size_t)g.n * g.c * g.h * g.w * 4);
     gp.w_bytes = (uint32_t)((size_t)gp.K16 * gp.cblocks * g.r * g.s * 64 * (half ? 16 : 4));
     gp.cb_stride = gather ? 32u * gp.plane_bytes : half ? 64u : (uint32_t)(4 * g.h * g.w * 4);
-    if (half && !gather) {
-        __half *xt = static_cast<__half *>(ws);
-        dim3 grid(ceil_div(g.h * g.w, 256), gp.cpad / 8, g.n);
-        hipLaunchKernelGGL(to_channels_last_kernel, grid, dim3(256), 0, st, static_cast<const __half *>(x), xt, g.c,
-                           g.h * g.w, gp.cpad);
-        gp.x = xt;
+    return gp;
+}
+
+// float16 layers with a filter larger than 1x1 read x from a channel-last copy in the workspace.
+static void launch_channels_last(const Geo &g, const GemmParams &gp, const void *x, void *xt, hipStream_t st) {
+    dim3 grid(ceil_div(g.h * g.w, 256), gp.cpad / 8, g.n);
+    hipLaunchKernelGGL(to_channels_last_kernel, grid, dim3(256), 0, st, static_cast<const __half *>(x),
+                       static_cast<__half *>(xt), g.c, g.h * g.w, gp.cpad);
+}
+
+hipError_t launch_im2col(const Geo &g, const void *x, const void *w, const float *bias, void *y, void *ws, hipStream_t st) {
+    const GemmPlan pl = plan_im2col(g);
+    const bool half = g.dtype == NNV_F16;
+    GemmParams gp = gemm_params(g, pl.mode, x, w, bias, y);
+    gp.ks_shift = pl.ks_shift;
+    if (half && pl.mode != 1) {
+        launch_channels_last(g, gp, x, ws, st);
+        gp.x = ws;
     }
     const int KS = 1 << pl.ks_shift;
     const int waves = KS;
@@ -440,5 +592,96 @@ hipError_t launch_im2col(const Geo &g, const void *x, const void *w, const float
     else launch_gemm_variant<false>(pl, gp, grid, dim3(64 * waves), lds, st);
     return hipGetLastError();
 }
+
+// ---- many layers in one launch: item plan of one layer
+struct ItemPlan {
+    int mode, tm, nmt, ntn, nsplit;
+    size_t part_bytes;      // partial tiles (0 if the layer is not split)
+    size_t xt_bytes;        // channel-last float16 copy of x (0 if not needed)
+};
+
+// k-steps (one MFMA per 16 x 16 block each) a work item aims at: long enough to amortise an
+// item's addressing, first loads and store, short enough that the chip's last round of items
+// stays small against the whole launch.
+static int g_item_steps = getenv("NNV_ITEM_STEPS") ? atoi(getenv("NNV_ITEM_STEPS")) : 96;   // TUNING ONLY
+
+static ItemPlan plan_items(const Geo &g) {
+    ItemPlan ip{};
+    const GemmPlan pl = plan_im2col(g);
+    const bool half = g.dtype == NNV_F16;
+    ip.mode = pl.mode;
+    ip.xt_bytes = pl.xt_bytes;
+    const int kg16 = ceil_div(g.kg, 16);
+    const int K16 = g.groups * kg16;
+    // two panels per tile unless that leaves a third or more of the tile rows empty
+    // (a tile's panels must belong to one group)
+    ip.tm = (kg16 % 2 == 0 || (g.groups == 1 && kg16 >= 5)) ? 2 : 1;
+    ip.nmt = ceil_div(K16, ip.tm);
+    ip.ntn = ceil_div(ceil_div(g.n * g.p * g.q, 16), 2);
+    const int cblocks = half ? ceil_div(g.cg, 32) : ceil_div(g.cg, 4);
+    const bool row = pl.mode == 5 || pl.mode == 7 || (pl.mode == 3 && half);
+    const int nunits = pl.mode == 0 ? cblocks * g.r * g.s : row ? cblocks * g.r : cblocks;
+    const int unit_steps = pl.mode == 0 ? 1 : row ? pl.mode : g.r * g.s;
+    const int chunk_units = pl.mode == 1 ? (half ? 2 : 8) : 1;
+    const long steps = (long)nunits * unit_steps;
+    long nsplit = (steps + g_item_steps / 2) / g_item_steps;
+    const long most = std::max(1, nunits / chunk_units);          // every range holds at least one chunk
+    nsplit = std::max(1L, std::min(nsplit, most));
+    // ranges are ceil(nunits / nsplit) units long: drop ranges that would come out empty
+    const int per = ceil_div(nunits, (int)nsplit);
+    ip.nsplit = ceil_div(nunits, per);
+    ip.part_bytes = ip.nsplit > 1 ? (size_t)ip.nmt * ip.ntn * ip.nsplit * (ip.tm * 8) * 64 * sizeof(float) : 0;
+    return ip;
+}
+
+size_t im2col_items_workspace_bytes(const Geo &g) {
+    const ItemPlan ip = plan_items(g);
+    return align_up(ip.part_bytes, 256) + align_up(ip.xt_bytes, 256);
+}
+
+// Launches layers [0, n) (all of one storage type, n <= kMaxGemmLayers) as one item launch plus,
+// if any layer is split, one reduction launch.  ws[i] is layer i's own workspace region of
+// im2col_items_workspace_bytes.
+hipError_t launch_im2col_items(int n, const Geo *geos, const void *const *x, const void *const *w, const float *const *bias,
+                               void *const *y, void *const *ws, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    if (n > kMaxGemmLayers) return hipErrorInvalidValue;
+    const bool half = geos[0].dtype == NNV_F16;
+    GemmItemTable tbl{};
+    int items = 0, red = 0;
+    for (int i = 0; i < n; ++i) {
+        const Geo &g = geos[i];
+        if ((g.dtype == NNV_F16) != half) return hipErrorInvalidValue;
+        const ItemPlan ip = plan_items(g);
+        GemmItemLayer &L = tbl.layer[i];
+        L.g = gemm_params(g, ip.mode, x[i], w[i], bias ? bias[i] : nullptr, y[i]);
+        char *region = static_cast<char *>(ws[i]);
+        if (ip.xt_bytes) {
+            void *xt = region + align_up(ip.part_bytes, 256);
+            launch_channels_last(g, L.g, x[i], xt, st);
+            L.g.x = xt;
+        }
+        L.part = ip.nsplit > 1 ? reinterpret_cast<float *>(region) : nullptr;
+        L.item0 = items;
+        L.ntn = ip.ntn;
+        L.nsplit = ip.nsplit;
+        L.mode = ip.mode;
+        L.tm = ip.tm;
+        L.red0 = red;
+        items += ip.nmt * ip.ntn * ip.nsplit;
+        if (ip.nsplit > 1) red += ip.nmt * ip.ntn * (ip.tm * 8) / 4;
+    }
+    tbl.nlayers = n;
+    tbl.nitems = items;
+    tbl.group = getenv("NNV_ITEM_GROUP") ? atoi(getenv("NNV_ITEM_GROUP")) : 8;   // TUNING ONLY
+    tbl.nred = red;
+    const int per_xcd = ceil_div(ceil_div(items, tbl.group), 8) * tbl.group;
+    if (half) hipLaunchKernelGGL(gemm_items_kernel<true>, dim3(per_xcd * 8), dim3(64), 0, st, tbl);
+    else hipLaunchKernelGGL(gemm_items_kernel<false>, dim3(per_xcd * 8), dim3(64), 0, st, tbl);
+    if (red > 0) hipLaunchKernelGGL(gemm_reduce_kernel, dim3(red), dim3(256), 0, st, tbl);
+    return hipGetLastError();
+}
+
+void im2col_items_set_steps(int steps) { if (steps > 0) g_item_steps = steps; }
 
 }  // namespace nnv
