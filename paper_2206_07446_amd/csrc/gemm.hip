@@ -25,7 +25,7 @@
 // one chunk ahead of the MFMAs (register ping-pong).  KS wavefronts of a workgroup share one
 // output tile and split the channel blocks; partial sums meet in LDS, fixed order.
 #include <algorithm>
-#include <cstdlib>
+#include <climits>
 #include "nnv_internal.h"
 #include "buf.h"
 
@@ -122,6 +122,17 @@ __device__ __forceinline__ void gemm_accumulate(const GemmParams &g, const int m
         const bool ok = pvalid[t] && (unsigned)(ih0[t] + r) < (unsigned)g.H && (unsigned)(iw0[t] + s) < (unsigned)g.W;
         return ok ? (uint32_t)(xbase[t] + r * tap_h + s * tap_w) : kOobOffset;
     };
+    // row mode: the column part of the tap offsets (origin + s, or out of range) does not change
+    // from chunk to chunk; a chunk's offsets are that plus its row, or out of range for a row in
+    // the padding
+    uint32_t colv[TN][ROW ? NVOFF : 1];
+    if (ROW) {
+#pragma unroll
+        for (int t = 0; t < TN; ++t)
+#pragma unroll
+            for (int sx = 0; sx < NVOFF; ++sx)
+                colv[t][sx] = (pvalid[t] && (unsigned)(iw0[t] + sx) < (unsigned)g.W) ? (uint32_t)(xbase[t] + sx * tap_w) : kOobOffset;
+    }
     // byte offset per tap of the current chunk; loop-invariant for MODE 1 and 3
     uint32_t voff[TN][NVOFF];
     if (MODE == 1) {
@@ -196,9 +207,12 @@ __device__ __forceinline__ void gemm_accumulate(const GemmParams &g, const int m
             else { cb = u / g.R; r0 = u - cb * g.R; }
             if (ROW) {
 #pragma unroll
-                for (int t = 0; t < TN; ++t)
+                for (int t = 0; t < TN; ++t) {
+                    const bool rok = (unsigned)(ih0[t] + r0) < (unsigned)g.H;
+                    const uint32_t radd = (uint32_t)(r0 * tap_h);
 #pragma unroll
-                    for (int s = 0; s < NVOFF; ++s) voff[t][s] = tap_off(t, r0, s);
+                    for (int s = 0; s < NVOFF; ++s) voff[t][s] = rok ? colv[t][s] + radd : kOobOffset;   // 2^31 + anything below 2^31 stays out of range
+                }
             } else if (MODE == 0) {
 #pragma unroll
                 for (int t = 0; t < TN; ++t) voff[t][0] = tap_off(t, r0, s0);
@@ -249,37 +263,270 @@ __device__ __forceinline__ void gemm_accumulate(const GemmParams &g, const int m
     if (u_begin < u_end) {
 #pragma unroll
         for (int i = 0; i < NBUF - 1; ++i) load_chunk(i, u_begin + i * UNITS);
+        __builtin_amdgcn_s_setprio(0);
+        // The scheduling barriers keep the loads of a later chunk in front of the MFMAs of the
+        // current one: left alone, the compiler sinks them behind the MFMAs to save registers,
+        // which puts every load's latency in front of the instruction that needs it.
+        __builtin_amdgcn_sched_barrier(0);
         for (int u = u_begin; u < u_end; u += NBUF * UNITS) {
 #pragma unroll
             for (int i = 0; i < NBUF; ++i) {
                 load_chunk((i + NBUF - 1) % NBUF, u + (i + NBUF - 1) * UNITS);
+                __builtin_amdgcn_sched_barrier(0);
                 if (i == 0 || u + i * UNITS < u_end) compute(i, u + i * UNITS);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
 
 }
 
-// One finished output: row 4 * slot + j of panel mb0 + m, pixel column t of the tile; bias, optional
-// clamp at zero, one rounding to the storage type.
-__device__ __forceinline__ void gemm_store(const GemmParams &g, const int img, const int pq, const bool valid,
-                                           const int mb0, const int m, const int j, const int slot, const float v) {
-    const int grp = mb0 / g.kg16, mbl = mb0 - grp * g.kg16;
-    const int kl = (mbl + m) * 16 + slot * 4 + j;         // row within the group
-    const int k = grp * g.Kg + kl;
-    if (kl < g.Kg && mbl + m < g.kg16 && valid) {
-        const size_t o = ((size_t)img * g.K + k) * (g.P * g.Q) + pq;
-        float r = v + (g.bias ? g.bias[k] : 0.f);
-        if (g.relu) r = fmaxf(r, 0.f);
-        if (g.half_out) static_cast<__half *>(g.y)[o] = __float2half_rn(r);
-        else static_cast<float *>(g.y)[o] = r;
+// ---- the k-loops of the work-item kernel for float32 3x3 and 1x1 filters, TM = 1, 2 or 4 panels per tile.
+// What bounds the 32 x 32 tile on a busy chip is the vector memory path of a CU (address unit and
+// data return are 60-70 % busy, measured), not the matrix pipe: every MFMA needs one operand
+// fragment through it.  A 64 x 32 tile needs 0.75.  To keep the register count where four
+// wavefronts still fit on a SIMD, a chunk is one filter row (3 k-steps) and three chunks form the
+// ring, so loads run two chunks (48 MFMAs) ahead; the buffer of a chunk is the filter row it
+// belongs to, which makes every index in the unrolled loop a constant.
+template <int TN>
+__device__ __forceinline__ void gemm_pixels(const GemmParams &g, const int mb0, const int nb0, const int lane,
+                                            PixState<TN> &px, int (&ih0)[TN], int (&iw0)[TN], int (&xbase)[TN]) {
+    const int col = lane & 15, slot = lane >> 4;
+    const int cbase = (mb0 / g.kg16) * g.Cg;              // first input channel of the tile's group
+    const int PQ = g.P * g.Q;
+#pragma unroll
+    for (int t = 0; t < TN; ++t) {
+        const int n = (nb0 + t) * 16 + col;
+        px.valid[t] = n < g.npix;
+        const int nn = px.valid[t] ? n : 0;
+        const int img = g.N == 1 ? 0 : nn / PQ;
+        const int pq = nn - img * PQ;
+        const int p = pq / g.Q, q = pq - p * g.Q;
+        px.img[t] = img; px.pq[t] = pq;
+        ih0[t] = p * g.sh - g.ph;
+        iw0[t] = q * g.sw - g.pw;
+        xbase[t] = (((img * g.C + cbase + slot) * g.H + ih0[t]) * g.W + iw0[t]) * 4;
     }
+}
+
+template <int TM, int TN>
+__device__ __forceinline__ void gemm_accumulate_3x3(const GemmParams &g, const int mb0, const int nb0, const int ks,
+                                                    const int nsplit, const int lane, floatx4 (&acc)[TM][TN],
+                                                    PixState<TN> &px) {
+    const int slot = lane >> 4;
+    int ih0[TN], iw0[TN], xbase[TN];
+    gemm_pixels<TN>(g, mb0, nb0, lane, px, ih0, iw0, xbase);
+    uint32_t voff[TN][9];
+    const int tap_h = g.W * 4;
+#pragma unroll
+    for (int t = 0; t < TN; ++t)
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            const bool rok = px.valid[t] && (unsigned)(ih0[t] + r) < (unsigned)g.H;
+#pragma unroll
+            for (int sx = 0; sx < 3; ++sx)
+                voff[t][r * 3 + sx] = (rok && (unsigned)(iw0[t] + sx) < (unsigned)g.W) ? (uint32_t)(xbase[t] + r * tap_h + sx * 4) : kOobOffset;
+        }
+    const int cblocks = g.cblocks;
+    const int per = (cblocks + nsplit - 1) / nsplit;
+    const int cb_begin = min(cblocks, ks * per), cb_end = min(cblocks, cb_begin + per);
+    const __amdgpu_buffer_rsrc_t xres = make_rsrc(g.x, g.x_bytes);
+    const __amdgpu_buffer_rsrc_t wres = make_rsrc(g.wp, g.w_bytes);
+    uint32_t a_voff[TM], a_base[TM];      // per-lane offset (out of range for panels beyond K), scalar fragment index of the panel
+#pragma unroll
+    for (int m = 0; m < TM; ++m) {
+        const bool ok = mb0 + m < g.K16;
+        a_voff[m] = ok ? (uint32_t)lane * 4u : kOobOffset;
+        a_base[m] = ok ? (uint32_t)(mb0 + m) * (uint32_t)cblocks * 9u : 0u;
+    }
+    float a[3][3][TM], b[3][3][TN];
+    auto load_row = [&](const int r, int cb) __attribute__((always_inline)) {
+        cb = max(min(cb, cb_end - 1), 0);          // past the range: re-read valid data that is not used
+        const bool partial = g.c_rem != 0 && cb == cblocks - 1;     // uniform
+#pragma unroll
+        for (int m = 0; m < TM; ++m) {
+            const uint32_t soff = (a_base[m] + (uint32_t)cb * 9u + (uint32_t)r * 3u) * 256u;
+#pragma unroll
+            for (int sx = 0; sx < 3; ++sx) a[r][sx][m] = buf_load<float>(wres, a_voff[m] + sx * 256u, soff);
+        }
+        const uint32_t b_soff = (uint32_t)cb * g.cb_stride;
+#pragma unroll
+        for (int sx = 0; sx < 3; ++sx)
+#pragma unroll
+            for (int t = 0; t < TN; ++t) {
+                uint32_t vo = voff[t][r * 3 + sx];
+                if (partial) vo = slot < g.c_rem ? vo : kOobOffset;
+                b[r][sx][t] = buf_load<float>(xres, vo, b_soff);
+            }
+    };
+    auto compute_row = [&](const int r) __attribute__((always_inline)) {
+#pragma unroll
+        for (int sx = 0; sx < 3; ++sx)
+#pragma unroll
+            for (int m = 0; m < TM; ++m)
+#pragma unroll
+                for (int t = 0; t < TN; ++t)
+                    acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[r][sx][m], b[r][sx][t], acc[m][t], 0, 0, 0);
+    };
+#pragma unroll
+    for (int m = 0; m < TM; ++m)
+#pragma unroll
+        for (int t = 0; t < TN; ++t) acc[m][t] = floatx4{0.f, 0.f, 0.f, 0.f};
+    if (cb_begin < cb_end) {
+        load_row(0, cb_begin);
+        load_row(1, cb_begin);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_setprio(0);
+        for (int cb = cb_begin; cb < cb_end; ++cb) {
+            load_row(2, cb);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_row(0);
+            __builtin_amdgcn_sched_barrier(0);
+            load_row(0, cb + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_row(1);
+            __builtin_amdgcn_sched_barrier(0);
+            load_row(1, cb + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_row(2);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
+
+// 1x1 filters: a chunk is four channel blocks, three chunks form the ring.
+template <int TM, int TN>
+__device__ __forceinline__ void gemm_accumulate_1x1(const GemmParams &g, const int mb0, const int nb0, const int ks,
+                                                    const int nsplit, const int lane, floatx4 (&acc)[TM][TN],
+                                                    PixState<TN> &px) {
+    constexpr int CH = 4;
+    int ih0[TN], iw0[TN], xbase[TN];
+    gemm_pixels<TN>(g, mb0, nb0, lane, px, ih0, iw0, xbase);
+    uint32_t voff[TN];
+#pragma unroll
+    for (int t = 0; t < TN; ++t)
+        voff[t] = (px.valid[t] && (unsigned)ih0[t] < (unsigned)g.H && (unsigned)iw0[t] < (unsigned)g.W) ? (uint32_t)xbase[t] : kOobOffset;
+    const int cblocks = g.cblocks;
+    const int nchunks = (cblocks + CH - 1) / CH;
+    const int per = (nchunks + nsplit - 1) / nsplit;
+    const int q_begin = min(nchunks, ks * per), q_end = min(nchunks, q_begin + per);
+    const __amdgpu_buffer_rsrc_t xres = make_rsrc(g.x, g.x_bytes);
+    const __amdgpu_buffer_rsrc_t wres = make_rsrc(g.wp, g.w_bytes);
+    uint32_t a_voff[TM], a_base[TM];
+#pragma unroll
+    for (int m = 0; m < TM; ++m) {
+        const bool ok = mb0 + m < g.K16;
+        a_voff[m] = ok ? (uint32_t)lane * 4u : kOobOffset;
+        a_base[m] = ok ? (uint32_t)(mb0 + m) * (uint32_t)cblocks : 0u;
+    }
+    // Chunks past the range and blocks past C are read through an empty resource (every load
+    // returns 0), so the MFMAs need no condition and the unrolled loop keeps one accumulator set.
+    const __amdgpu_buffer_rsrc_t zres = make_rsrc(g.x, 0u);
+    float a[3][CH][TM], b[3][CH][TN];
+    auto load_chunk = [&](const int buf, const int q) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            const int cbj = q * CH + j;
+            const bool ok = q < q_end && cbj < cblocks;          // uniform
+            const int cb = ok ? cbj : 0;
+            const __amdgpu_buffer_rsrc_t wsel = ok ? wres : zres, xsel = ok ? xres : zres;
+#pragma unroll
+            for (int m = 0; m < TM; ++m) a[buf][j][m] = buf_load<float>(wsel, a_voff[m], (a_base[m] + (uint32_t)cb) * 256u);
+#pragma unroll
+            for (int t = 0; t < TN; ++t) b[buf][j][t] = buf_load<float>(xsel, voff[t], (uint32_t)cb * g.cb_stride);
+        }
+    };
+    auto compute = [&](const int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < CH; ++j)
+#pragma unroll
+            for (int m = 0; m < TM; ++m)
+#pragma unroll
+                for (int t = 0; t < TN; ++t)
+                    acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[buf][j][m], b[buf][j][t], acc[m][t], 0, 0, 0);
+    };
+#pragma unroll
+    for (int m = 0; m < TM; ++m)
+#pragma unroll
+        for (int t = 0; t < TN; ++t) acc[m][t] = floatx4{0.f, 0.f, 0.f, 0.f};
+    if (q_begin < q_end) {
+        load_chunk(0, q_begin);
+        load_chunk(1, q_begin + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_setprio(0);
+        for (int q = q_begin; q < q_end; q += 3) {
+            load_chunk(2, q + 2);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(0);
+            __builtin_amdgcn_sched_barrier(0);
+            load_chunk(0, q + 3);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(1);
+            __builtin_amdgcn_sched_barrier(0);
+            load_chunk(1, q + 4);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(2);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
+
+// Row state of a lane's outputs: for each of its 4 * TM rows the element offset of the row in y
+// (k * P * Q, or out of range) and the bias value.
+template <int TM> struct RowState {
+    uint32_t off[TM][4];      // byte offset of (image 0, row k, pixel 0), kOobOffset for rows beyond K
+    float bias[TM][4];
+};
+
+template <int TM>
+__device__ __forceinline__ void gemm_rows(const GemmParams &g, const int mb0, const int slot, RowState<TM> &rs) {
+    const int PQ = g.P * g.Q, Kg = g.Kg, kg16 = g.kg16;
+    const uint32_t esz = g.half_out ? 2u : 4u;
+    const float *bias = g.bias;
+    const int grp = mb0 / kg16, mbl = mb0 - grp * kg16;
+    const __amdgpu_buffer_rsrc_t bres = make_rsrc(bias, bias ? (uint32_t)g.K * 4u : 0u);   // no bias: every load reads 0
+#pragma unroll
+    for (int m = 0; m < TM; ++m)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int kl = (mbl + m) * 16 + slot * 4 + j;         // row within the group
+            const int k = grp * Kg + kl;
+            const bool ok = kl < Kg && mbl + m < kg16;
+            rs.off[m][j] = ok ? (uint32_t)(k * PQ) * esz : kOobOffset;
+            rs.bias[m][j] = buf_load<float>(bres, ok ? (uint32_t)k * 4u : kOobOffset, 0u);
+        }
+}
+
+// One finished output: bias, optional clamp at zero, one rounding to the storage type; the store is
+// range-checked, so rows beyond K and pixels beyond the layer (offset out of range) write nothing.
+__device__ __forceinline__ void gemm_store(const __amdgpu_buffer_rsrc_t yres, const bool relu, const bool half,
+                                           const uint32_t off, const float bias, const float v) {
+    float r = v + bias;
+    if (relu) r = fmaxf(r, 0.f);
+    if (half) {
+        const _Float16 h = (_Float16)r;      // round to nearest even
+        __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, h), yres, off, 0u, 0);
+    } else {
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, r), yres, off, 0u, 0);
+    }
+}
+
+// Byte offset of pixel (img, pq) within its row of y, or out of range.
+__device__ __forceinline__ uint32_t gemm_pixel_offset(const GemmParams &g, const int img, const int pq, const bool valid) {
+    const uint32_t esz = g.half_out ? 2u : 4u;
+    return valid ? ((uint32_t)img * (uint32_t)(g.K * g.P * g.Q) + (uint32_t)pq) * esz : kOobOffset;
+}
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t gemm_y_rsrc(const GemmParams &g) {
+    return make_rsrc(g.y, (uint32_t)g.N * (uint32_t)(g.K * g.P * g.Q) * (g.half_out ? 2u : 4u));
 }
 
 // One layer per launch: a workgroup of KS wavefronts owns one output tile, the wavefronts split
 // the channel blocks and add their partial sums through LDS in fixed order.
+// (the 32 x 32 tile is launched as one wavefront per workgroup only, and needs more than the 128
+// registers a 16-wavefront workgroup leaves each lane)
 template <bool HALF, int TM, int TN, int MODE, int NBUF>
-__global__ __launch_bounds__(1024) void im2col_gemm_kernel(const GemmParams g) {
+__global__ __launch_bounds__(TM * TN == 4 ? 64 : 1024) void im2col_gemm_kernel(const GemmParams g) {
     extern __shared__ __align__(16) float red[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar
@@ -311,6 +558,13 @@ __global__ __launch_bounds__(1024) void im2col_gemm_kernel(const GemmParams g) {
     }
     // epilogue: lane holds rows 4*slot + j, column col of each block; wavefront ks finishes the
     // accumulator registers reg = ks, ks + KS, ...
+    RowState<TM> rs;
+    gemm_rows<TM>(g, mb0, slot, rs);
+    const __amdgpu_buffer_rsrc_t yres = gemm_y_rsrc(g);
+    const bool relu = g.relu, half_out = g.half_out;
+    uint32_t pixoff[TN];
+#pragma unroll
+    for (int t = 0; t < TN; ++t) pixoff[t] = gemm_pixel_offset(g, px.img[t], px.pq[t], px.valid[t]);
 #pragma unroll
     for (int m = 0; m < TM; ++m) {
 #pragma unroll
@@ -324,7 +578,9 @@ __global__ __launch_bounds__(1024) void im2col_gemm_kernel(const GemmParams g) {
                     v = 0.f;
                     for (int z = 0; z < KS; ++z) v += red[((nt * KS + z) * NREG + reg) * 64 + lane];
                 }
-                gemm_store(g, px.img[t], px.pq[t], px.valid[t], mb0, m, j, slot, v);
+                // either offset may be the out-of-range constant 2^31; both at once would wrap to a small sum
+                const uint32_t off = rs.off[m][j] == kOobOffset ? kOobOffset : rs.off[m][j] + pixoff[t];
+                gemm_store(yres, relu, half_out, off, rs.bias[m][j], v);
             }
         }
     }
@@ -342,36 +598,51 @@ __global__ __launch_bounds__(1024) void im2col_gemm_kernel(const GemmParams g) {
 struct GemmItemLayer {
     GemmParams g;
     float *part;        // partial tiles of a split layer (workspace): [tile][split][reg][lane]
-    int item0;          // first item of the layer in the launch
     int ntn;            // tiles along the pixels
     int nsplit;         // ranges of the reduction (1: the item stores y itself)
     int mode, tm;       // chunking mode (ModeT); 16-row panels per tile (1 or 2)
-    int red0;           // first workgroup of the layer in the reduction launch
 };
 struct GemmItemTable {
     GemmItemLayer layer[kMaxGemmLayers];
+    // first item / first reduction workgroup of each layer, INT_MAX beyond the last layer: a
+    // workgroup finds its layer by counting the entries it has reached (one load of the array,
+    // no chain of dependent loads)
+    int item0[kMaxGemmLayers], red0[kMaxGemmLayers];
     int nlayers, nitems;
     int group;          // consecutive items handed to one XCD
     int nred;           // workgroups of the reduction launch
 };
 static_assert(sizeof(GemmItemTable) <= 4096, "the table is passed by value as the kernel argument");
 
-template <bool HALF, int TM, int MODE>
+template <bool HALF, int TM, int MODE, int NBUF = 2>
 __device__ __forceinline__ void gemm_item(const GemmItemLayer &L, const int local, const int lane) {
     constexpr int TN = 2;
     const int nb = local % L.ntn, rest = local / L.ntn;
     const int ks = rest % L.nsplit, mt = rest / L.nsplit;       // order: tile row, range, tile column (fastest)
     floatx4 acc[TM][TN];
     PixState<TN> px;
-    gemm_accumulate<HALF, TM, TN, MODE, 2>(L.g, mt * TM, nb * TN, ks, L.nsplit, lane, acc, px);
+    if constexpr (!HALF && MODE == 3) gemm_accumulate_3x3<TM, TN>(L.g, mt * TM, nb * TN, ks, L.nsplit, lane, acc, px);
+    else if constexpr (!HALF && MODE == 1) gemm_accumulate_1x1<TM, TN>(L.g, mt * TM, nb * TN, ks, L.nsplit, lane, acc, px);
+    else gemm_accumulate<HALF, TM, TN, MODE, NBUF>(L.g, mt * TM, nb * TN, ks, L.nsplit, lane, acc, px);
+    __builtin_amdgcn_s_setprio(3);
     if (L.nsplit == 1) {
+        RowState<TM> rs;
+        gemm_rows<TM>(L.g, mt * TM, lane >> 4, rs);
+        const __amdgpu_buffer_rsrc_t yres = gemm_y_rsrc(L.g);
+        const bool relu = L.g.relu, half_out = L.g.half_out;
+        uint32_t pixoff[TN];
+#pragma unroll
+        for (int t = 0; t < TN; ++t) pixoff[t] = gemm_pixel_offset(L.g, px.img[t], px.pq[t], px.valid[t]);
+        __builtin_amdgcn_sched_barrier(0);      // parameters and bias values first, then nothing but stores
 #pragma unroll
         for (int m = 0; m < TM; ++m)
 #pragma unroll
             for (int t = 0; t < TN; ++t)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    gemm_store(L.g, px.img[t], px.pq[t], px.valid[t], mt * TM, m, j, lane >> 4, acc[m][t][j]);
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t off = rs.off[m][j] == kOobOffset ? kOobOffset : rs.off[m][j] + pixoff[t];
+                    gemm_store(yres, relu, half_out, off, rs.bias[m][j], acc[m][t][j]);
+                }
     } else {
         constexpr int NREG = TM * TN * 4;
         float *o = L.part + ((size_t)(mt * L.ntn + nb) * L.nsplit + ks) * (NREG * 64) + lane;
@@ -384,60 +655,128 @@ __device__ __forceinline__ void gemm_item(const GemmItemLayer &L, const int loca
     }
 }
 
-template <bool HALF>
-__global__ __launch_bounds__(64) void gemm_items_kernel(const GemmItemTable tbl) {
+// The table is the kernel argument; the kernel reads it through the kernel-argument segment
+// pointer (constant address space, scalar loads at computed offsets).  Indexing the by-value
+// parameter itself with a run-time layer number makes the compiler copy all 4 KB of it to
+// scratch memory first, in every wavefront.
+typedef const __attribute__((address_space(4))) GemmItemTable *GemmItemTablePtr;
+
+__device__ __forceinline__ void load_item_layer(GemmItemLayer &dst, const GemmItemTablePtr tbl, const int li) {
+    static_assert(sizeof(GemmItemLayer) % 4 == 0, "copied word by word");
+    const __attribute__((address_space(4))) uint32_t *src = (const __attribute__((address_space(4))) uint32_t *)&tbl->layer[li];
+    uint32_t *d = reinterpret_cast<uint32_t *>(&dst);
+#pragma unroll
+    for (int i = 0; i < (int)(sizeof(GemmItemLayer) / 4); ++i) d[i] = src[i];
+}
+
+template <bool HALF, int NBUF = 2>
+__global__ __launch_bounds__(64, 3) void gemm_items_kernel(const GemmItemTable tbl_arg) {
+    const GemmItemTablePtr tbl = (GemmItemTablePtr)__builtin_amdgcn_kernarg_segment_ptr();
     // Workgroup i runs on XCD i % 8.  Groups of `group` consecutive items (neighbouring tiles of
     // one layer: they share a weight panel) are dealt to the XCDs in turn, so every XCD sees the
     // same mix of layers in the same order and a panel is fetched into one L2.
-    const int G = tbl.group;
+    // An item's addressing competes for issue slots with the MFMA loops of the other wavefronts on
+    // its SIMD, which always have an instruction ready: without a higher priority it is served
+    // last and takes several microseconds.  The k-loop drops back to the default priority.
+    __builtin_amdgcn_s_setprio(3);
+    const int G = tbl->group;
     const int i = blockIdx.x, xcd = i & 7, j = i >> 3;
     const int item = ((j / G) * 8 + xcd) * G + j % G;
-    if (item >= tbl.nitems) return;
-    int li = 0;
-    while (li + 1 < tbl.nlayers && item >= tbl.layer[li + 1].item0) ++li;
-    const GemmItemLayer &L = tbl.layer[li];
-    const int local = item - L.item0;
+    if (item >= tbl->nitems) return;
+    int li = 0, first = 0;
+#pragma unroll
+    for (int l = 1; l < kMaxGemmLayers; ++l) {
+        const int i0 = tbl->item0[l];
+        if (item >= i0) { ++li; first = i0; }
+    }
+    GemmItemLayer L;
+    load_item_layer(L, tbl, li);                     // one batch of scalar loads
+    const int local = item - first;
     const int lane = threadIdx.x;
-    if (L.tm == 2) {
+    if (L.tm == 4) {
+        if constexpr (!HALF) {
+            if (L.mode == 3) gemm_item<false, 4, 3, NBUF>(L, local, lane);
+            else gemm_item<false, 4, 1, NBUF>(L, local, lane);
+        }
+    } else if (L.tm == 2) {
         switch (L.mode) {
-            case 1: gemm_item<HALF, 2, 1>(L, local, lane); break;
-            case 3: gemm_item<HALF, 2, 3>(L, local, lane); break;
-            case 5: if constexpr (!HALF) gemm_item<HALF, 2, 5>(L, local, lane); break;
-            case 7: if constexpr (!HALF) gemm_item<HALF, 2, 7>(L, local, lane); break;
-            default: gemm_item<HALF, 2, 0>(L, local, lane); break;
+            case 1: gemm_item<HALF, 2, 1, NBUF>(L, local, lane); break;
+            case 3: gemm_item<HALF, 2, 3, NBUF>(L, local, lane); break;
+            case 5: if constexpr (!HALF) gemm_item<HALF, 2, 5, NBUF>(L, local, lane); break;
+            case 7: if constexpr (!HALF) gemm_item<HALF, 2, 7, NBUF>(L, local, lane); break;
+            default: gemm_item<HALF, 2, 0, NBUF>(L, local, lane); break;
         }
     } else {
         switch (L.mode) {
-            case 1: gemm_item<HALF, 1, 1>(L, local, lane); break;
-            case 3: gemm_item<HALF, 1, 3>(L, local, lane); break;
-            case 5: if constexpr (!HALF) gemm_item<HALF, 1, 5>(L, local, lane); break;
-            case 7: if constexpr (!HALF) gemm_item<HALF, 1, 7>(L, local, lane); break;
-            default: gemm_item<HALF, 1, 0>(L, local, lane); break;
+            case 1: gemm_item<HALF, 1, 1, NBUF>(L, local, lane); break;
+            case 3: gemm_item<HALF, 1, 3, NBUF>(L, local, lane); break;
+            case 5: if constexpr (!HALF) gemm_item<HALF, 1, 5, NBUF>(L, local, lane); break;
+            case 7: if constexpr (!HALF) gemm_item<HALF, 1, 7, NBUF>(L, local, lane); break;
+            default: gemm_item<HALF, 1, 0, NBUF>(L, local, lane); break;
         }
     }
 }
 
+__device__ static inline int ceil_div_dev(int a, int b) { return (a + b - 1) / b; }
+
 // Adds the nsplit partial tiles of every split layer in the order of the ranges and stores y.
-__global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmItemTable tbl) {
+// A thread owns four consecutive lanes of one accumulator register (16-byte loads); the loads of
+// four ranges are in flight at once, the additions keep the order of the ranges.
+__global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmItemTable tbl_arg) {
+    const GemmItemTablePtr tbl = (GemmItemTablePtr)__builtin_amdgcn_kernarg_segment_ptr();
     const int b = blockIdx.x;
-    int li = 0;
-    while (li + 1 < tbl.nlayers && b >= tbl.layer[li + 1].red0) ++li;
-    const GemmItemLayer &L = tbl.layer[li];
+    int li = 0, first = 0;
+#pragma unroll
+    for (int l = 1; l < kMaxGemmLayers; ++l) {      // the last layer that starts at or before b
+        const int r0 = tbl->red0[l];
+        if (b >= r0) { ++li; first = r0; }
+    }
+    GemmItemLayer L;
+    load_item_layer(L, tbl, li);
     const int nreg = L.tm * 8;                                   // accumulator registers per lane: TM x 2 blocks x 4
-    const int e = (b - L.red0) * 256 + threadIdx.x;              // over [tile][reg][lane]
-    const int tile = e / (nreg * 64), rl = e - tile * (nreg * 64);
-    const int reg = rl >> 6, lane = rl & 63;
-    const float *src = L.part + (size_t)tile * L.nsplit * (nreg * 64) + rl;
-    float v = 0.f;
-    for (int z = 0; z < L.nsplit; ++z) v += src[(size_t)z * (nreg * 64)];
+    const int per_tile = nreg * 64;
+    const int e = ((b - first) * 256 + threadIdx.x) * 4;          // over [tile][reg][lane]
+    const int tile = e / per_tile, rl = e - tile * per_tile;
+    const int reg = rl >> 6, lane0 = rl & 63;
+    if (tile >= ceil_div_dev(L.g.K16, L.tm) * L.ntn) return;     // second half of the last workgroup of an odd tile count
+    const float4 *src = reinterpret_cast<const float4 *>(L.part + (size_t)tile * L.nsplit * per_tile + rl);
+    const size_t zs = (size_t)per_tile / 4;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    int z = 0;
+    for (; z + 4 <= L.nsplit; z += 4) {
+        const float4 p0 = src[(z + 0) * zs], p1 = src[(z + 1) * zs], p2 = src[(z + 2) * zs], p3 = src[(z + 3) * zs];
+        v.x += p0.x; v.y += p0.y; v.z += p0.z; v.w += p0.w;
+        v.x += p1.x; v.y += p1.y; v.z += p1.z; v.w += p1.w;
+        v.x += p2.x; v.y += p2.y; v.z += p2.z; v.w += p2.w;
+        v.x += p3.x; v.y += p3.y; v.z += p3.z; v.w += p3.w;
+    }
+    for (; z < L.nsplit; ++z) {
+        const float4 p = src[z * zs];
+        v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+    }
+    // the four values are rows (lane0 / 16) * 4 + jj of panel m, pixels (lane0 % 16) .. + 3 of block t
     const int mt = tile / L.ntn, nb = tile - mt * L.ntn;
     const int m = reg >> 3, t = (reg >> 2) & 1, jj = reg & 3;
-    const int n = (nb * 2 + t) * 16 + (lane & 15);
-    const bool valid = n < L.g.npix;
-    const int nn = valid ? n : 0;
-    const int PQ = L.g.P * L.g.Q;
-    const int img = nn / PQ;
-    gemm_store(L.g, img, nn - img * PQ, valid, mt * L.tm, m, jj, lane >> 4, v);
+    const int PQ = L.g.P * L.g.Q, Kg = L.g.Kg, kg16 = L.g.kg16, npix = L.g.npix;
+    const bool relu = L.g.relu, half_out = L.g.half_out;
+    const float *bias = L.g.bias;
+    const __amdgpu_buffer_rsrc_t yres = gemm_y_rsrc(L.g);
+    const int mb0 = mt * L.tm, grp = mb0 / kg16, mbl = mb0 - grp * kg16;
+    const int kl = (mbl + m) * 16 + (lane0 >> 4) * 4 + jj;
+    const int k = grp * Kg + kl;
+    const bool rok = kl < Kg && mbl + m < kg16;
+    const float bv = (bias && rok) ? bias[k] : 0.f;
+    const uint32_t esz = half_out ? 2u : 4u;
+    const float vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int n = (nb * 2 + t) * 16 + (lane0 & 15) + i;
+        const bool valid = rok && n < npix;
+        const int nn = valid ? n : 0;
+        const int img = nn / PQ;
+        const uint32_t off = valid ? ((uint32_t)(img * L.g.K + k) * (uint32_t)PQ + (uint32_t)(nn - img * PQ)) * esz : kOobOffset;
+        gemm_store(yres, relu, half_out, off, bv, vv[i]);
+    }
 }
 
 // half NCHW -> half [N][H][W][cpad] (channels last, zero padded to a multiple of 32).
@@ -596,6 +935,7 @@ hipError_t launch_im2col(const Geo &g, const void *x, const void *w, const float
 // ---- many layers in one launch: item plan of one layer
 struct ItemPlan {
     int mode, tm, nmt, ntn, nsplit;
+    int steps;              // k-steps of the whole reduction
     size_t part_bytes;      // partial tiles (0 if the layer is not split)
     size_t xt_bytes;        // channel-last float16 copy of x (0 if not needed)
 };
@@ -603,9 +943,9 @@ struct ItemPlan {
 // k-steps (one MFMA per 16 x 16 block each) a work item aims at: long enough to amortise an
 // item's addressing, first loads and store, short enough that the chip's last round of items
 // stays small against the whole launch.
-static int g_item_steps = getenv("NNV_ITEM_STEPS") ? atoi(getenv("NNV_ITEM_STEPS")) : 96;   // TUNING ONLY
+constexpr int kItemSteps = 144;
 
-static ItemPlan plan_items(const Geo &g) {
+static ItemPlan plan_items(const Geo &g, const int item_steps) {
     ItemPlan ip{};
     const GemmPlan pl = plan_im2col(g);
     const bool half = g.dtype == NNV_F16;
@@ -616,15 +956,24 @@ static ItemPlan plan_items(const Geo &g) {
     // two panels per tile unless that leaves a third or more of the tile rows empty
     // (a tile's panels must belong to one group)
     ip.tm = (kg16 % 2 == 0 || (g.groups == 1 && kg16 >= 5)) ? 2 : 1;
+    // float32 3x3 and 1x1 layers with at least 64 output channels: four panels per tile
+    if (!half && g.groups == 1 && (pl.mode == 3 || pl.mode == 1) && (kg16 % 4 == 0 || kg16 >= 12)) ip.tm = 4;
     ip.nmt = ceil_div(K16, ip.tm);
     ip.ntn = ceil_div(ceil_div(g.n * g.p * g.q, 16), 2);
     const int cblocks = half ? ceil_div(g.cg, 32) : ceil_div(g.cg, 4);
     const bool row = pl.mode == 5 || pl.mode == 7 || (pl.mode == 3 && half);
-    const int nunits = pl.mode == 0 ? cblocks * g.r * g.s : row ? cblocks * g.r : cblocks;
-    const int unit_steps = pl.mode == 0 ? 1 : row ? pl.mode : g.r * g.s;
-    const int chunk_units = pl.mode == 1 ? (half ? 2 : 8) : 1;
+    int nunits = pl.mode == 0 ? cblocks * g.r * g.s : row ? cblocks * g.r : cblocks;
+    int unit_steps = pl.mode == 0 ? 1 : row ? pl.mode : g.r * g.s;
+    int chunk_units = pl.mode == 1 ? (half ? 2 : 8) : 1;
+    int target = item_steps;
+    if (ip.tm == 4) {
+        // a wide item does twice the MFMAs per k-step: somewhat fewer steps per item
+        target = std::max(9, item_steps * 3 / 4);
+    }
+    if (!half && pl.mode == 1) { nunits = ceil_div(cblocks, 4); unit_steps = 4; chunk_units = 1; }   // float32 1x1: the kernel splits whole chunks of 4 blocks
     const long steps = (long)nunits * unit_steps;
-    long nsplit = (steps + g_item_steps / 2) / g_item_steps;
+    ip.steps = (int)steps;
+    long nsplit = (steps + target / 2) / target;
     const long most = std::max(1, nunits / chunk_units);          // every range holds at least one chunk
     nsplit = std::max(1L, std::min(nsplit, most));
     // ranges are ceil(nunits / nsplit) units long: drop ranges that would come out empty
@@ -635,7 +984,7 @@ static ItemPlan plan_items(const Geo &g) {
 }
 
 size_t im2col_items_workspace_bytes(const Geo &g) {
-    const ItemPlan ip = plan_items(g);
+    const ItemPlan ip = plan_items(g, kItemSteps);
     return align_up(ip.part_bytes, 256) + align_up(ip.xt_bytes, 256);
 }
 
@@ -647,13 +996,24 @@ hipError_t launch_im2col_items(int n, const Geo *geos, const void *const *x, con
     if (n <= 0) return hipSuccess;
     if (n > kMaxGemmLayers) return hipErrorInvalidValue;
     const bool half = geos[0].dtype == NNV_F16;
+    // Order: layers with the longest items first, so that the chip's last round of items is made
+    // of the short ones.
+    ItemPlan plans[kMaxGemmLayers];
+    int order[kMaxGemmLayers];
+    for (int i = 0; i < n; ++i) {
+        if ((geos[i].dtype == NNV_F16) != half) return hipErrorInvalidValue;
+        plans[i] = plan_items(geos[i], kItemSteps);
+        order[i] = i;
+    }
+    auto item_len = [&](int i) { return ceil_div(plans[i].steps, plans[i].nsplit) * plans[i].tm; };
+    std::stable_sort(order, order + n, [&](int a, int b) { return item_len(a) > item_len(b); });
     GemmItemTable tbl{};
     int items = 0, red = 0;
-    for (int i = 0; i < n; ++i) {
+    for (int o = 0; o < n; ++o) {
+        const int i = order[o];
         const Geo &g = geos[i];
-        if ((g.dtype == NNV_F16) != half) return hipErrorInvalidValue;
-        const ItemPlan ip = plan_items(g);
-        GemmItemLayer &L = tbl.layer[i];
+        const ItemPlan &ip = plans[i];
+        GemmItemLayer &L = tbl.layer[o];
         L.g = gemm_params(g, ip.mode, x[i], w[i], bias ? bias[i] : nullptr, y[i]);
         char *region = static_cast<char *>(ws[i]);
         if (ip.xt_bytes) {
@@ -662,18 +1022,19 @@ hipError_t launch_im2col_items(int n, const Geo *geos, const void *const *x, con
             L.g.x = xt;
         }
         L.part = ip.nsplit > 1 ? reinterpret_cast<float *>(region) : nullptr;
-        L.item0 = items;
+        tbl.item0[o] = items;
+        tbl.red0[o] = red;
         L.ntn = ip.ntn;
         L.nsplit = ip.nsplit;
         L.mode = ip.mode;
         L.tm = ip.tm;
-        L.red0 = red;
         items += ip.nmt * ip.ntn * ip.nsplit;
-        if (ip.nsplit > 1) red += ip.nmt * ip.ntn * (ip.tm * 8) / 4;
+        if (ip.nsplit > 1) red += ceil_div(ip.nmt * ip.ntn * (ip.tm * 8), 16);     // 1024 values per workgroup
     }
+    for (int i = n; i < kMaxGemmLayers; ++i) tbl.item0[i] = tbl.red0[i] = INT_MAX;
     tbl.nlayers = n;
     tbl.nitems = items;
-    tbl.group = getenv("NNV_ITEM_GROUP") ? atoi(getenv("NNV_ITEM_GROUP")) : 8;   // TUNING ONLY
+    tbl.group = 8;
     tbl.nred = red;
     const int per_xcd = ceil_div(ceil_div(items, tbl.group), 8) * tbl.group;
     if (half) hipLaunchKernelGGL(gemm_items_kernel<true>, dim3(per_xcd * 8), dim3(64), 0, st, tbl);
@@ -681,7 +1042,5 @@ hipError_t launch_im2col_items(int n, const Geo *geos, const void *const *x, con
     if (red > 0) hipLaunchKernelGGL(gemm_reduce_kernel, dim3(red), dim3(256), 0, st, tbl);
     return hipGetLastError();
 }
-
-void im2col_items_set_steps(int steps) { if (steps > 0) g_item_steps = steps; }
 
 }  // namespace nnv

@@ -71,7 +71,7 @@ hipError_t launch_im2col(const Geo &g, const void *x, const void *w, const float
 // Many independent IM2COL_GEMM layers (one storage type, at most kMaxGemmLayers) in one launch of
 // single-wavefront work items, plus one reduction launch if a layer's channels are split; ws[i] is
 // layer i's own region of im2col_items_workspace_bytes bytes.
-constexpr int kMaxGemmLayers = 21;
+constexpr int kMaxGemmLayers = 20;
 size_t im2col_items_workspace_bytes(const Geo &g);
 hipError_t launch_im2col_items(int n, const Geo *geos, const void *const *x, const void *const *w,
                                const float *const *bias, void *const *y, void *const *ws, hipStream_t st);
