@@ -160,7 +160,9 @@ int nnv_conv_forward_relu(const nnv_conv_desc *desc, nnv_kind kind, const void *
  * layer (Algorithm 1's input, Section 3.3, Table 2), and a batch-1 layer alone neither fills
  * the GPU nor outlasts its own launch: IM2COL_GEMM layers of one storage type share one
  * launch of single-wavefront work items (output tile x range of the reduction) and one
- * reduction launch; layers of other kinds are executed one after the other as by
+ * reduction launch; Winograd layers of one kind and storage type share three launches (all
+ * input transforms, all tile GEMMs, all output transforms), except those nnv_conv_forward
+ * runs as one fused kernel; the remaining layers are executed one after the other as by
  * nnv_conv_forward.  Results per layer are as nnv_conv_forward's up to the order of the
  * float32 summation over the channels (deterministic: fixed order).
  *   descs, kinds, x, w_tx, y : HOST arrays of length n_layers (descriptors, kinds, device

@@ -238,8 +238,10 @@ int static_scratch(void **out) {
 // Layers of one launch run concurrently, so each needs a workspace region of its own; launches
 // follow one another on the stream, so the regions of different launches overlap.
 struct GroupedPlan {
+    enum Class { SINGLE = 0, GEMM_ITEMS = 1, WINO_MANY = 2 };
     struct Batch {
-        int cls;                    // 0: single layer through forward_checked, 1: IM2COL_GEMM work items
+        int cls;
+        int kind;                   // WINO_MANY: the Winograd kind of the batch
         std::vector<int> layers;
         std::vector<size_t> offset; // workspace offset of each layer's region
     };
@@ -250,26 +252,38 @@ struct GroupedPlan {
 GroupedPlan plan_grouped(int n, const Geo *geos, const nnv_kind *kinds) {
     GroupedPlan gp;
     std::vector<char> taken(n, 0);
-    for (int half = 0; half < 2; ++half) {
-        GroupedPlan::Batch cur{1, {}, {}};
+    // collect the layers that satisfy `pick` into batches of at most `cap`, each layer with a
+    // workspace region of its own
+    auto collect = [&](int cls, int kind, int cap, auto pick, auto region_bytes) {
+        GroupedPlan::Batch cur{cls, kind, {}, {}};
         size_t off = 0;
         auto close = [&]() {
             if (!cur.layers.empty()) { gp.bytes = std::max(gp.bytes, off); gp.batches.push_back(cur); }
             cur.layers.clear(); cur.offset.clear(); off = 0;
         };
         for (int i = 0; i < n; ++i) {
-            if (kinds[i] != NNV_IM2COL_GEMM || (geos[i].dtype == NNV_F16) != (half == 1)) continue;
+            if (taken[i] || !pick(i)) continue;
             taken[i] = 1;
             cur.layers.push_back(i);
             cur.offset.push_back(off);
-            off += im2col_items_workspace_bytes(geos[i]);
-            if ((int)cur.layers.size() == kMaxGemmLayers) close();
+            off += align_up(region_bytes(i), 256);
+            if ((int)cur.layers.size() == cap) close();
         }
         close();
+    };
+    for (int half = 0; half < 2; ++half) {
+        auto same_type = [&](int i) { return (geos[i].dtype == NNV_F16) == (half == 1); };
+        collect(GroupedPlan::GEMM_ITEMS, NNV_IM2COL_GEMM, kMaxGemmLayers,
+                [&](int i) { return kinds[i] == NNV_IM2COL_GEMM && same_type(i); },
+                [&](int i) { return im2col_items_workspace_bytes(geos[i]); });
+        for (int kind : {NNV_WINO_F2, NNV_WINO_F4, NNV_WINO_F6})
+            collect(GroupedPlan::WINO_MANY, kind, kMaxWinoLayers,
+                    [&](int i) { return kinds[i] == kind && same_type(i) && wino_many_supported(geos[i], kind); },
+                    [&](int i) { return ws_bytes(geos[i], kind); });
     }
     for (int i = 0; i < n; ++i) {
         if (taken[i]) continue;
-        gp.batches.push_back(GroupedPlan::Batch{0, {i}, {0}});
+        gp.batches.push_back(GroupedPlan::Batch{GroupedPlan::SINGLE, kinds[i], {i}, {0}});
         gp.bytes = std::max(gp.bytes, ws_bytes(geos[i], kinds[i]));
     }
     return gp;
@@ -395,7 +409,7 @@ int nnv_conv_forward_grouped(int n_layers, const nnv_conv_desc *descs, const nnv
     if (gp.bytes > 0 && misaligned(workspace)) return NNV_E_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     for (const GroupedPlan::Batch &b : gp.batches) {
-        if (b.cls == 0) {
+        if (b.cls == GroupedPlan::SINGLE) {
             const int i = b.layers[0];
             rc = forward_checked(geos[i], kinds[i], x[i], w_tx[i], bias ? bias[i] : nullptr, y[i], workspace, st);
             if (rc) return rc;
@@ -411,7 +425,9 @@ int nnv_conv_forward_grouped(int n_layers, const nnv_conv_desc *descs, const nnv
             bg[j] = geos[i]; bx[j] = x[i]; bw[j] = w_tx[i]; bb[j] = bias ? bias[i] : nullptr; by[j] = y[i];
             bws[j] = static_cast<char *>(workspace) + b.offset[j];
         }
-        hipError_t e = launch_im2col_items(m, bg.data(), bx.data(), bw.data(), bb.data(), by.data(), bws.data(), st);
+        hipError_t e = b.cls == GroupedPlan::GEMM_ITEMS
+                           ? launch_im2col_items(m, bg.data(), bx.data(), bw.data(), bb.data(), by.data(), bws.data(), st)
+                           : launch_wino_many(m, bg.data(), b.kind, bx.data(), bw.data(), bb.data(), by.data(), bws.data(), st);
         if (e != hipSuccess) return hip_fail(e);
     }
     return NNV_OK;

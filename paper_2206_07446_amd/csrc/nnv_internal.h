@@ -77,6 +77,11 @@ hipError_t launch_im2col_items(int n, const Geo *geos, const void *const *x, con
                                const float *const *bias, void *const *y, void *const *ws, hipStream_t st);
 
 size_t wino_workspace_bytes(const Geo &g, int kind);
+// Many layers of one Winograd kind and storage type in three launches (see winograd.hip).
+constexpr int kMaxWinoLayers = 20;
+bool wino_many_supported(const Geo &g, int kind);
+hipError_t launch_wino_many(int n, const Geo *geos, int kind, const void *const *x, const void *const *U,
+                            const float *const *bias, void *const *y, void *const *ws, hipStream_t st);
 hipError_t launch_wino(const Geo &g, int kind, const void *x, const void *w, const float *bias, void *y, void *ws, hipStream_t st);
 
 }  // namespace nnv

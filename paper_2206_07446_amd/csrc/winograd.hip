@@ -11,6 +11,7 @@
 // precision; the transforms and the accumulation are float32.
 // float32 F(2x2) / F(4x4) layers with many tiles and few channels run instead as ONE kernel
 // (wino_fused_kernel below) that keeps V and M in registers and needs no workspace.
+#include <climits>
 #include <type_traits>
 #include "nnv_internal.h"
 #include "buf.h"
@@ -57,21 +58,22 @@ struct WinoParams {
 
 // ---- 1. input transform.  Block = 16 tiles x 16 channels (float32: x blockDim/16 channels, so
 // that small layers can be spread over more, smaller workgroups).
+// (tb, by): tile block and channel group of the workgroup; bdim: its threads
 template <int SET, bool HALF>
-__global__ __launch_bounds__(256) void wino_input_kernel(const WinoParams w) {
+__device__ __forceinline__ void wino_input_block(const WinoParams &w, const int tb, const int by, const int bdim) {
     using Wm = WinoMat<SET>;
     constexpr int A = Wm::A, M = Wm::M;
     typedef typename std::conditional<HALF, __half, float>::type T;
     int t_in, c;
     if (HALF) {   // lanes: 8 channels fastest, then tiles -> 128 B contiguous half stores
         t_in = (threadIdx.x >> 3) & 15;
-        c = blockIdx.y * 16 + (threadIdx.x >> 7) * 8 + (threadIdx.x & 7);
+        c = by * 16 + (threadIdx.x >> 7) * 8 + (threadIdx.x & 7);
     } else {      // lanes: 16 tiles fastest, then channels -> 256 B contiguous stores
         t_in = threadIdx.x & 15;
-        c = (blockIdx.y * blockDim.x + threadIdx.x) >> 4;
+        c = (by * bdim + threadIdx.x) >> 4;
     }
     if (c >= w.cpad) return;
-    const int tb = blockIdx.x, t = tb * 16 + t_in;
+    const int t = tb * 16 + t_in;
     // The alpha x alpha patch, all loads in flight at once: elements in the zero padding, of
     // tiles past the end and of padding channels get an out-of-range offset and read as zero.
     float d[A][A];
@@ -116,6 +118,11 @@ __global__ __launch_bounds__(256) void wino_input_kernel(const WinoParams w) {
     }
 }
 
+template <int SET, bool HALF>
+__global__ __launch_bounds__(256) void wino_input_kernel(const WinoParams w) {
+    wino_input_block<SET, HALF>(w, blockIdx.x, blockIdx.y, blockDim.x);
+}
+
 // ---- 2. batched tile GEMM.  grid = (tile-block groups, k-block groups, alpha^2).
 template <bool HALF> struct WFrag {
     typedef float type;
@@ -130,23 +137,14 @@ template <> struct WFrag<true> {
 // every four cycles, so every select or address computation in the loop costs as much as a
 // quarter of a float32 MFMA.  Offsets are a per-lane constant (or an out-of-range constant
 // for fragments outside the problem) plus a scalar that advances by one fragment per step.
+// One wavefront's tile of one frequency: TM x TN blocks of 16 x 16, summed over the ks-th of KS
+// ranges of the channel steps; `red` is the workgroup's LDS (used if KS > 1), nt the wavefront's
+// tile slot in it.
 template <bool HALF, int TM, int TN, int D>
-__global__ __launch_bounds__(1024) void wino_gemm_kernel(const WinoParams w) {
+__device__ __forceinline__ void wino_gemm_tile(const WinoParams &w, const int xi, const int kb0, const int tb0,
+                                               const int ks, const int KS, const int ks_shift, const int nt,
+                                               const int lane, float *red) {
     typedef typename WFrag<HALF>::type frag_t;
-    extern __shared__ __align__(16) float red[];
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar
-    const int KS = 1 << w.ks_shift;
-    const int ks = wave & (KS - 1), nt = wave >> w.ks_shift;
-    const int tiles_per_wg = (blockDim.x >> 6) >> w.ks_shift;
-    // logical workgroup order: frequency slowest, so an XCD works on a few frequencies and keeps
-    // their U and V panels in its own L2
-    const int lwg = xcd_logical_tile(w.gemm_wgs_per_xi * w.alpha2);
-    if (lwg < 0) return;
-    const int xi = lwg / w.gemm_wgs_per_xi;
-    const int tile = (lwg - xi * w.gemm_wgs_per_xi) * tiles_per_wg + nt;   // flattened (k-block group, tile-block group)
-    const int kbt = tile / w.ntb, tbt = tile - kbt * w.ntb;
-    const int kb0 = kbt * TM, tb0 = tbt * TN;              // kb0 >= K16 for surplus wavefronts
     const __amdgpu_buffer_rsrc_t ures = make_rsrc(w.U, w.u_bytes);
     const __amdgpu_buffer_rsrc_t vres = make_rsrc(w.V, w.v_bytes);
     constexpr uint32_t FB = sizeof(frag_t), FRAG = 64 * FB;
@@ -164,7 +162,7 @@ __global__ __launch_bounds__(1024) void wino_gemm_kernel(const WinoParams w) {
         b_voff[t] = ok ? lane * FB : kOobOffset;
         b_base[t] = ok ? ((uint32_t)xi * w.T16 + tb0 + t) * w.csteps : 0u;
     }
-    const int per_wave = (w.csteps + KS - 1) >> w.ks_shift;
+    const int per_wave = (w.csteps + KS - 1) >> ks_shift;
     const int s_begin = min(w.csteps, ks * per_wave);
     const int s_end = min(w.csteps, s_begin + per_wave);
 
@@ -206,13 +204,19 @@ __global__ __launch_bounds__(1024) void wino_gemm_kernel(const WinoParams w) {
                 if (s0 + d < s_end) mfma_step(buf, d);
         }
     };
+    // (scheduling barriers: the loads of the next chunk stay in front of this chunk's MFMAs)
     if (s_begin < s_end) {
         load_chunk(0, s_begin);
+        __builtin_amdgcn_sched_barrier(0);
         for (int s0 = s_begin; s0 < s_end; s0 += 2 * D) {
             load_chunk(1, s0 + D);
+            __builtin_amdgcn_sched_barrier(0);
             compute(0, s0);
+            __builtin_amdgcn_sched_barrier(0);
             load_chunk(0, s0 + 2 * D);
+            __builtin_amdgcn_sched_barrier(0);
             if (s0 + D < s_end) compute(1, s0 + D);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
     constexpr int NREG = TM * TN * 4;
@@ -247,6 +251,24 @@ __global__ __launch_bounds__(1024) void wino_gemm_kernel(const WinoParams w) {
             }
         }
     }
+}
+
+template <bool HALF, int TM, int TN, int D>
+__global__ __launch_bounds__(1024) void wino_gemm_kernel(const WinoParams w) {
+    extern __shared__ __align__(16) float red[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar
+    const int KS = 1 << w.ks_shift;
+    const int ks = wave & (KS - 1), nt = wave >> w.ks_shift;
+    const int tiles_per_wg = (blockDim.x >> 6) >> w.ks_shift;
+    // logical workgroup order: frequency slowest, so an XCD works on a few frequencies and keeps
+    // their U and V panels in its own L2
+    const int lwg = xcd_logical_tile(w.gemm_wgs_per_xi * w.alpha2);
+    if (lwg < 0) return;
+    const int xi = lwg / w.gemm_wgs_per_xi;
+    const int tile = (lwg - xi * w.gemm_wgs_per_xi) * tiles_per_wg + nt;   // flattened (k-block group, tile-block group)
+    const int kbt = tile / w.ntb, tbt = tile - kbt * w.ntb;
+    wino_gemm_tile<HALF, TM, TN, D>(w, xi, kbt * TM, tbt * TN, ks, KS, w.ks_shift, nt, lane, red);   // kb0 >= K16 for surplus wavefronts
 }
 
 // Bias, optional clamp at zero and store of the M x M outputs of tile t, channel k, clipped to P x Q.
@@ -311,12 +333,11 @@ __device__ __forceinline__ void wino_store_tile(const WinoParams &w, float (&Y)[
 
 // ---- 3. output transform.  Block = 16 tiles x blockDim/16 output channels.
 template <int SET, bool HALF>
-__global__ __launch_bounds__(256) void wino_output_kernel(const WinoParams w) {
+__device__ __forceinline__ void wino_output_block(const WinoParams &w, const int tb, const int by, const int bdim) {
     using Wm = WinoMat<SET>;
     constexpr int A = Wm::A, M = Wm::M;
     const int t_in = threadIdx.x & 15;
-    const int tb = blockIdx.x;
-    const int k = (blockIdx.y * blockDim.x + threadIdx.x) >> 4, kb = k >> 4, k_in = k & 15;
+    const int k = (by * bdim + threadIdx.x) >> 4, kb = k >> 4, k_in = k & 15;
     const int t = tb * 16 + t_in;
     if (t >= w.T || k >= w.K) return;
     const float *mp = w.M + ((size_t)kb * w.T16 + tb) * 256 + k_in * 16 + t_in;
@@ -330,6 +351,89 @@ __global__ __launch_bounds__(256) void wino_output_kernel(const WinoParams w) {
     NNV_MATMUL_LEFT(Wm::AT, M, A, A, m, tmp)
     NNV_MATMUL_RIGHT_T(Wm::AT, M, A, M, tmp, Y)
     wino_store_tile<M, HALF>(w, Y, t, k);
+}
+
+template <int SET, bool HALF>
+__global__ __launch_bounds__(256) void wino_output_kernel(const WinoParams w) {
+    wino_output_block<SET, HALF>(w, blockIdx.x, blockIdx.y, blockDim.x);
+}
+
+// ---- many layers of one Winograd variant and storage type in three launches (input transforms,
+// tile GEMMs, output transforms of all of them), for the same reason as the implicit GEMM's
+// work-item launch: a batch-1 layer fills neither the chip nor the time its launch takes.
+// A workgroup finds its layer by counting the entries of a prefix array it has reached.
+struct WinoTable {
+    WinoParams layer[kMaxWinoLayers];
+    int in0[kMaxWinoLayers];      // first workgroup of each layer: input transform,
+    int gemm0[kMaxWinoLayers];    //   tile GEMM (work items: frequency x tile),
+    int out0[kMaxWinoLayers];     //   output transform; INT_MAX beyond the last layer
+    int in_by[kMaxWinoLayers], out_by[kMaxWinoLayers];     // channel groups per tile block (the "y" extent of the single launches)
+    int tm[kMaxWinoLayers], tn[kMaxWinoLayers];            // tile of the GEMM items
+    int n_in, n_gemm, n_out;
+};
+static_assert(sizeof(WinoTable) <= 4096, "the table is passed by value as the kernel argument");
+typedef const __attribute__((address_space(4))) WinoTable *WinoTablePtr;
+
+__device__ __forceinline__ void load_wino_layer(WinoParams &dst, const WinoTablePtr tbl, const int li) {
+    static_assert(sizeof(WinoParams) % 4 == 0, "copied word by word");
+    const __attribute__((address_space(4))) uint32_t *src = (const __attribute__((address_space(4))) uint32_t *)&tbl->layer[li];
+    uint32_t *d = reinterpret_cast<uint32_t *>(&dst);
+#pragma unroll
+    for (int i = 0; i < (int)(sizeof(WinoParams) / 4); ++i) d[i] = src[i];
+}
+
+#define NNV_FIND_LAYER(prefix, b, li, first)                                      \
+    int li = 0, first = 0;                                                        \
+    _Pragma("unroll") for (int l_ = 1; l_ < kMaxWinoLayers; ++l_) {               \
+        const int p_ = tbl->prefix[l_];                                           \
+        if ((b) >= p_) { ++li; first = p_; }                                      \
+    }
+
+template <int SET, bool HALF>
+__global__ __launch_bounds__(256) void wino_input_many_kernel(const WinoTable tbl_arg) {
+    const WinoTablePtr tbl = (WinoTablePtr)__builtin_amdgcn_kernarg_segment_ptr();
+    const int b = blockIdx.x;
+    NNV_FIND_LAYER(in0, b, li, first)
+    WinoParams w;
+    load_wino_layer(w, tbl, li);
+    const int local = b - first, by_n = tbl->in_by[li];
+    wino_input_block<SET, HALF>(w, local / by_n, local % by_n, 256);
+}
+
+template <int SET, bool HALF>
+__global__ __launch_bounds__(256) void wino_output_many_kernel(const WinoTable tbl_arg) {
+    const WinoTablePtr tbl = (WinoTablePtr)__builtin_amdgcn_kernarg_segment_ptr();
+    const int b = blockIdx.x;
+    NNV_FIND_LAYER(out0, b, li, first)
+    WinoParams w;
+    load_wino_layer(w, tbl, li);
+    const int local = b - first, by_n = tbl->out_by[li];
+    wino_output_block<SET, HALF>(w, local / by_n, local % by_n, 256);
+}
+
+// Tile GEMM work items: one wavefront per (frequency, tile); no split of the channel steps (the
+// alpha^2 frequencies already give thousands of items).  Items of a layer are ordered frequency
+// slowest; groups of 8 consecutive items go to one XCD.
+template <bool HALF>
+__global__ __launch_bounds__(64) void wino_gemm_many_kernel(const WinoTable tbl_arg) {
+    const WinoTablePtr tbl = (WinoTablePtr)__builtin_amdgcn_kernarg_segment_ptr();
+    constexpr int G = 8;
+    const int i = blockIdx.x, xcd = i & 7, j = i >> 3;
+    const int item = ((j / G) * 8 + xcd) * G + j % G;
+    if (item >= tbl->n_gemm) return;
+    NNV_FIND_LAYER(gemm0, item, li, first)
+    WinoParams w;
+    load_wino_layer(w, tbl, li);
+    const int local = item - first;
+    const int tm = tbl->tm[li], tn = tbl->tn[li];
+    const int per_xi = w.gemm_wgs_per_xi;                 // tiles per frequency
+    const int xi = local / per_xi, tile = local - xi * per_xi;
+    const int kbt = tile / w.ntb, tbt = tile - kbt * w.ntb;
+    const int lane = threadIdx.x;
+    constexpr int D = HALF ? 2 : 8;
+    if (tm == 2 && tn == 2) wino_gemm_tile<HALF, 2, 2, D>(w, xi, kbt * 2, tbt * 2, 0, 1, 0, 0, lane, nullptr);
+    else if (tm == 2) wino_gemm_tile<HALF, 2, 1, D>(w, xi, kbt * 2, tbt, 0, 1, 0, 0, lane, nullptr);
+    else wino_gemm_tile<HALF, 1, 1, D>(w, xi, kbt, tbt, 0, 1, 0, 0, lane, nullptr);
 }
 
 // ---- fused variant (float32, F(2x2) and F(4x4)): all three steps in one kernel, no workspace.
@@ -580,6 +684,76 @@ static hipError_t launch_wino_t(const Geo &g, const WinoPlan &p, WinoParams &w, 
         dim3 grid(p.T16, p.K16 * (256 / bt), 1);
         hipLaunchKernelGGL((wino_output_kernel<SET, HALF>), grid, dim3(bt), 0, st, w);
     }
+    return hipGetLastError();
+}
+
+static WinoParams wino_params(const Geo &g, const WinoPlan &p, const void *x, const void *U, const float *bias, void *y,
+                              void *ws) {
+    const bool half = g.dtype == NNV_F16;
+    WinoParams w{};
+    w.x = x; w.U = U; w.bias = bias; w.y = y;
+    w.V = ws;
+    w.M = reinterpret_cast<float *>(static_cast<char *>(ws) + p.v_bytes);
+    w.N = g.n; w.C = g.c; w.H = g.h; w.W = g.w; w.K = g.k; w.ph = g.ph; w.pw = g.pw; w.P = g.p; w.Q = g.q;
+    w.x_bytes = (uint32_t)((size_t)g.n * g.c * g.h * g.w * (half ? 2 : 4));
+    w.relu = g.relu;
+    w.th = p.th; w.tw = p.tw; w.T = p.T; w.T16 = p.T16; w.K16 = p.K16; w.cpad = p.cpad; w.csteps = p.csteps;
+    const size_t aa = (size_t)p.alpha * p.alpha;
+    w.u_bytes = (uint32_t)(aa * p.K16 * p.csteps * 64 * (half ? 16 : 4));
+    w.v_bytes = (uint32_t)(aa * p.T16 * p.csteps * 64 * (half ? 16 : 4));
+    w.alpha2 = (int)aa;
+    return w;
+}
+
+bool wino_many_supported(const Geo &g, int kind) {
+    const WinoPlan p = plan_wino(g, kind);
+    return !wino_fused(g, kind, p) && p.T16 <= (1 << 20) && p.K16 <= 65535;
+}
+
+template <int SET, bool HALF>
+static void launch_wino_many_t(const WinoTable &tbl, hipStream_t st) {
+    hipLaunchKernelGGL((wino_input_many_kernel<SET, HALF>), dim3(tbl.n_in), dim3(256), 0, st, tbl);
+    const int per_xcd = ceil_div(ceil_div(tbl.n_gemm, 8), 8) * 8;
+    hipLaunchKernelGGL((wino_gemm_many_kernel<HALF>), dim3(per_xcd * 8), dim3(64), 0, st, tbl);
+    hipLaunchKernelGGL((wino_output_many_kernel<SET, HALF>), dim3(tbl.n_out), dim3(256), 0, st, tbl);
+}
+
+// Layers [0, n) of one Winograd kind and storage type (n <= kMaxWinoLayers, none of them on the
+// fused route) in three launches; ws[i] is layer i's own region of wino_workspace_bytes.
+hipError_t launch_wino_many(int n, const Geo *geos, int kind, const void *const *x, const void *const *U,
+                            const float *const *bias, void *const *y, void *const *ws, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    if (n > kMaxWinoLayers) return hipErrorInvalidValue;
+    const bool half = geos[0].dtype == NNV_F16;
+    WinoTable tbl{};
+    long n_in = 0, n_gemm = 0, n_out = 0;
+    for (int i = 0; i < n; ++i) {
+        const Geo &g = geos[i];
+        if ((g.dtype == NNV_F16) != half || !wino_many_supported(g, kind)) return hipErrorInvalidValue;
+        const WinoPlan p = plan_wino(g, kind);
+        WinoParams &w = tbl.layer[i];
+        w = wino_params(g, p, x[i], U[i], bias ? bias[i] : nullptr, y[i], ws[i]);
+        // tile of a GEMM item: as large as the layer allows (the launch holds thousands of items)
+        const int tm = p.K16 >= 2 ? 2 : 1, tn = (tm == 2 && p.T16 >= 2) ? 2 : 1;
+        w.ks_shift = 0;
+        w.ntb = ceil_div(p.T16, tn);
+        w.gemm_wgs_per_xi = ceil_div(p.K16, tm) * w.ntb;
+        tbl.tm[i] = tm; tbl.tn[i] = tn;
+        tbl.in_by[i] = half ? p.cpad / 16 : ceil_div(p.cpad * 16, 256);
+        tbl.out_by[i] = p.K16;
+        tbl.in0[i] = (int)n_in; tbl.gemm0[i] = (int)n_gemm; tbl.out0[i] = (int)n_out;
+        n_in += (long)p.T16 * tbl.in_by[i];
+        n_gemm += (long)w.alpha2 * w.gemm_wgs_per_xi;
+        n_out += (long)p.T16 * tbl.out_by[i];
+        if (n_in >= (1L << 30) || n_gemm >= (1L << 30) || n_out >= (1L << 30)) return hipErrorInvalidValue;
+    }
+    for (int i = n; i < kMaxWinoLayers; ++i) tbl.in0[i] = tbl.gemm0[i] = tbl.out0[i] = INT_MAX;
+    tbl.n_in = (int)n_in; tbl.n_gemm = (int)n_gemm; tbl.n_out = (int)n_out;
+    const int set = wino_set(kind, geos[0].dtype);
+    if (set == WS_F2) { if (half) launch_wino_many_t<0, true>(tbl, st); else launch_wino_many_t<0, false>(tbl, st); }
+    else if (set == WS_F4) launch_wino_many_t<1, false>(tbl, st);
+    else if (set == WS_F6) launch_wino_many_t<3, false>(tbl, st);
+    else launch_wino_many_t<2, true>(tbl, st);
     return hipGetLastError();
 }
 

@@ -167,11 +167,62 @@ def test_full_stacks_gemm_kind(env, name, half):
     print(name, half, f"worst rel err {worst:.2e}")
 
 
+WINO_SMALL = [
+    Ly("cfg1", 16, 32, 32, 16, 3, 1, 1),
+    Ly("ragged", 37, 13, 19, 20, 3, 1, 1),
+    Ly("batch2", 8, 9, 10, 24, 3, 1, 1, n=2),
+    Ly("pad0", 12, 10, 10, 16, 3, 1, 0),
+    Ly("pad2", 4, 6, 7, 5, 3, 1, 2),
+    Ly("tiny", 1, 3, 3, 1, 3, 1, 1),
+    Ly("deep", 512, 7, 7, 64, 3, 1, 1),
+    Ly("batch3", 20, 11, 13, 40, 3, 1, 1, n=3),
+    Ly("batch5_deep", 128, 7, 7, 64, 3, 1, 1, n=5),
+    Ly("wide_k", 24, 20, 18, 200, 3, 1, 1),
+    Ly("one_k16", 40, 30, 30, 16, 3, 1, 1),              # a single 16-row panel: 16 x 16 GEMM tiles
+    Ly("fz_ragged", 6, 90, 90, 24, 3, 1, 1),             # float32 F(2x2)/F(4x4): the fused single-kernel route, run on its own
+]
+
+
+@pytest.mark.parametrize("kind", [2, 3, 5], ids=["f2", "f4", "f6"])
+@pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
+def test_winograd_layers_in_one_call(env, kind, half):
+    nnv, torch = env
+    layers = [l for l in WINO_SMALL + WINO_SMALL[:10] if kind in applicable_kinds(l, half)]
+    if not layers:
+        pytest.skip("F(6x6) exists in float32 only")
+    cases = [Case(nnv, torch, l, kind, half, 1400 + i, bias=(i % 2 == 1)) for i, l in enumerate(layers)]
+    assert half or len(cases) > 20          # more than one launch group carries
+    run_grouped(nnv, torch, cases)
+    run_grouped(nnv, torch, cases, relu=True)
+    if not half:                            # against the single calls: float32 summation order only
+        dev = torch.device("cuda:0")
+        run_grouped(nnv, torch, cases)
+        for c in cases:
+            need = nnv.nnv_workspace_bytes(c.desc, kind)
+            ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+            y1 = torch.empty(c.numel, device=dev)
+            nnv.nnv_conv_forward(c.desc, kind, c.xd, c.wt, c.bd, y1, ws)
+            torch.cuda.synchronize()
+            a, b = c.result().ravel(), y1.cpu().numpy().astype(np.float64)
+            assert np.abs(a - b).max() <= 0.1 * conv_tolerance(kind, False) * np.abs(b).max(), c.layer.name
+
+
+@pytest.mark.parametrize("name,kind,half", [("resnet18", 2, False), ("resnet18", 3, False), ("resnet18", 5, False),
+                                            ("vgg16", 3, False), ("resnet50", 3, True), ("resnet50", 2, True)])
+def test_full_stacks_winograd(env, name, kind, half):
+    nnv, torch = env
+    cases = [Case(nnv, torch, l, kind, half, 220607446 + 4000 + i) for i, l in enumerate(stack(name)) if l.winograd_ok
+             and kind in applicable_kinds(l, half)]
+    worst = run_grouped(nnv, torch, cases, big=True)
+    print(name, KIND_NAMES[kind], half, f"worst rel err {worst:.2e}")
+
+
 def test_graph_replay(env):
     """The grouped call captured into a HIP graph and replayed, outputs and workspace scrambled in between."""
     nnv, torch = env
     dev = torch.device("cuda:0")
     cases = [Case(nnv, torch, l, nnv.IM2COL_GEMM, False, 1200 + i) for i, l in enumerate(SMALL[:16])]
+    cases += [Case(nnv, torch, l, nnv.WINO_F4, False, 1250 + i) for i, l in enumerate(WINO_SMALL[:8])]
     descs, kinds = [c.desc for c in cases], [c.kind for c in cases]
     need = nnv.nnv_conv_forward_grouped_workspace_bytes(descs, kinds)
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
