@@ -238,7 +238,7 @@ int static_scratch(void **out) {
 // Layers of one launch run concurrently, so each needs a workspace region of its own; launches
 // follow one another on the stream, so the regions of different launches overlap.
 struct GroupedPlan {
-    enum Class { SINGLE = 0, GEMM_ITEMS = 1, WINO_MANY = 2 };
+    enum Class { SINGLE = 0, GEMM_ITEMS = 1, WINO_MANY = 2, DIRECT_MANY = 3, DW_MANY = 4 };
     struct Batch {
         int cls;
         int kind;                   // WINO_MANY: the Winograd kind of the batch
@@ -276,6 +276,11 @@ GroupedPlan plan_grouped(int n, const Geo *geos, const nnv_kind *kinds) {
         collect(GroupedPlan::GEMM_ITEMS, NNV_IM2COL_GEMM, kMaxGemmLayers,
                 [&](int i) { return kinds[i] == NNV_IM2COL_GEMM && same_type(i); },
                 [&](int i) { return im2col_items_workspace_bytes(geos[i]); });
+        collect(GroupedPlan::DIRECT_MANY, NNV_DIRECT, kMaxDirectLayers,
+                [&](int i) { return kinds[i] == NNV_DIRECT && same_type(i) && direct_many_supported(geos[i]); },
+                [&](int) { return (size_t)0; });
+        collect(GroupedPlan::DW_MANY, NNV_DEPTHWISE, kMaxDwLayers,
+                [&](int i) { return kinds[i] == NNV_DEPTHWISE && same_type(i); }, [&](int) { return (size_t)0; });
         for (int kind : {NNV_WINO_F2, NNV_WINO_F4, NNV_WINO_F6})
             collect(GroupedPlan::WINO_MANY, kind, kMaxWinoLayers,
                     [&](int i) { return kinds[i] == kind && same_type(i) && wino_many_supported(geos[i], kind); },
@@ -425,9 +430,21 @@ int nnv_conv_forward_grouped(int n_layers, const nnv_conv_desc *descs, const nnv
             bg[j] = geos[i]; bx[j] = x[i]; bw[j] = w_tx[i]; bb[j] = bias ? bias[i] : nullptr; by[j] = y[i];
             bws[j] = static_cast<char *>(workspace) + b.offset[j];
         }
-        hipError_t e = b.cls == GroupedPlan::GEMM_ITEMS
-                           ? launch_im2col_items(m, bg.data(), bx.data(), bw.data(), bb.data(), by.data(), bws.data(), st)
-                           : launch_wino_many(m, bg.data(), b.kind, bx.data(), bw.data(), bb.data(), by.data(), bws.data(), st);
+        hipError_t e = hipSuccess;
+        switch (b.cls) {
+            case GroupedPlan::GEMM_ITEMS:
+                e = launch_im2col_items(m, bg.data(), bx.data(), bw.data(), bb.data(), by.data(), bws.data(), st);
+                break;
+            case GroupedPlan::WINO_MANY:
+                e = launch_wino_many(m, bg.data(), b.kind, bx.data(), bw.data(), bb.data(), by.data(), bws.data(), st);
+                break;
+            case GroupedPlan::DIRECT_MANY:
+                e = launch_direct_many(m, bg.data(), bx.data(), bw.data(), bb.data(), by.data(), st);
+                break;
+            default:
+                e = launch_depthwise_many(m, bg.data(), bx.data(), bw.data(), bb.data(), by.data(), st);
+                break;
+        }
         if (e != hipSuccess) return hip_fail(e);
     }
     return NNV_OK;

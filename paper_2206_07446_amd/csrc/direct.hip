@@ -7,6 +7,8 @@
 // scalar loads, and x is read along W (coalesced).  depthwise: HBM-bound, one thread per
 // output pixel of one channel plane, taps of the channel (3x3 or 5x5) from the packed
 // [C/32][taps][32] layout.
+#include <climits>
+#include <type_traits>
 #include "nnv_internal.h"
 #include "buf.h"
 
@@ -179,21 +181,16 @@ __global__ __launch_bounds__(1024) void direct_conv_tiled_kernel(const T *__rest
 // grid hold zeros, and because lane indices wrap modulo 64 they serve as the zero padding on
 // all four sides.  (Cutting larger planes into 6x6-output tiles with an 8x8 halo patch was
 // measured too and loses: 36 useful lanes of 64 cost more than the loads save.)
+// lblk: the workgroup's logical block (image, pixel group, output-channel group); CS: its wavefronts
 template <typename T, int TK, int FS, bool GRID8 = false>
-__global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__restrict__ x, const float *__restrict__ w,
-                                                                 const float *__restrict__ bias, T *__restrict__ y,
-                                                                 const DirectParams d) {
-    extern __shared__ __align__(16) float lds[];
+__device__ __forceinline__ void direct_slane_block(const T *__restrict__ x, const float *__restrict__ w,
+                                                   const float *__restrict__ bias, T *__restrict__ y,
+                                                   const DirectParams &d, const int lblk, const int CS, float *lds) {
     constexpr int ESZ = sizeof(T);
     constexpr int RS = FS * FS;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int CS = blockDim.x >> 6;
     const int PQ = d.P * d.Q, HW = d.H * d.W;
-    // XCD-aware block order: an XCD gets a contiguous range of output-channel groups (deep layers,
-    // filters dominate the traffic) or of pixel groups (shallow layers, x dominates)
-    const int lblk = xcd_logical_tile(d.grid_nx * d.grid_ny * d.N);
-    if (lblk < 0) return;
     const int img = lblk / (d.grid_nx * d.grid_ny), l2 = lblk - img * (d.grid_nx * d.grid_ny);
     const int bx = d.k_major ? l2 % d.grid_nx : l2 / d.grid_ny;
     const int by = d.k_major ? l2 / d.grid_nx : l2 % d.grid_ny;
@@ -229,7 +226,11 @@ __global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__rest
     const __amdgpu_buffer_rsrc_t xres = make_rsrc(x + (size_t)img * d.C * HW, (uint32_t)((size_t)d.C * HW * ESZ));
     const uint32_t plane = (uint32_t)(HW * ESZ);
     const size_t wk = (size_t)d.C * RS;
-    const float *wrow = w + (size_t)k0 * wk;
+    // The taps are wave-uniform and nothing in this kernel writes them: reading them through the
+    // constant address space makes them scalar loads whatever the compiler can prove about
+    // aliasing (in the many-layer kernel the pointers come out of a table, and it proves nothing).
+    typedef const __attribute__((address_space(4))) float *ConstFloatPtr;
+    const ConstFloatPtr wrow = (ConstFloatPtr)(uintptr_t)(w + (size_t)k0 * wk);
     float acc[TK];
 #pragma unroll
     for (int j = 0; j < TK; ++j) acc[j] = 0.f;
@@ -266,7 +267,7 @@ __global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__rest
         float xa[RS], xb[RS];
         load_pixels(xa, c);
         load_pixels(xb, c + CS);
-        const float *wa = wrow + (size_t)c * RS, *wb = wrow + (size_t)(c + CS) * RS;
+        const ConstFloatPtr wa = wrow + (size_t)c * RS, wb = wrow + (size_t)(c + CS) * RS;
 #pragma unroll
         for (int j = 0; j < TK; ++j)
 #pragma unroll
@@ -279,7 +280,7 @@ __global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__rest
     for (; c < d.C; c += CS) {
         float xa[RS];
         load_pixels(xa, c);
-        const float *wa = wrow + (size_t)c * RS;
+        const ConstFloatPtr wa = wrow + (size_t)c * RS;
 #pragma unroll
         for (int j = 0; j < TK; ++j)
 #pragma unroll
@@ -301,6 +302,74 @@ __global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__rest
                 if (jj == j) v = acc[jj];
         }
         if (live) st<T>(y, ((size_t)img * d.K + k0 + j) * PQ + pix, act(v + (bias ? bias[k0 + j] : 0.f), d.relu));
+    }
+}
+
+template <typename T, int TK, int FS, bool GRID8 = false>
+__global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__restrict__ x, const float *__restrict__ w,
+                                                                 const float *__restrict__ bias, T *__restrict__ y,
+                                                                 const DirectParams d) {
+    extern __shared__ __align__(16) float lds[];
+    // XCD-aware block order: an XCD gets a contiguous range of output-channel groups (deep layers,
+    // filters dominate the traffic) or of pixel groups (shallow layers, x dominates)
+    const int lblk = xcd_logical_tile(d.grid_nx * d.grid_ny * d.N);
+    if (lblk < 0) return;
+    direct_slane_block<T, TK, FS, GRID8>(x, w, bias, y, d, lblk, blockDim.x >> 6, lds);
+}
+
+// ---- many direct-convolution layers (groups 1, square 1x1 / 3x3 / 5x5 / 7x7 filter) in one launch
+// of four-wavefront workgroups: a workgroup finds its layer by counting the entries of a prefix
+// array it has reached and then runs that layer's block.
+struct DirectLayer {
+    const void *x;
+    const float *w, *bias;
+    void *y;
+    DirectParams d;
+    int variant;        // 8 * (index of the filter size in {1, 3, 5, 7}) + 4 * (8 channels per lane) + 2 * (lane grid) ; see below
+};
+struct DirectTable {
+    DirectLayer layer[kMaxDirectLayers];
+    int block0[kMaxDirectLayers];     // first workgroup of each layer, INT_MAX beyond the last
+    int nblocks;
+};
+static_assert(sizeof(DirectTable) <= 4096, "the table is passed by value as the kernel argument");
+typedef const __attribute__((address_space(4))) DirectTable *DirectTablePtr;
+constexpr int kDirectManyWaves = 4;
+
+template <typename T>
+__global__ __launch_bounds__(64 * kDirectManyWaves) void direct_conv_many_kernel(const DirectTable tbl_arg) {
+    __shared__ __align__(16) float lds[kDirectManyWaves * 8 * 64];
+    const DirectTablePtr tbl = (DirectTablePtr)__builtin_amdgcn_kernarg_segment_ptr();
+    // groups of 8 consecutive blocks (neighbouring pixel or channel groups of a layer) go to one XCD
+    const int i = blockIdx.x, xcd = i & 7, j = i >> 3;
+    const int b = ((j >> 3) * 8 + xcd) * 8 + (j & 7);
+    if (b >= tbl->nblocks) return;
+    int li = 0, first = 0;
+#pragma unroll
+    for (int l = 1; l < kMaxDirectLayers; ++l) {
+        const int p = tbl->block0[l];
+        if (b >= p) { ++li; first = p; }
+    }
+    DirectLayer L;
+    {
+        static_assert(sizeof(DirectLayer) % 4 == 0, "copied word by word");
+        const __attribute__((address_space(4))) uint32_t *src = (const __attribute__((address_space(4))) uint32_t *)&tbl->layer[li];
+        uint32_t *dst = reinterpret_cast<uint32_t *>(&L);
+#pragma unroll
+        for (int k = 0; k < (int)(sizeof(DirectLayer) / 4); ++k) dst[k] = src[k];
+    }
+    const T *x = static_cast<const T *>(L.x);
+    T *y = static_cast<T *>(L.y);
+    const int lblk = b - first;
+    switch (L.variant) {
+        case 0: direct_slane_block<T, 4, 1>(x, L.w, L.bias, y, L.d, lblk, kDirectManyWaves, lds); break;
+        case 4: direct_slane_block<T, 8, 1>(x, L.w, L.bias, y, L.d, lblk, kDirectManyWaves, lds); break;
+        case 8: direct_slane_block<T, 4, 3>(x, L.w, L.bias, y, L.d, lblk, kDirectManyWaves, lds); break;
+        case 10: direct_slane_block<T, 4, 3, true>(x, L.w, L.bias, y, L.d, lblk, kDirectManyWaves, lds); break;
+        case 12: direct_slane_block<T, 8, 3>(x, L.w, L.bias, y, L.d, lblk, kDirectManyWaves, lds); break;
+        case 14: direct_slane_block<T, 8, 3, true>(x, L.w, L.bias, y, L.d, lblk, kDirectManyWaves, lds); break;
+        case 16: direct_slane_block<T, 4, 5>(x, L.w, L.bias, y, L.d, lblk, kDirectManyWaves, lds); break;
+        default: direct_slane_block<T, 4, 7>(x, L.w, L.bias, y, L.d, lblk, kDirectManyWaves, lds); break;
     }
 }
 
@@ -424,6 +493,41 @@ static hipError_t launch_direct_t(const Geo &g, const T *x, const float *w, cons
     return hipGetLastError();
 }
 
+bool direct_many_supported(const Geo &g) { return slane_supported(g); }
+
+// Layers [0, n) (one storage type, n <= kMaxDirectLayers, each direct_many_supported) in one launch.
+hipError_t launch_direct_many(int n, const Geo *geos, const void *const *x, const void *const *w, const float *const *bias,
+                              void *const *y, hipStream_t st_) {
+    if (n <= 0) return hipSuccess;
+    if (n > kMaxDirectLayers) return hipErrorInvalidValue;
+    const bool half = geos[0].dtype == NNV_F16;
+    DirectTable tbl{};
+    long blocks = 0;
+    for (int i = 0; i < n; ++i) {
+        const Geo &g = geos[i];
+        if ((g.dtype == NNV_F16) != half || !slane_supported(g)) return hipErrorInvalidValue;
+        DirectLayer &L = tbl.layer[i];
+        L.x = x[i]; L.w = static_cast<const float *>(w[i]); L.bias = bias ? bias[i] : nullptr; L.y = y[i];
+        L.d = DirectParams{g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.sh, g.sw, g.ph, g.pw, g.p, g.q, g.cg, g.kg, 0, 0, 0, g.relu};
+        const bool grid8 = g.r == 3 && g.sh == 1 && g.sw == 1 && g.h <= 7 && g.w <= 7 && g.ph <= 1 && g.pw <= 1;
+        const int tk = (g.k % 8 == 0 && g.r <= 3) ? 8 : 4;      // the launch holds plenty of blocks: 8 outputs per loaded pixel
+        L.d.grid_nx = grid8 ? 1 : ceil_div(g.p * g.q, 64);
+        L.d.grid_ny = g.k / tk;
+        L.d.k_major = (size_t)g.k * g.c * g.r * g.s * 4 >= (size_t)g.c * g.h * g.w * (half ? 2 : 4);
+        const int fs_index = g.r == 1 ? 0 : g.r == 3 ? 1 : g.r == 5 ? 2 : 3;
+        L.variant = 8 * fs_index + 4 * (tk == 8) + 2 * (grid8 ? 1 : 0);
+        tbl.block0[i] = (int)blocks;
+        blocks += (long)L.d.grid_nx * L.d.grid_ny * g.n;
+        if (blocks >= (1L << 30)) return hipErrorInvalidValue;
+    }
+    for (int i = n; i < kMaxDirectLayers; ++i) tbl.block0[i] = INT_MAX;
+    tbl.nblocks = (int)blocks;
+    const int per_xcd = ceil_div(ceil_div((int)blocks, 8), 8) * 8;
+    if (half) hipLaunchKernelGGL(direct_conv_many_kernel<__half>, dim3(per_xcd * 8), dim3(64 * kDirectManyWaves), 0, st_, tbl);
+    else hipLaunchKernelGGL(direct_conv_many_kernel<float>, dim3(per_xcd * 8), dim3(64 * kDirectManyWaves), 0, st_, tbl);
+    return hipGetLastError();
+}
+
 hipError_t launch_direct(const Geo &g, const void *x, const float *w, const float *bias, void *y, hipStream_t st_) {
     if (g.dtype == NNV_F16)
         return launch_direct_t<__half>(g, static_cast<const __half *>(x), w, bias, static_cast<__half *>(y), st_);
@@ -437,14 +541,20 @@ struct DwParams {
 };
 
 template <typename T, int FS>
-__global__ __launch_bounds__(256) void depthwise_kernel(const T *__restrict__ x, const T *__restrict__ wp,
-                                                        const float *__restrict__ bias, T *__restrict__ y,
-                                                        const DwParams d) {
-    const int pq = blockIdx.x * 256 + threadIdx.x;
-    const int c = blockIdx.y, img = blockIdx.z;
+__device__ __forceinline__ void depthwise_block(const T *__restrict__ x, const T *__restrict__ wp,
+                                                const float *__restrict__ bias, T *__restrict__ y, const DwParams &d,
+                                                const int pqb, const int c, const int img) {
+    const int pq = pqb * 256 + threadIdx.x;
     if (pq >= d.P * d.Q) return;
     const int p = pq / d.Q, q = pq - p * d.Q;
-    const T *wc = wp + (size_t)(c >> 5) * (FS * FS * 32) + (c & 31);
+    // the channel's taps are uniform over the workgroup: constant address space = scalar loads
+    typedef typename std::conditional<sizeof(T) == 2, unsigned short, float>::type Raw;
+    typedef const __attribute__((address_space(4))) Raw *ConstTapPtr;
+    const ConstTapPtr wc = (ConstTapPtr)(uintptr_t)(wp + (size_t)(c >> 5) * (FS * FS * 32) + (c & 31));
+    auto tap = [&](int i) -> float {
+        if constexpr (sizeof(T) == 2) return (float)__builtin_bit_cast(_Float16, (unsigned short)wc[i]);
+        else return wc[i];
+    };
     const T *xc = x + ((size_t)img * d.C + c) * d.H * d.W;
     const int ih0 = p * d.st - d.ph, iw0 = q * d.st - d.pw;
     float acc = bias ? bias[c] : 0.f;
@@ -457,10 +567,130 @@ __global__ __launch_bounds__(256) void depthwise_kernel(const T *__restrict__ x,
             const int iw = iw0 + s;
             const bool ok = rok && iw >= 0 && iw < d.W;
             const float xv = ok ? ld<T>(xc, (size_t)ih * d.W + iw) : 0.f;
-            acc = fmaf(xv, ld<T>(wc, (r * FS + s) * 32), acc);
+            acc = fmaf(xv, tap((r * FS + s) * 32), acc);
         }
     }
     st<T>(y, ((size_t)img * d.C + c) * d.P * d.Q + pq, act(acc, d.relu));
+}
+
+template <typename T, int FS>
+__global__ __launch_bounds__(256) void depthwise_kernel(const T *__restrict__ x, const T *__restrict__ wp,
+                                                        const float *__restrict__ bias, T *__restrict__ y,
+                                                        const DwParams d) {
+    depthwise_block<T, FS>(x, wp, bias, y, d, blockIdx.x, blockIdx.y, blockIdx.z);
+}
+
+// ---- many depthwise layers in one launch (a MobileNet-style network has 13-17 of them, each a few
+// microseconds of work).  y of a layer is one contiguous [N*C][P*Q] array: a thread owns
+// kDwPerThread outputs of that flat array (stride 256, so every store of a wavefront is one
+// contiguous run whatever the plane size: 7x7 planes fill the lanes like 112x112 ones), finds
+// channel and pixel by division, and reads the channel's taps with ordinary (cached) loads.
+// Two outputs per thread for 3x3 and one for 5x5 keep the kernel at 8 wavefronts per SIMD: what
+// bounds these small layers is how many loads the chip has in flight, not a thread's own pace.
+__host__ __device__ constexpr int dw_per_thread(int fs) { return fs == 3 ? 2 : 1; }
+struct DwLayer {
+    const void *x, *w;
+    const float *bias;
+    void *y;
+    DwParams d;
+    int fs;
+};
+struct DwTable {
+    DwLayer layer[kMaxDwLayers];
+    int block0[kMaxDwLayers];     // first workgroup of each layer, INT_MAX beyond the last
+    int nblocks;
+};
+static_assert(sizeof(DwTable) <= 4096, "the table is passed by value as the kernel argument");
+typedef const __attribute__((address_space(4))) DwTable *DwTablePtr;
+
+template <typename T, int FS>
+__device__ __forceinline__ void depthwise_flat_block(const T *__restrict__ x, const T *__restrict__ wp,
+                                                     const float *__restrict__ bias, T *__restrict__ y,
+                                                     const DwParams &d, const int blk) {
+    constexpr int kDwPerThread = dw_per_thread(FS);
+    const int PQ = d.P * d.Q, total = d.N * d.C * PQ;
+    int o[kDwPerThread], pq[kDwPerThread], c[kDwPerThread], plane[kDwPerThread];
+    float acc[kDwPerThread];
+#pragma unroll
+    for (int i = 0; i < kDwPerThread; ++i) {
+        o[i] = (blk * kDwPerThread + i) * 256 + threadIdx.x;
+        const int oo = o[i] < total ? o[i] : 0;
+        plane[i] = oo / PQ;                        // image * C + channel
+        pq[i] = oo - plane[i] * PQ;
+        c[i] = d.N == 1 ? plane[i] : plane[i] % d.C;
+        acc[i] = bias ? bias[c[i]] : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < kDwPerThread; ++i) {
+        const int p = pq[i] / d.Q, q = pq[i] - p * d.Q;
+        const T *wc = wp + (size_t)(c[i] >> 5) * (FS * FS * 32) + (c[i] & 31);
+        const T *xc = x + (size_t)plane[i] * d.H * d.W;
+        const int ih0 = p * d.st - d.ph, iw0 = q * d.st - d.pw;
+#pragma unroll
+        for (int r = 0; r < FS; ++r) {
+            const int ih = ih0 + r;
+            const bool rok = ih >= 0 && ih < d.H;
+#pragma unroll
+            for (int s2 = 0; s2 < FS; ++s2) {
+                const int iw = iw0 + s2;
+                const bool ok = rok && iw >= 0 && iw < d.W;
+                const float xv = ok ? ld<T>(xc, (size_t)ih * d.W + iw) : 0.f;
+                acc[i] = fmaf(xv, ld<T>(wc, (r * FS + s2) * 32), acc[i]);
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kDwPerThread; ++i)
+        if (o[i] < total) st<T>(y, (size_t)o[i], act(acc[i], d.relu));
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void depthwise_many_kernel(const DwTable tbl_arg) {
+    const DwTablePtr tbl = (DwTablePtr)__builtin_amdgcn_kernarg_segment_ptr();
+    const int b = blockIdx.x;
+    int li = 0, first = 0;
+#pragma unroll
+    for (int l = 1; l < kMaxDwLayers; ++l) {
+        const int p = tbl->block0[l];
+        if (b >= p) { ++li; first = p; }
+    }
+    DwLayer L;
+    {
+        static_assert(sizeof(DwLayer) % 4 == 0, "copied word by word");
+        const __attribute__((address_space(4))) uint32_t *src = (const __attribute__((address_space(4))) uint32_t *)&tbl->layer[li];
+        uint32_t *dst = reinterpret_cast<uint32_t *>(&L);
+#pragma unroll
+        for (int k = 0; k < (int)(sizeof(DwLayer) / 4); ++k) dst[k] = src[k];
+    }
+    const T *x = static_cast<const T *>(L.x), *w = static_cast<const T *>(L.w);
+    T *y = static_cast<T *>(L.y);
+    if (L.fs == 5) depthwise_flat_block<T, 5>(x, w, L.bias, y, L.d, b - first);
+    else depthwise_flat_block<T, 3>(x, w, L.bias, y, L.d, b - first);
+}
+
+hipError_t launch_depthwise_many(int n, const Geo *geos, const void *const *x, const void *const *w, const float *const *bias,
+                                 void *const *y, hipStream_t st_) {
+    if (n <= 0) return hipSuccess;
+    if (n > kMaxDwLayers) return hipErrorInvalidValue;
+    const bool half = geos[0].dtype == NNV_F16;
+    DwTable tbl{};
+    long blocks = 0;
+    for (int i = 0; i < n; ++i) {
+        const Geo &g = geos[i];
+        if ((g.dtype == NNV_F16) != half) return hipErrorInvalidValue;
+        DwLayer &L = tbl.layer[i];
+        L.x = x[i]; L.w = w[i]; L.bias = bias ? bias[i] : nullptr; L.y = y[i];
+        L.d = DwParams{g.n, g.c, g.h, g.w, g.sh, g.ph, g.pw, g.p, g.q, g.relu};
+        L.fs = g.r;
+        tbl.block0[i] = (int)blocks;
+        blocks += ((long)g.n * g.c * g.p * g.q + 256 * dw_per_thread(g.r) - 1) / (256 * dw_per_thread(g.r));
+        if (blocks >= (1L << 30)) return hipErrorInvalidValue;
+    }
+    for (int i = n; i < kMaxDwLayers; ++i) tbl.block0[i] = INT_MAX;
+    tbl.nblocks = (int)blocks;
+    if (half) hipLaunchKernelGGL(depthwise_many_kernel<__half>, dim3((unsigned)blocks), dim3(256), 0, st_, tbl);
+    else hipLaunchKernelGGL(depthwise_many_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, st_, tbl);
+    return hipGetLastError();
 }
 
 hipError_t launch_depthwise(const Geo &g, const void *x, const void *w, const float *bias, void *y, hipStream_t st_) {

@@ -65,6 +65,16 @@ hipError_t launch_fill_u32(uint32_t *dst, size_t n, uint32_t v, hipStream_t st);
 hipError_t launch_direct(const Geo &g, const void *x, const float *w, const float *bias, void *y, hipStream_t st);
 hipError_t launch_depthwise(const Geo &g, const void *x, const void *w, const float *bias, void *y, hipStream_t st);
 
+// Many layers in one launch: direct convolution (layers for which direct_many_supported holds) and
+// depthwise convolution; one storage type per call.
+constexpr int kMaxDirectLayers = 32;
+constexpr int kMaxDwLayers = 40;
+bool direct_many_supported(const Geo &g);
+hipError_t launch_direct_many(int n, const Geo *geos, const void *const *x, const void *const *w, const float *const *bias,
+                              void *const *y, hipStream_t st);
+hipError_t launch_depthwise_many(int n, const Geo *geos, const void *const *x, const void *const *w,
+                                 const float *const *bias, void *const *y, hipStream_t st);
+
 size_t im2col_workspace_bytes(const Geo &g);
 hipError_t launch_im2col(const Geo &g, const void *x, const void *w, const float *bias, void *y, void *ws, hipStream_t st);
 

@@ -217,12 +217,66 @@ def test_full_stacks_winograd(env, name, kind, half):
     print(name, KIND_NAMES[kind], half, f"worst rel err {worst:.2e}")
 
 
+DIRECT_DW = [
+    Ly("cfg1", 16, 32, 32, 16, 3, 1, 1),
+    Ly("ragged", 37, 13, 19, 20, 3, 1, 1),
+    Ly("batch2", 8, 9, 10, 24, 3, 1, 1, n=2),
+    Ly("tiny", 1, 3, 3, 4, 3, 1, 1),
+    Ly("s2", 16, 15, 15, 32, 3, 2, 1),
+    Ly("stem", 3, 32, 32, 64, 7, 2, 3),
+    Ly("pw", 96, 14, 14, 24, 1, 1, 0),
+    Ly("pw_s2", 64, 14, 14, 128, 1, 2, 0),
+    Ly("pw_odd_c", 41, 7, 7, 16, 1, 1, 0),
+    Ly("deep", 512, 7, 7, 64, 3, 1, 1),                      # 7x7 plane: the lane-grid variant
+    Ly("plane5", 9, 5, 7, 8, 3, 1, 1),
+    Ly("plane7_pad0", 9, 7, 7, 12, 3, 1, 0),
+    Ly("k5", 6, 11, 9, 8, 5, 1, 2),
+    Ly("batch3", 20, 11, 13, 40, 3, 1, 1, n=3),
+    Ly("k_odd", 10, 9, 9, 7, 3, 1, 1),                       # K not a multiple of 4: runs on its own
+    Ly("grp2", 8, 9, 9, 12, 3, 1, 1, groups=2),              # grouped: runs on its own
+    Ly("dw_s1", 32, 14, 14, 32, 3, 1, 1, groups=32),
+    Ly("dw_s2", 48, 15, 15, 48, 3, 2, 1, groups=48),
+    Ly("dw_n2", 5, 7, 7, 5, 3, 1, 1, groups=5, n=2),
+    Ly("dw5_s1", 40, 14, 14, 40, 5, 1, 2, groups=40),
+    Ly("dw5_s2", 72, 15, 13, 72, 5, 2, 2, groups=72, n=2),
+    Ly("dw_big", 96, 40, 40, 96, 3, 1, 1, groups=96),
+]
+
+
+@pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
+def test_direct_and_depthwise_layers_in_one_call(env, half):
+    nnv, torch = env
+    cases = [Case(nnv, torch, l, nnv.DIRECT, half, 1500 + i, bias=(i % 2 == 0)) for i, l in enumerate(DIRECT_DW + DIRECT_DW[:14])]
+    cases += [Case(nnv, torch, l, nnv.DEPTHWISE, half, 1600 + i, bias=(i % 2 == 1)) for i, l in enumerate(DIRECT_DW) if l.is_depthwise]
+    run_grouped(nnv, torch, cases)
+    run_grouped(nnv, torch, cases, relu=True)
+    dev = torch.device("cuda:0")
+    run_grouped(nnv, torch, cases)
+    for c in cases:                       # the same block code as the single launches; only the channel split differs
+        y1 = torch.empty(c.numel, dtype=torch.float16 if half else torch.float32, device=dev)
+        nnv.nnv_conv_forward(c.desc, c.kind, c.xd, c.wt, c.bd, y1, None)
+        torch.cuda.synchronize()
+        a, b = c.result().ravel(), y1.cpu().numpy().astype(np.float64)
+        assert np.abs(a - b).max() <= (2e-3 if half else 2e-5) * np.abs(b).max(), c.layer.name
+
+
+@pytest.mark.parametrize("name,kind", [("resnet18", 0), ("mobilenetv2", 0), ("mobilenetv2", 4), ("efficientnet_b0", 4)])
+def test_full_stacks_direct_and_depthwise(env, name, kind):
+    nnv, torch = env
+    cases = [Case(nnv, torch, l, kind, False, 220607446 + 5000 + i) for i, l in enumerate(stack(name))
+             if kind in applicable_kinds(l, False)]
+    worst = run_grouped(nnv, torch, cases, big=True)
+    print(name, KIND_NAMES[kind], f"worst rel err {worst:.2e}")
+
+
 def test_graph_replay(env):
     """The grouped call captured into a HIP graph and replayed, outputs and workspace scrambled in between."""
     nnv, torch = env
     dev = torch.device("cuda:0")
     cases = [Case(nnv, torch, l, nnv.IM2COL_GEMM, False, 1200 + i) for i, l in enumerate(SMALL[:16])]
     cases += [Case(nnv, torch, l, nnv.WINO_F4, False, 1250 + i) for i, l in enumerate(WINO_SMALL[:8])]
+    cases += [Case(nnv, torch, l, nnv.DIRECT, False, 1270 + i) for i, l in enumerate(DIRECT_DW[:12])]
+    cases += [Case(nnv, torch, l, nnv.DEPTHWISE, False, 1290 + i) for i, l in enumerate(DIRECT_DW) if l.is_depthwise]
     descs, kinds = [c.desc for c in cases], [c.kind for c in cases]
     need = nnv.nnv_conv_forward_grouped_workspace_bytes(descs, kinds)
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
