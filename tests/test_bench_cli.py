@@ -17,4 +17,5 @@ def test_source_digest_is_stable_and_names_the_kernel_sources():
     import bench
     d = bench.csrc_digest()
     assert len(d) == 16 and d == bench.csrc_digest()
-    assert set(bench.MEASURED_TRAFFIC["MB_per_step"]) <= {"transform_kernel", "direct_conv_slane_kernel", "im2col_gemm_kernel"}
+    assert set(bench.MEASURED_TRAFFIC["MB_per_step"]) <= set(bench.PHASE_KERNELS)
+    assert set(bench.PHASE_LAUNCHES) == set(bench.PHASE_KERNELS)

@@ -1,7 +1,7 @@
 """Parity in the launch configuration that bench.py times: the ResNet-18-shaped stack at full
 size, every (layer, kind) pair of the step, the whole transformation as ONE grouped launch, the
-forward pass of each kind with one shared workspace, each phase captured into a HIP graph on a
-side stream and replayed.  Every transformed buffer and every output of the second replay is
+forward pass of each kind as ONE grouped call (nnv_conv_forward_grouped) with one shared
+workspace, each phase captured into a HIP graph on a side stream and replayed.  Every transformed buffer and every output of the second replay is
 compared with the oracle; between the replays all destinations are overwritten, so a replay
 that did no work cannot pass."""
 import numpy as np
@@ -31,18 +31,19 @@ def test_step_as_timed_matches_oracle():
         for kind in bench.applicable_kinds(nnv, layer):
             pairs.append(bench.Pair(nnv, torch, layer, kind, wd, xd, dev))
     assert len(pairs) == 66
-    ws = torch.empty(max(max(p.ws_bytes for p in pairs), 256), dtype=torch.uint8, device=dev)
     descs, kinds = [p.desc for p in pairs], [p.kind for p in pairs]
     srcs, dsts = [p.w_raw for p in pairs], [p.w_tx for p in pairs]
     step_kinds = (nnv.DIRECT, nnv.IM2COL_GEMM, nnv.WINO_F2, nnv.WINO_F4)
+    by_kind = {k: [p for p in pairs if p.kind == k] for k in step_kinds}
+    need = max(nnv.nnv_conv_forward_grouped_workspace_bytes([p.desc for p in sel], [p.kind for p in sel])
+               for sel in by_kind.values())
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
 
     def transform_all():
         nnv.nnv_transform_weights_grouped(descs, kinds, srcs, dsts)
 
     def forward_kind(kind):
-        for p in pairs:
-            if p.kind == kind:
-                nnv.nnv_conv_forward(p.desc, p.kind, p.x, p.w_tx, None, p.y, ws, ws.numel())
+        bench.grouped_forward(nnv, by_kind[kind], ws)
 
     def scramble():
         for p in pairs:
