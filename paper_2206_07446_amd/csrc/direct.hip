@@ -7,6 +7,7 @@
 // scalar loads, and x is read along W (coalesced).  depthwise: HBM-bound, one thread per
 // output pixel of one channel plane, taps of the channel (3x3 or 5x5) from the packed
 // [C/32][taps][32] layout.
+#include <algorithm>
 #include <climits>
 #include <type_traits>
 #include "nnv_internal.h"
@@ -334,11 +335,13 @@ struct DirectTable {
 };
 static_assert(sizeof(DirectTable) <= 4096, "the table is passed by value as the kernel argument");
 typedef const __attribute__((address_space(4))) DirectTable *DirectTablePtr;
-constexpr int kDirectManyWaves = 4;
+// A launch runs workgroups of 4 or 16 wavefronts (the wavefronts of a workgroup split the input
+// channels): deep layers have few blocks with long channel loops and need the wider split.
 
 template <typename T>
-__global__ __launch_bounds__(64 * kDirectManyWaves) void direct_conv_many_kernel(const DirectTable tbl_arg) {
-    __shared__ __align__(16) float lds[kDirectManyWaves * 8 * 64];
+__global__ __launch_bounds__(1024) void direct_conv_many_kernel(const DirectTable tbl_arg) {
+    extern __shared__ __align__(16) float lds[];      // waves x 8 outputs x 64 lanes
+    const int waves = blockDim.x >> 6;
     const DirectTablePtr tbl = (DirectTablePtr)__builtin_amdgcn_kernarg_segment_ptr();
     // groups of 8 consecutive blocks (neighbouring pixel or channel groups of a layer) go to one XCD
     const int i = blockIdx.x, xcd = i & 7, j = i >> 3;
@@ -362,14 +365,14 @@ __global__ __launch_bounds__(64 * kDirectManyWaves) void direct_conv_many_kernel
     T *y = static_cast<T *>(L.y);
     const int lblk = b - first;
     switch (L.variant) {
-        case 0: direct_slane_block<T, 4, 1>(x, L.w, L.bias, y, L.d, lblk, kDirectManyWaves, lds); break;
-        case 4: direct_slane_block<T, 8, 1>(x, L.w, L.bias, y, L.d, lblk, kDirectManyWaves, lds); break;
-        case 8: direct_slane_block<T, 4, 3>(x, L.w, L.bias, y, L.d, lblk, kDirectManyWaves, lds); break;
-        case 10: direct_slane_block<T, 4, 3, true>(x, L.w, L.bias, y, L.d, lblk, kDirectManyWaves, lds); break;
-        case 12: direct_slane_block<T, 8, 3>(x, L.w, L.bias, y, L.d, lblk, kDirectManyWaves, lds); break;
-        case 14: direct_slane_block<T, 8, 3, true>(x, L.w, L.bias, y, L.d, lblk, kDirectManyWaves, lds); break;
-        case 16: direct_slane_block<T, 4, 5>(x, L.w, L.bias, y, L.d, lblk, kDirectManyWaves, lds); break;
-        default: direct_slane_block<T, 4, 7>(x, L.w, L.bias, y, L.d, lblk, kDirectManyWaves, lds); break;
+        case 0: direct_slane_block<T, 4, 1>(x, L.w, L.bias, y, L.d, lblk, waves, lds); break;
+        case 4: direct_slane_block<T, 8, 1>(x, L.w, L.bias, y, L.d, lblk, waves, lds); break;
+        case 8: direct_slane_block<T, 4, 3>(x, L.w, L.bias, y, L.d, lblk, waves, lds); break;
+        case 10: direct_slane_block<T, 4, 3, true>(x, L.w, L.bias, y, L.d, lblk, waves, lds); break;
+        case 12: direct_slane_block<T, 8, 3>(x, L.w, L.bias, y, L.d, lblk, waves, lds); break;
+        case 14: direct_slane_block<T, 8, 3, true>(x, L.w, L.bias, y, L.d, lblk, waves, lds); break;
+        case 16: direct_slane_block<T, 4, 5>(x, L.w, L.bias, y, L.d, lblk, waves, lds); break;
+        default: direct_slane_block<T, 4, 7>(x, L.w, L.bias, y, L.d, lblk, waves, lds); break;
     }
 }
 
@@ -495,36 +498,50 @@ static hipError_t launch_direct_t(const Geo &g, const T *x, const float *w, cons
 
 bool direct_many_supported(const Geo &g) { return slane_supported(g); }
 
-// Layers [0, n) (one storage type, n <= kMaxDirectLayers, each direct_many_supported) in one launch.
+// Layers [0, n) (one storage type, n <= kMaxDirectLayers, each direct_many_supported): one launch
+// for the layers with up to 128 input channels (workgroups of 4 wavefronts) and one for the deeper
+// ones (16 wavefronts); within a launch the layers with the longest channel loops come first.
 hipError_t launch_direct_many(int n, const Geo *geos, const void *const *x, const void *const *w, const float *const *bias,
                               void *const *y, hipStream_t st_) {
     if (n <= 0) return hipSuccess;
     if (n > kMaxDirectLayers) return hipErrorInvalidValue;
     const bool half = geos[0].dtype == NNV_F16;
-    DirectTable tbl{};
-    long blocks = 0;
-    for (int i = 0; i < n; ++i) {
-        const Geo &g = geos[i];
-        if ((g.dtype == NNV_F16) != half || !slane_supported(g)) return hipErrorInvalidValue;
-        DirectLayer &L = tbl.layer[i];
-        L.x = x[i]; L.w = static_cast<const float *>(w[i]); L.bias = bias ? bias[i] : nullptr; L.y = y[i];
-        L.d = DirectParams{g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.sh, g.sw, g.ph, g.pw, g.p, g.q, g.cg, g.kg, 0, 0, 0, g.relu};
-        const bool grid8 = g.r == 3 && g.sh == 1 && g.sw == 1 && g.h <= 7 && g.w <= 7 && g.ph <= 1 && g.pw <= 1;
-        const int tk = (g.k % 8 == 0 && g.r <= 3) ? 8 : 4;      // the launch holds plenty of blocks: 8 outputs per loaded pixel
-        L.d.grid_nx = grid8 ? 1 : ceil_div(g.p * g.q, 64);
-        L.d.grid_ny = g.k / tk;
-        L.d.k_major = (size_t)g.k * g.c * g.r * g.s * 4 >= (size_t)g.c * g.h * g.w * (half ? 2 : 4);
-        const int fs_index = g.r == 1 ? 0 : g.r == 3 ? 1 : g.r == 5 ? 2 : 3;
-        L.variant = 8 * fs_index + 4 * (tk == 8) + 2 * (grid8 ? 1 : 0);
-        tbl.block0[i] = (int)blocks;
-        blocks += (long)L.d.grid_nx * L.d.grid_ny * g.n;
-        if (blocks >= (1L << 30)) return hipErrorInvalidValue;
+    for (int pass = 0; pass < 2; ++pass) {
+        const int waves = pass == 0 ? 16 : 4;
+        int order[kMaxDirectLayers], m = 0;
+        for (int i = 0; i < n; ++i) {
+            if ((geos[i].dtype == NNV_F16) != half || !slane_supported(geos[i])) return hipErrorInvalidValue;
+            if ((geos[i].c > 128) == (pass == 0)) order[m++] = i;
+        }
+        if (m == 0) continue;
+        std::stable_sort(order, order + m, [&](int a, int b) {
+            return (long)geos[a].c * geos[a].r * geos[a].s > (long)geos[b].c * geos[b].r * geos[b].s;
+        });
+        DirectTable tbl{};
+        long blocks = 0;
+        for (int o = 0; o < m; ++o) {
+            const Geo &g = geos[order[o]];
+            const int i = order[o];
+            DirectLayer &L = tbl.layer[o];
+            L.x = x[i]; L.w = static_cast<const float *>(w[i]); L.bias = bias ? bias[i] : nullptr; L.y = y[i];
+            L.d = DirectParams{g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.sh, g.sw, g.ph, g.pw, g.p, g.q, g.cg, g.kg, 0, 0, 0, g.relu};
+            const bool grid8 = g.r == 3 && g.sh == 1 && g.sw == 1 && g.h <= 7 && g.w <= 7 && g.ph <= 1 && g.pw <= 1;
+            const int tk = (g.k % 8 == 0 && g.r <= 3) ? 8 : 4;      // the launch holds plenty of blocks: 8 outputs per loaded pixel
+            L.d.grid_nx = grid8 ? 1 : ceil_div(g.p * g.q, 64);
+            L.d.grid_ny = g.k / tk;
+            L.d.k_major = (size_t)g.k * g.c * g.r * g.s * 4 >= (size_t)g.c * g.h * g.w * (half ? 2 : 4);
+            const int fs_index = g.r == 1 ? 0 : g.r == 3 ? 1 : g.r == 5 ? 2 : 3;
+            L.variant = 8 * fs_index + 4 * (tk == 8) + 2 * (grid8 ? 1 : 0);
+            tbl.block0[o] = (int)blocks;
+            blocks += (long)L.d.grid_nx * L.d.grid_ny * g.n;
+            if (blocks >= (1L << 30)) return hipErrorInvalidValue;
+        }
+        for (int o = m; o < kMaxDirectLayers; ++o) tbl.block0[o] = INT_MAX;
+        tbl.nblocks = (int)blocks;
+        const int per_xcd = ceil_div(ceil_div((int)blocks, 8), 8) * 8;
+        if (half) hipLaunchKernelGGL(direct_conv_many_kernel<__half>, dim3(per_xcd * 8), dim3(64 * waves), (size_t)waves * 8 * 64 * sizeof(float), st_, tbl);
+        else hipLaunchKernelGGL(direct_conv_many_kernel<float>, dim3(per_xcd * 8), dim3(64 * waves), (size_t)waves * 8 * 64 * sizeof(float), st_, tbl);
     }
-    for (int i = n; i < kMaxDirectLayers; ++i) tbl.block0[i] = INT_MAX;
-    tbl.nblocks = (int)blocks;
-    const int per_xcd = ceil_div(ceil_div((int)blocks, 8), 8) * 8;
-    if (half) hipLaunchKernelGGL(direct_conv_many_kernel<__half>, dim3(per_xcd * 8), dim3(64 * kDirectManyWaves), 0, st_, tbl);
-    else hipLaunchKernelGGL(direct_conv_many_kernel<float>, dim3(per_xcd * 8), dim3(64 * kDirectManyWaves), 0, st_, tbl);
     return hipGetLastError();
 }
 

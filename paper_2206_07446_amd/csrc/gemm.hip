@@ -669,8 +669,10 @@ __device__ __forceinline__ void load_item_layer(GemmItemLayer &dst, const GemmIt
     for (int i = 0; i < (int)(sizeof(GemmItemLayer) / 4); ++i) d[i] = src[i];
 }
 
+constexpr int kItemWaves = 4;      // items per workgroup (one wavefront each)
+
 template <bool HALF, int NBUF = 2>
-__global__ __launch_bounds__(64, 3) void gemm_items_kernel(const GemmItemTable tbl_arg) {
+__global__ __launch_bounds__(64 * kItemWaves, 3) void gemm_items_kernel(const GemmItemTable tbl_arg) {
     const GemmItemTablePtr tbl = (GemmItemTablePtr)__builtin_amdgcn_kernarg_segment_ptr();
     // Workgroup i runs on XCD i % 8.  Groups of `group` consecutive items (neighbouring tiles of
     // one layer: they share a weight panel) are dealt to the XCDs in turn, so every XCD sees the
@@ -679,9 +681,13 @@ __global__ __launch_bounds__(64, 3) void gemm_items_kernel(const GemmItemTable t
     // its SIMD, which always have an instruction ready: without a higher priority it is served
     // last and takes several microseconds.  The k-loop drops back to the default priority.
     __builtin_amdgcn_s_setprio(3);
+    // The wavefronts of a workgroup take consecutive items (neighbouring tiles along the pixels:
+    // the same weight fragments at about the same time, so three of four reads of them hit in
+    // the CU's L1); they share nothing else and never wait for one another.
     const int G = tbl->group;
     const int i = blockIdx.x, xcd = i & 7, j = i >> 3;
-    const int item = ((j / G) * 8 + xcd) * G + j % G;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int item = (((j / G) * 8 + xcd) * G + j % G) * kItemWaves + wave;
     if (item >= tbl->nitems) return;
     int li = 0, first = 0;
 #pragma unroll
@@ -692,7 +698,7 @@ __global__ __launch_bounds__(64, 3) void gemm_items_kernel(const GemmItemTable t
     GemmItemLayer L;
     load_item_layer(L, tbl, li);                     // one batch of scalar loads
     const int local = item - first;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63;
     if (L.tm == 4) {
         if constexpr (!HALF) {
             if (L.mode == 3) gemm_item<false, 4, 3, NBUF>(L, local, lane);
@@ -1034,11 +1040,12 @@ hipError_t launch_im2col_items(int n, const Geo *geos, const void *const *x, con
     for (int i = n; i < kMaxGemmLayers; ++i) tbl.item0[i] = tbl.red0[i] = INT_MAX;
     tbl.nlayers = n;
     tbl.nitems = items;
-    tbl.group = 8;
+    tbl.group = 2;       // workgroups (of kItemWaves items) handed to one XCD in a row
     tbl.nred = red;
-    const int per_xcd = ceil_div(ceil_div(items, tbl.group), 8) * tbl.group;
-    if (half) hipLaunchKernelGGL(gemm_items_kernel<true>, dim3(per_xcd * 8), dim3(64), 0, st, tbl);
-    else hipLaunchKernelGGL(gemm_items_kernel<false>, dim3(per_xcd * 8), dim3(64), 0, st, tbl);
+    const int wgs = ceil_div(items, kItemWaves);
+    const int per_xcd = ceil_div(ceil_div(wgs, tbl.group), 8) * tbl.group;
+    if (half) hipLaunchKernelGGL(gemm_items_kernel<true>, dim3(per_xcd * 8), dim3(64 * kItemWaves), 0, st, tbl);
+    else hipLaunchKernelGGL(gemm_items_kernel<false>, dim3(per_xcd * 8), dim3(64 * kItemWaves), 0, st, tbl);
     if (red > 0) hipLaunchKernelGGL(gemm_reduce_kernel, dim3(red), dim3(256), 0, st, tbl);
     return hipGetLastError();
 }

@@ -46,9 +46,11 @@ struct TransformJob {
     int block0;      // first block of this job in the launch
     int nblocks;
 };
-constexpr int kMaxJobs = 64;   // 64 jobs of 56 bytes: the table still fits the 4 KB of kernel arguments
+constexpr int kMaxJobs = 64;   // 64 jobs of 56 bytes + 64 block offsets: the table still fits the 4 KB of kernel arguments
 struct JobTable {
     TransformJob job[kMaxJobs];
+    int first_block[kMaxJobs];   // job[j].block0 again, INT_MAX beyond the last job: a block finds its job by
+                                 // counting the entries it has reached (no chain of dependent loads)
     int njobs;
 };
 static_assert(sizeof(JobTable) <= 4096, "the job table is passed by value as the kernel argument");

@@ -10,6 +10,7 @@
 //     wavefront store is one contiguous 256 B .. 1 KB piece of the output fragment.
 // One launch can carry many layers (a job table passed by value as kernel argument),
 // because single layers of a batch-1 CNN are far too small to fill 256 CUs.
+#include <climits>
 #include "nnv_internal.h"
 #include "wino_consts.h"
 
@@ -59,40 +60,16 @@ typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
 typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 template <typename V> __device__ static inline void nt_store(V *p, V v) { __builtin_nontemporal_store(v, p); }
 
-// U = G g G^T for one 3x3 filter held in registers.
-template <int SET>
-__device__ static inline void wino_u(const float g[9], float u[WinoMat<SET>::A * WinoMat<SET>::A]) {
-    using W = WinoMat<SET>;
-    constexpr int A = W::A;
-    float t[A][3];
-#pragma unroll
-    for (int a = 0; a < A; ++a)
-#pragma unroll
-        for (int s = 0; s < 3; ++s) {
-            float acc = 0.f;
-#pragma unroll
-            for (int r = 0; r < 3; ++r)
-                if (W::G[a][r] != 0.f) acc += W::G[a][r] * g[r * 3 + s];
-            t[a][s] = acc;
-        }
-#pragma unroll
-    for (int a = 0; a < A; ++a)
-#pragma unroll
-        for (int b = 0; b < A; ++b) {
-            float acc = 0.f;
-#pragma unroll
-            for (int s = 0; s < 3; ++s)
-                if (W::G[b][s] != 0.f) acc += t[a][s] * W::G[b][s];
-            u[a * A + b] = acc;
-        }
-}
-
 __device__ static inline uint32_t pack_half2(float a, float b) {
     __half2 h = __floats2half2_rn(a, b);
     return *reinterpret_cast<uint32_t *>(&h);
 }
 
-// Winograd weight transformation of one block: 16 output channels x up to 64 channels.
+// Channels per block of a Winograd job: 32 in float32 (21 KB of LDS per block, seven blocks per CU;
+// measured 4 % faster than 64), 64 in float16 (a wavefront packs 8 channels per lane pair).
+__host__ __device__ constexpr int wino_chunk(bool half) { return half ? 64 : 32; }
+
+// Winograd weight transformation of one block: 16 output channels x up to wino_chunk channels.
 template <int SET, bool HALF>
 __device__ static inline void wino_block(const TransformJob &job, int local_block, float *lds) {
     using W = WinoMat<SET>;
@@ -100,57 +77,93 @@ __device__ static inline void wino_block(const TransformJob &job, int local_bloc
     const int kb = local_block / job.nchunks, chunk = local_block % job.nchunks;
     const int K16 = (job.K + 15) / 16;
     const int cpad = HALF ? ((job.C + 31) / 32) * 32 : ((job.C + 3) / 4) * 4;
-    const int c0 = chunk * 64;
-    const int cfill = min(64, cpad - c0);
-    const int cvalid = max(0, min(64, job.C - c0));
-    const int ROW = lds_row_stride(64 * 9);
+    constexpr int CH = wino_chunk(HALF);
+    const int c0 = chunk * CH;
+    const int cfill = min(CH, cpad - c0);
+    const int cvalid = max(0, min(CH, job.C - c0));
+    const int ROW = lds_row_stride(CH * 9);
     stage_rows(job.src, lds, ROW, kb * 16, job.K, (size_t)job.C * 9, (size_t)c0 * 9, cvalid * 9, cfill * 9);
     if (!HALF) {
         float *dst = static_cast<float *>(job.dst);
         const int k_in = threadIdx.x & 15, csub = threadIdx.x >> 4;
 #pragma unroll 1
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < CH / 16; ++j) {
             const int cl = j * 16 + csub;
             if (cl >= cfill) break;
-            float g[9], u[AA];
+            float g[9];
 #pragma unroll
             for (int i = 0; i < 9; ++i) g[i] = lds[k_in * ROW + cl * 9 + i];
-            wino_u<SET>(g, u);
+            // U = G g G^T one row at a time, each row stored as soon as it exists: one live output
+            // pointer and one row of values instead of alpha^2 of each keeps the registers low
+            // (16-byte stores by threads that own four filters were measured too: slower)
             float *o = dst + ((size_t)kb * cpad + c0 + cl) * 16 + k_in;
             const size_t xi_stride = (size_t)K16 * cpad * 16;
 #pragma unroll
-            for (int xi = 0; xi < AA; ++xi) nt_store(&o[xi * xi_stride], u[xi]);
+            for (int a = 0; a < W::A; ++a) {
+                float t[3];
+#pragma unroll
+                for (int s2 = 0; s2 < 3; ++s2) {
+                    float acc = 0.f;
+#pragma unroll
+                    for (int r = 0; r < 3; ++r)
+                        if (W::G[a][r] != 0.f) acc += W::G[a][r] * g[r * 3 + s2];
+                    t[s2] = acc;
+                }
+#pragma unroll
+                for (int b = 0; b < W::A; ++b) {
+                    float acc = 0.f;
+#pragma unroll
+                    for (int s2 = 0; s2 < 3; ++s2)
+                        if (W::G[b][s2] != 0.f) acc += t[s2] * W::G[b][s2];
+                    nt_store(o, acc);
+                    o += xi_stride;
+                }
+            }
         }
     } else {
         __half *dst = static_cast<__half *>(job.dst);
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
         const int oct = wave * 2 + (lane >> 5), hq = lane & 1, k_in = (lane >> 1) & 15;
         if (oct * 8 < cfill) {
-            uint32_t lo[AA], hi[AA];
+            // four filters per thread (channels cl .. cl + 3 of its 8-channel lane pair), U row by row
+            float g[4][9];
+            const int cl = oct * 8 + hq * 4;
 #pragma unroll
-            for (int pr = 0; pr < 2; ++pr) {
-                float g0[9], g1[9], u0[AA], u1[AA];
-                const int cl = oct * 8 + hq * 4 + pr * 2;
+            for (int f = 0; f < 4; ++f)
 #pragma unroll
-                for (int i = 0; i < 9; ++i) {
-                    g0[i] = lds[k_in * ROW + cl * 9 + i];
-                    g1[i] = lds[k_in * ROW + (cl + 1) * 9 + i];
-                }
-                wino_u<SET>(g0, u0);
-                wino_u<SET>(g1, u1);
-#pragma unroll
-                for (int xi = 0; xi < AA; ++xi) {
-                    const uint32_t v = pack_half2(u0[xi], u1[xi]);
-                    if (pr == 0) lo[xi] = v; else hi[xi] = v;
-                }
-            }
+                for (int i = 0; i < 9; ++i) g[f][i] = lds[k_in * ROW + (cl + f) * 9 + i];
             const int cabs = c0 + oct * 8;
             const int c32n = cpad / 32;
             __half *o = dst + ((size_t)kb * c32n + cabs / 32) * 512 + ((cabs % 32) / 8) * 128 + k_in * 8 + hq * 4;
             const size_t xi_stride = (size_t)K16 * c32n * 512;
 #pragma unroll
-            for (int xi = 0; xi < AA; ++xi)
-                nt_store(reinterpret_cast<uint2v *>(o + xi * xi_stride), uint2v{lo[xi], hi[xi]});
+            for (int a = 0; a < W::A; ++a) {
+                float t[4][3];
+#pragma unroll
+                for (int f = 0; f < 4; ++f)
+#pragma unroll
+                    for (int s2 = 0; s2 < 3; ++s2) {
+                        float acc = 0.f;
+#pragma unroll
+                        for (int r = 0; r < 3; ++r)
+                            if (W::G[a][r] != 0.f) acc += W::G[a][r] * g[f][r * 3 + s2];
+                        t[f][s2] = acc;
+                    }
+#pragma unroll
+                for (int b = 0; b < W::A; ++b) {
+                    float u[4];
+#pragma unroll
+                    for (int f = 0; f < 4; ++f) {
+                        float acc = 0.f;
+#pragma unroll
+                        for (int s2 = 0; s2 < 3; ++s2)
+                            if (W::G[b][s2] != 0.f) acc += t[f][s2] * W::G[b][s2];
+                        u[f] = acc;
+                    }
+                    nt_store(reinterpret_cast<uint2v *>(o), uint2v{pack_half2(u[0], u[1]), pack_half2(u[2], u[3])});
+                    o += xi_stride;
+                }
+            }
         }
     }
 }
@@ -215,13 +228,26 @@ __device__ static inline void dw_block(const TransformJob &job, int local_block)
 // F6: the launch holds F(6x6) jobs.  Their 64 outputs per filter take more registers than
 // any other job, so launches without them run an instantiation that leaves that branch out
 // and keeps four wavefronts per SIMD.
+// The table is read through the kernel-argument segment pointer (constant address space, scalar
+// loads); a block's job is found by counting, the job's record is loaded in one batch.
+typedef const __attribute__((address_space(4))) JobTable *JobTablePtr;
+
 template <bool F6>
-__global__ __launch_bounds__(256) void transform_kernel(const JobTable tbl) {
+__global__ __launch_bounds__(256) void transform_kernel(const JobTable tbl_arg) {
     extern __shared__ __align__(16) float lds[];
+    const JobTablePtr tbl = (JobTablePtr)__builtin_amdgcn_kernarg_segment_ptr();
     const int b = blockIdx.x;
     int j = 0;
-    while (j + 1 < tbl.njobs && tbl.job[j + 1].block0 <= b) ++j;
-    const TransformJob &job = tbl.job[j];
+#pragma unroll
+    for (int l = 1; l < kMaxJobs; ++l) j += b >= tbl->first_block[l] ? 1 : 0;
+    TransformJob job;
+    {
+        static_assert(sizeof(TransformJob) % 4 == 0, "copied word by word");
+        const __attribute__((address_space(4))) uint32_t *src = (const __attribute__((address_space(4))) uint32_t *)&tbl->job[j];
+        uint32_t *dst = reinterpret_cast<uint32_t *>(&job);
+#pragma unroll
+        for (int k = 0; k < (int)(sizeof(TransformJob) / 4); ++k) dst[k] = src[k];
+    }
     const int lb = b - job.block0;
     if (job.type == JOB_WINO) {
         if (job.wset == WS_F2) {
@@ -256,8 +282,8 @@ int fill_transform_job(const Geo &g, int kind, const float *src, void *dst, Tran
         job->type = JOB_WINO;
         job->wset = wino_set(kind, g.dtype);
         const int cpad = job->half ? ceil_div(g.cg, 32) * 32 : ceil_div(g.cg, 4) * 4;
-        job->cchunk = 64;
-        job->nchunks = ceil_div(cpad, 64);
+        job->cchunk = wino_chunk(job->half);
+        job->nchunks = ceil_div(cpad, job->cchunk);
         job->nblocks = k16 * job->nchunks;
     } else if (kind == NNV_IM2COL_GEMM) {
         job->type = JOB_GEMM;
@@ -285,7 +311,7 @@ int fill_transform_job(const Geo &g, int kind, const float *src, void *dst, Tran
 }
 
 size_t transform_job_lds_bytes(const TransformJob &job) {
-    if (job.type == JOB_WINO) return (size_t)kRows * lds_row_stride(64 * 9) * sizeof(float);
+    if (job.type == JOB_WINO) return (size_t)kRows * lds_row_stride(wino_chunk(job.half) * 9) * sizeof(float);
     if (job.type == JOB_GEMM) {
         const int cpad = job.half ? ceil_div(job.C, 32) * 32 : ceil_div(job.C, 4) * 4;
         const int cc = job.cchunk < cpad ? job.cchunk : cpad;
@@ -294,8 +320,10 @@ size_t transform_job_lds_bytes(const TransformJob &job) {
     return 0;
 }
 
-hipError_t launch_transform_jobs(const JobTable &tbl, int total_blocks, size_t lds, hipStream_t st) {
+hipError_t launch_transform_jobs(const JobTable &table, int total_blocks, size_t lds, hipStream_t st) {
     if (total_blocks <= 0) return hipSuccess;
+    JobTable tbl = table;
+    for (int j = 0; j < kMaxJobs; ++j) tbl.first_block[j] = j < tbl.njobs ? tbl.job[j].block0 : INT_MAX;
     bool f6 = false;
     for (int j = 0; j < tbl.njobs; ++j) f6 = f6 || (tbl.job[j].type == JOB_WINO && tbl.job[j].wset == WS_F6);
     if (lds > 64 * 1024) {
