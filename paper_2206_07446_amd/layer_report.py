@@ -101,6 +101,44 @@ def counter_pass(stack_name: str, half: bool):
             print(f"{i:02d} {layer.name} {KIND_NAMES[kind]}", flush=True)
 
 
+def grouped_pass(stack_name: str, half: bool):
+    """The whole stack through nnv_conv_forward_grouped, one call per kind that runs any of its
+    layers, three times eagerly, nothing timed: the program to put under
+    `rocprofv3 --kernel-trace --stats` or `--pmc <counter> --kernel-trace` when the kernels of
+    the grouped launches are wanted (work items of all layers in one launch)."""
+    import torch
+    from nnv_workloads import stack, layer_tensors
+    from . import binding as nnv
+    dev = torch.device("cuda:0")
+    dtype = nnv.F16 if half else nnv.F32
+    per_kind = {}
+    for i, layer in enumerate(stack(stack_name)):
+        desc = nnv.make_desc(layer, dtype)
+        w, x = layer_tensors(layer, 220607446 + i)
+        wd, xd = torch.from_numpy(w).to(dev), torch.from_numpy(x).to(dev)
+        if half:
+            xd = xd.half()
+        for kind in range(6):
+            if not nnv.nnv_kind_supported(desc, kind):
+                continue
+            wt = wd if kind == nnv.DIRECT else torch.empty(nnv.nnv_transformed_bytes(desc, kind), dtype=torch.uint8, device=dev)
+            y = torch.empty(layer.n * layer.k * layer.p * layer.q, dtype=xd.dtype, device=dev)
+            per_kind.setdefault(kind, []).append((layer, desc, wd, wt, xd, y))
+    for kind, sel in per_kind.items():
+        descs, kinds = [s[1] for s in sel], [kind] * len(sel)
+        nnv.nnv_transform_weights_grouped(descs, kinds, [s[2] for s in sel], [s[3] for s in sel])
+        need = nnv.nnv_conv_forward_grouped_workspace_bytes(descs, kinds)
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+        for _ in range(3):
+            nnv.nnv_conv_forward_grouped(descs, kinds, [s[4] for s in sel], [s[3] for s in sel], None, [s[5] for s in sel], ws, need)
+        torch.cuda.synchronize()
+        esz = 2 if half else 4
+        act = sum(esz * (l.n * l.c * l.h * l.w + l.n * l.k * l.p * l.q) for l, *_ in sel)
+        wbytes = sum(nnv.nnv_transformed_bytes(d, kind) for _, d, *_ in sel)
+        print(f"{KIND_NAMES[kind]}: {len(sel)} layers, {sum(2.0 * l.macs for l, *_ in sel) / 1e9:.3f} GFLOP direct-equivalent, "
+              f"activations {act / 1e6:.1f} MB + weights {wbytes / 1e6:.1f} MB", flush=True)
+
+
 def summary(half: bool):
     """One line per workload: layers, GMAC, and per kind the summed forward time of the layers it
     can run (and how many), then the sum over layers of the fastest kind of each."""
@@ -125,9 +163,14 @@ def main():
     ap.add_argument("--stack", default="resnet18")
     ap.add_argument("--half", action="store_true")
     ap.add_argument("--summary", action="store_true", help="totals of every workload instead of one per-layer table")
+    ap.add_argument("--grouped-pass", action="store_true",
+                    help="run the stack through nnv_conv_forward_grouped, one call per kind, three times (for rocprofv3)")
     ap.add_argument("--counter-pass", action="store_true",
                     help="run every (layer, kind) three times eagerly, nothing timed (for rocprofv3 --pmc)")
     args = ap.parse_args()
+    if args.grouped_pass:
+        grouped_pass(args.stack, args.half)
+        return
     if args.counter_pass:
         counter_pass(args.stack, args.half)
         return
