@@ -190,7 +190,7 @@ __device__ __forceinline__ void direct_slane_block(const T *__restrict__ x, cons
     constexpr int ESZ = sizeof(T);
     constexpr int RS = FS * FS;
     const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wave = CS == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // CS == 1: the wavefront works alone, wherever it sits in the workgroup
     const int PQ = d.P * d.Q, HW = d.H * d.W;
     const int img = lblk / (d.grid_nx * d.grid_ny), l2 = lblk - img * (d.grid_nx * d.grid_ny);
     const int bx = d.k_major ? l2 % d.grid_nx : l2 / d.grid_ny;
@@ -318,6 +318,185 @@ __global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__rest
     direct_slane_block<T, TK, FS, GRID8>(x, w, bias, y, d, lblk, blockDim.x >> 6, lds);
 }
 
+// ---- 3x3 stride-1 pad-1 float32 layers with the lanes along the output channels
+//
+// lane = output channel (64 per wavefront), tile = TR = 2 output rows x TW columns held as TR * TW
+// accumulators per lane (one-row tiles were measured: too few FMAs per scalar row load).  The two operands swap roles against the
+// kernel above: a lane's taps
+// (9 consecutive floats per input channel in OIHW, 36 for a group of four channels) come by
+// 16-byte vector loads that stream each filter from HBM once per tile, and the input pixels,
+// which every lane needs alike, come through the scalar cache as FMA scalar operands (4 rows x
+// (TW + 2) columns per channel).  Per channel that is 18 * TW FMAs for 9 vector dwords and 4
+// scalar row loads, against 72 FMAs for 9 vector and 16 scalar loads above, and a tap is used
+// 2 * TW times once it is in a register.  Zero padding: columns outside the row are left out
+// at compile time (the tile variants LE / RE know whether they touch the left / right edge),
+// rows outside the plane are read from a row of zeros.  A scalar load cannot be waited for
+// without waiting for every scalar load issued after it, so the order is pinned: the row two
+// stages ahead is requested right after the wait for the current row, and has the FMAs of two
+// rows to arrive.  Two other ways of feeding the pixels were measured and dropped: held once per
+// quad of lanes and broadcast by a DPP operand on the FMA (DPP FMAs run at about half rate),
+// and staged in LDS and read back as broadcasts (10 % slower at full occupancy, no faster at low).
+// The cs wavefronts of a tile split the channels; partial sums meet in LDS, one output row of
+// the tile per pass, in a fixed order.
+constexpr int kKlWaves = 8;                 // wavefronts per workgroup
+__device__ const float kl_zero_row[16] = {};
+
+struct KLaneLayer {
+    const float *x, *w, *bias;
+    float *y;
+    int N, C, H, W, K;
+    int tw;       // tile width: 14, or 7 for 7-wide planes (W is a multiple of it)
+    int nseg;     // W / tw
+    int ntile;    // nseg * ceil(H / 2)
+    int cs;       // wavefronts per tile (1, 2, 4 or 8): each takes C / cs channels, a multiple of 4
+    int wgt;      // workgroups per (image, block of 64 output channels) = ceil(ntile / (8 / cs))
+    int relu;
+};
+// tile geometry of a layer (the same arithmetic sizes the launch on the host and places a workgroup on the device)
+__host__ __device__ static inline void klane_geometry(KLaneLayer &L) {
+    L.tw = L.W == 7 ? 7 : 14;
+    L.nseg = L.W / L.tw;
+    L.ntile = L.nseg * ((L.H + 1) / 2);
+    int cs = L.C >= 128 ? 8 : 4;
+    while (cs > 1 && L.C % (4 * cs) != 0) cs >>= 1;
+    L.cs = cs;
+    L.wgt = (L.ntile + kKlWaves / cs - 1) / (kKlWaves / cs);
+}
+__host__ __device__ static inline int klane_blocks(const KLaneLayer &L) { return L.wgt * (L.K / 64) * L.N; }
+typedef const __attribute__((address_space(4))) float *KlConstPtr;
+typedef float kl_f4 __attribute__((ext_vector_type(4)));
+
+// taps of the four channels c .. c + 3 (36 floats per lane)
+__device__ __forceinline__ void klane_load_taps(__amdgpu_buffer_rsrc_t wres, uint32_t voff, uint32_t c, kl_f4 (&t)[9]) {
+#pragma unroll
+    for (int i = 0; i < 9; ++i)
+        t[i] = __builtin_bit_cast(kl_f4, __builtin_amdgcn_raw_buffer_load_b128(wres, voff + i * 16, c * 36u, 0));
+}
+
+template <int TW, int TR, bool LE, bool RE>
+__device__ __forceinline__ void klane_accumulate(const KLaneLayer &L, const int img, const int kb, const int p0, const int q0,
+                                                 const int cw, const int lane, float (&acc)[TR * TW]) {
+    constexpr int NR = TR + 2;                                   // patch rows
+    constexpr int NCOL = TW + 2;                                 // patch columns, the first one left of the tile
+    constexpr int NL = NCOL - (LE ? 1 : 0) - (RE ? 1 : 0);       // pixels read per patch row
+    const int HW = L.H * L.W;
+    const __amdgpu_buffer_rsrc_t wres = make_rsrc(L.w, (uint32_t)((size_t)L.K * L.C * 36));
+    const uint32_t voff = (uint32_t)(kb * 64 + lane) * (uint32_t)L.C * 36u;
+    // the patch rows: first pixel read, and the step from one channel to the next (0 for the zero row)
+    KlConstPtr row[NR];
+    uint32_t step[NR];
+    const float *ximg = L.x + (size_t)img * L.C * HW;
+#pragma unroll
+    for (int pr = 0; pr < NR; ++pr) {
+        const int ih = p0 - 1 + pr;
+        const bool ok = ih >= 0 && ih < L.H;
+        row[pr] = ok ? (KlConstPtr)(uintptr_t)(ximg + (size_t)ih * L.W + q0 - (LE ? 0 : 1)) : (KlConstPtr)(uintptr_t)kl_zero_row;
+        step[pr] = ok ? (uint32_t)HW : 0u;
+    }
+    // this wavefront's channels: [cbeg, cbeg + per), per a multiple of 4
+    const uint32_t per = (uint32_t)(L.C / L.cs), cbeg = (uint32_t)cw * per, cendx = cbeg + per;
+    auto load_row = [&](float (&R)[NL], int pr, uint32_t c) __attribute__((always_inline)) {
+        const KlConstPtr xr = row[pr] + (size_t)c * step[pr];
+#pragma unroll
+        for (int i = 0; i < NL; ++i) R[i] = xr[i];
+    };
+    kl_f4 cur[9], nxt[9];
+    klane_load_taps(wres, voff, cbeg, cur);
+    float R[NR][NL];
+    load_row(R[0], 0, cbeg);
+    load_row(R[1], 1, cbeg);
+    for (uint32_t c4 = cbeg; c4 < cendx; c4 += 4) {
+        // the next group's taps travel while this group is computed (the last group re-reads
+        // itself: the scalar offset is not part of the buffer range check, so it must stay inside)
+        klane_load_taps(wres, voff, c4 + 4 < cendx ? c4 + 4 : c4, nxt);
+        float t[36];
+#pragma unroll
+        for (int i = 0; i < 9; ++i) {
+            t[4 * i] = cur[i].x; t[4 * i + 1] = cur[i].y; t[4 * i + 2] = cur[i].z; t[4 * i + 3] = cur[i].w;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t c = c4 + j;
+#pragma unroll
+            for (int pr = 0; pr < NR; ++pr) {
+                // stage: first use of row pr (the wait for it lands here), then the request for the
+                // row two stages ahead, then the rest of row pr
+                bool first = true;
+#pragma unroll
+                for (int r = 0; r < TR; ++r) {
+                    const int dr = pr - r;
+                    if (dr < 0 || dr > 2) continue;
+#pragma unroll
+                    for (int q = 0; q < TW; ++q)
+#pragma unroll
+                        for (int ds = 0; ds < 3; ++ds) {
+                            const int col = q + ds;          // patch column, 0 .. NCOL - 1
+                            if ((LE && col == 0) || (RE && col == NCOL - 1)) continue;
+                            acc[r * TW + q] = fmaf(R[pr][col - (LE ? 1 : 0)], t[j * 9 + dr * 3 + ds], acc[r * TW + q]);
+                            if (first) {
+                                first = false;
+                                __builtin_amdgcn_sched_barrier(0);
+                                // the row two stages on: of this channel, or of the next one (the last channel
+                                // of the wavefront requests its own rows again: in range, never used)
+                                if (pr + 2 < NR) load_row(R[pr + 2], pr + 2, c);
+                                else load_row(R[pr + 2 - NR], pr + 2 - NR, c + 1 < cendx ? c + 1 : c);
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                        }
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 9; ++i) cur[i] = nxt[i];
+    }
+}
+
+template <int TW, int TR>
+__device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, float *lds) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int KB = L.K >> 6;
+    const int tg = lblk % L.wgt, rest = lblk / L.wgt;
+    const int kb = rest % KB, img = rest / KB;
+    const int tile = tg * (kKlWaves / L.cs) + wave / L.cs;
+    const int cw = wave % L.cs, w0 = wave - cw;
+    const bool live = tile < L.ntile;
+    const int rp = tile / L.nseg, seg = tile - rp * L.nseg;
+    const int p0 = rp * TR, q0 = seg * TW;
+    float acc[TR * TW];
+#pragma unroll
+    for (int i = 0; i < TR * TW; ++i) acc[i] = 0.f;
+    if (live) {
+        const bool le = seg == 0, re = seg == L.nseg - 1;
+        if (TW == 7 || (le && re)) klane_accumulate<TW, TR, true, true>(L, img, kb, p0, q0, cw, lane, acc);
+        else if (le) klane_accumulate<TW, TR, true, false>(L, img, kb, p0, q0, cw, lane, acc);
+        else if (re) klane_accumulate<TW, TR, false, true>(L, img, kb, p0, q0, cw, lane, acc);
+        else klane_accumulate<TW, TR, false, false>(L, img, kb, p0, q0, cw, lane, acc);
+    }
+    // Sum over the cs wavefronts of the tile and store, one output row of the tile per pass.  Every
+    // wavefront leaves its row as lds[(wave * TW + q) * 65 + lane]; then the tile's wavefronts share its
+    // 64 x TW outputs with the columns running fastest over the lanes, so that a store covers runs of
+    // TW consecutive floats of y instead of 64 separate rows (row stride 65: the transposed reads
+    // spread over the banks).  Fixed summation order.
+    const size_t ybase = ((size_t)img * L.K + (size_t)kb * 64) * L.H * L.W;
+#pragma unroll
+    for (int r = 0; r < TR; ++r) {
+#pragma unroll
+        for (int q = 0; q < TW; ++q) lds[(wave * TW + q) * 65 + lane] = acc[r * TW + q];
+        __syncthreads();
+        if (live && p0 + r < L.H) {
+            for (int o = cw * 64 + lane; o < 64 * TW; o += L.cs * 64) {
+                const int k = o / TW, q = o - k * TW;
+                float v = 0.f;
+                for (int ws = 0; ws < L.cs; ++ws) v += lds[((w0 + ws) * TW + q) * 65 + k];
+                const float b = L.bias ? L.bias[kb * 64 + k] : 0.f;
+                L.y[ybase + ((size_t)k * L.H + p0 + r) * L.W + q0 + q] = act(v + b, L.relu);
+            }
+        }
+        __syncthreads();
+    }
+}
+
 // ---- many direct-convolution layers (groups 1, square 1x1 / 3x3 / 5x5 / 7x7 filter) in one launch
 // of four-wavefront workgroups: a workgroup finds its layer by counting the entries of a prefix
 // array it has reached and then runs that layer's block.
@@ -326,7 +505,7 @@ struct DirectLayer {
     const float *w, *bias;
     void *y;
     DirectParams d;
-    int variant;        // 8 * (index of the filter size in {1, 3, 5, 7}) + 4 * (8 channels per lane) + 2 * (lane grid) ; see below
+    int variant;        // 8 * (index of the filter size in {1, 3, 5, 7}) + 4 * (8 channels per lane) + 2 * (lane grid), + 32: a block per wavefront; 64: output-channel lanes
 };
 struct DirectTable {
     DirectLayer layer[kMaxDirectLayers];
@@ -338,9 +517,10 @@ typedef const __attribute__((address_space(4))) DirectTable *DirectTablePtr;
 // A launch runs workgroups of 4 or 16 wavefronts (the wavefronts of a workgroup split the input
 // channels): deep layers have few blocks with long channel loops and need the wider split.
 
-template <typename T>
+// KL: the launch may hold output-channel-lane layers (float32 only; they need more registers)
+template <typename T, bool KL>
 __global__ __launch_bounds__(1024) void direct_conv_many_kernel(const DirectTable tbl_arg) {
-    extern __shared__ __align__(16) float lds[];      // waves x 8 outputs x 64 lanes
+    extern __shared__ __align__(16) float lds[];      // waves x 8 outputs x 64 lanes; kKlWaves x 14 x 65 with output-channel-lane layers
     const int waves = blockDim.x >> 6;
     const DirectTablePtr tbl = (DirectTablePtr)__builtin_amdgcn_kernarg_segment_ptr();
     // groups of 8 consecutive blocks (neighbouring pixel or channel groups of a layer) go to one XCD
@@ -363,16 +543,32 @@ __global__ __launch_bounds__(1024) void direct_conv_many_kernel(const DirectTabl
     }
     const T *x = static_cast<const T *>(L.x);
     T *y = static_cast<T *>(L.y);
-    const int lblk = b - first;
-    switch (L.variant) {
-        case 0: direct_slane_block<T, 4, 1>(x, L.w, L.bias, y, L.d, lblk, waves, lds); break;
-        case 4: direct_slane_block<T, 8, 1>(x, L.w, L.bias, y, L.d, lblk, waves, lds); break;
-        case 8: direct_slane_block<T, 4, 3>(x, L.w, L.bias, y, L.d, lblk, waves, lds); break;
-        case 10: direct_slane_block<T, 4, 3, true>(x, L.w, L.bias, y, L.d, lblk, waves, lds); break;
-        case 12: direct_slane_block<T, 8, 3>(x, L.w, L.bias, y, L.d, lblk, waves, lds); break;
-        case 14: direct_slane_block<T, 8, 3, true>(x, L.w, L.bias, y, L.d, lblk, waves, lds); break;
-        case 16: direct_slane_block<T, 4, 5>(x, L.w, L.bias, y, L.d, lblk, waves, lds); break;
-        default: direct_slane_block<T, 4, 7>(x, L.w, L.bias, y, L.d, lblk, waves, lds); break;
+    int lblk = b - first;
+    int cs = waves;
+    if (L.variant & 32) {
+        // a layer with fewer input channels than wavefronts: nothing to split, every wavefront takes a block of its own
+        lblk = lblk * waves + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        cs = 1;
+        if (lblk >= L.d.grid_nx * L.d.grid_ny * L.d.N) return;
+    }
+    if constexpr (KL) {
+        if (L.variant == 64) {       // launched with kKlWaves wavefronts per workgroup
+            KLaneLayer K{x, L.w, L.bias, y, L.d.N, L.d.C, L.d.H, L.d.W, L.d.K, 0, 0, 0, 0, 0, L.d.relu};
+            klane_geometry(K);
+            if (K.tw == 7) klane_tile<7, 2>(K, lblk, lds);
+            else klane_tile<14, 2>(K, lblk, lds);
+            return;
+        }
+    }
+    switch (L.variant & 31) {
+        case 0: direct_slane_block<T, 4, 1>(x, L.w, L.bias, y, L.d, lblk, cs, lds); break;
+        case 4: direct_slane_block<T, 8, 1>(x, L.w, L.bias, y, L.d, lblk, cs, lds); break;
+        case 8: direct_slane_block<T, 4, 3>(x, L.w, L.bias, y, L.d, lblk, cs, lds); break;
+        case 10: direct_slane_block<T, 4, 3, true>(x, L.w, L.bias, y, L.d, lblk, cs, lds); break;
+        case 12: direct_slane_block<T, 8, 3>(x, L.w, L.bias, y, L.d, lblk, cs, lds); break;
+        case 14: direct_slane_block<T, 8, 3, true>(x, L.w, L.bias, y, L.d, lblk, cs, lds); break;
+        case 16: direct_slane_block<T, 4, 5>(x, L.w, L.bias, y, L.d, lblk, cs, lds); break;
+        default: direct_slane_block<T, 4, 7>(x, L.w, L.bias, y, L.d, lblk, cs, lds); break;
     }
 }
 
@@ -498,49 +694,96 @@ static hipError_t launch_direct_t(const Geo &g, const T *x, const float *w, cons
 
 bool direct_many_supported(const Geo &g) { return slane_supported(g); }
 
-// Layers [0, n) (one storage type, n <= kMaxDirectLayers, each direct_many_supported): one launch
-// for the layers with up to 128 input channels (workgroups of 4 wavefronts) and one for the deeper
-// ones (16 wavefronts); within a launch the layers with the longest channel loops come first.
+// float32, groups 1, 3x3, stride 1, pad 1, K a multiple of 64, C a multiple of 4, rows of 7 or a multiple of 14 pixels
+// (stride 2 with one-row tiles was measured too: 21 FMAs per scalar row load, such wavefronts mostly wait)
+static bool klane_supported(const Geo &g) {
+    return g.dtype == NNV_F32 && g.groups == 1 && g.r == 3 && g.s == 3 && g.sh == 1 && g.sw == 1 && g.ph == 1 && g.pw == 1 &&
+           g.k % 64 == 0 && g.c % 4 == 0 && (g.w == 7 || g.w % 14 == 0);
+}
+static KLaneLayer klane_layer(const Geo &g) {
+    KLaneLayer K{nullptr, nullptr, nullptr, nullptr, g.n, g.c, g.h, g.w, g.k, 0, 0, 0, 0, 0, 0};
+    klane_geometry(K);
+    return K;
+}
+
+// Layers [0, n) (one storage type, n <= kMaxDirectLayers, each direct_many_supported): one launch of
+// 8-wavefront workgroups for the layers the output-channel-lane kernel covers, one of 16-wavefront
+// workgroups for the deep ones among the others (the wavefronts of a workgroup split the input
+// channels: a deep layer is a chain of scalar-load round trips per wavefront, the wide split
+// shortens it) and one of 4-wavefront workgroups for the rest.  Within a launch the longest
+// wavefronts come first.  (All three in one launch, dealt out alternately, was measured: slower.)
 hipError_t launch_direct_many(int n, const Geo *geos, const void *const *x, const void *const *w, const float *const *bias,
                               void *const *y, hipStream_t st_) {
     if (n <= 0) return hipSuccess;
     if (n > kMaxDirectLayers) return hipErrorInvalidValue;
     const bool half = geos[0].dtype == NNV_F16;
-    for (int pass = 0; pass < 2; ++pass) {
-        const int waves = pass == 0 ? 16 : 4;
+    bool any_klane = false;
+    for (int i = 0; i < n; ++i) {
+        if ((geos[i].dtype == NNV_F16) != half || !slane_supported(geos[i])) return hipErrorInvalidValue;
+        any_klane = any_klane || klane_supported(geos[i]);
+    }
+    // pass 0 / 1: workgroups of 16 / 4 wavefronts; pass 2: output-channel-lane layers, 8 wavefronts
+    for (int pass = 0; pass < 3; ++pass) {
+        const int waves = pass == 0 ? 16 : pass == 1 ? 4 : kKlWaves;
         int order[kMaxDirectLayers], m = 0;
+        long weight[kMaxDirectLayers];        // sort key: about the FMAs of one wavefront
         for (int i = 0; i < n; ++i) {
-            if ((geos[i].dtype == NNV_F16) != half || !slane_supported(geos[i])) return hipErrorInvalidValue;
-            if ((geos[i].c > 128) == (pass == 0)) order[m++] = i;
+            const Geo &g = geos[i];
+            int p;
+            if (klane_supported(g)) p = 2;
+            else if (any_klane) p = g.c >= 64 ? 0 : 1;      // what is left are few layers of short work: the wide channel split shortens their chains
+            else p = g.c > 128 ? 0 : 1;
+            if (p != pass) continue;
+            order[m++] = i;
+            if (klane_supported(g)) {
+                const KLaneLayer K = klane_layer(g);
+                weight[i] = (long)(g.c / K.cs) * K.tw * 18;
+            } else {
+                weight[i] = (long)ceil_div(g.c, waves) * g.r * g.s * 8;
+            }
         }
         if (m == 0) continue;
-        std::stable_sort(order, order + m, [&](int a, int b) {
-            return (long)geos[a].c * geos[a].r * geos[a].s > (long)geos[b].c * geos[b].r * geos[b].s;
-        });
+        std::stable_sort(order, order + m, [&](int a, int b) { return weight[a] > weight[b]; });
         DirectTable tbl{};
         long blocks = 0;
+        bool klane_in_launch = false;
         for (int o = 0; o < m; ++o) {
             const Geo &g = geos[order[o]];
             const int i = order[o];
             DirectLayer &L = tbl.layer[o];
             L.x = x[i]; L.w = static_cast<const float *>(w[i]); L.bias = bias ? bias[i] : nullptr; L.y = y[i];
             L.d = DirectParams{g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.sh, g.sw, g.ph, g.pw, g.p, g.q, g.cg, g.kg, 0, 0, 0, g.relu};
-            const bool grid8 = g.r == 3 && g.sh == 1 && g.sw == 1 && g.h <= 7 && g.w <= 7 && g.ph <= 1 && g.pw <= 1;
-            const int tk = (g.k % 8 == 0 && g.r <= 3) ? 8 : 4;      // the launch holds plenty of blocks: 8 outputs per loaded pixel
-            L.d.grid_nx = grid8 ? 1 : ceil_div(g.p * g.q, 64);
-            L.d.grid_ny = g.k / tk;
-            L.d.k_major = (size_t)g.k * g.c * g.r * g.s * 4 >= (size_t)g.c * g.h * g.w * (half ? 2 : 4);
-            const int fs_index = g.r == 1 ? 0 : g.r == 3 ? 1 : g.r == 5 ? 2 : 3;
-            L.variant = 8 * fs_index + 4 * (tk == 8) + 2 * (grid8 ? 1 : 0);
             tbl.block0[o] = (int)blocks;
-            blocks += (long)L.d.grid_nx * L.d.grid_ny * g.n;
+            if (pass == 2 && klane_supported(g)) {
+                const KLaneLayer K = klane_layer(g);
+                L.variant = 64;
+                blocks += klane_blocks(K);
+                klane_in_launch = true;
+            } else {
+                const bool grid8 = g.r == 3 && g.sh == 1 && g.sw == 1 && g.h <= 7 && g.w <= 7 && g.ph <= 1 && g.pw <= 1;
+                const int tk = (g.k % 8 == 0 && g.r <= 3) ? 8 : 4;      // the launch holds plenty of blocks: 8 outputs per loaded pixel
+                L.d.grid_nx = grid8 ? 1 : ceil_div(g.p * g.q, 64);
+                L.d.grid_ny = g.k / tk;
+                L.d.k_major = (size_t)g.k * g.c * g.r * g.s * 4 >= (size_t)g.c * g.h * g.w * (half ? 2 : 4);
+                const int fs_index = g.r == 1 ? 0 : g.r == 3 ? 1 : g.r == 5 ? 2 : 3;
+                L.variant = 8 * fs_index + 4 * (tk == 8) + 2 * (grid8 ? 1 : 0);
+                const long lb = (long)L.d.grid_nx * L.d.grid_ny * g.n;
+                if (g.c < waves) {
+                    L.variant |= 32;
+                    blocks += (lb + waves - 1) / waves;
+                } else {
+                    blocks += lb;
+                }
+            }
             if (blocks >= (1L << 30)) return hipErrorInvalidValue;
         }
         for (int o = m; o < kMaxDirectLayers; ++o) tbl.block0[o] = INT_MAX;
         tbl.nblocks = (int)blocks;
         const int per_xcd = ceil_div(ceil_div((int)blocks, 8), 8) * 8;
-        if (half) hipLaunchKernelGGL(direct_conv_many_kernel<__half>, dim3(per_xcd * 8), dim3(64 * waves), (size_t)waves * 8 * 64 * sizeof(float), st_, tbl);
-        else hipLaunchKernelGGL(direct_conv_many_kernel<float>, dim3(per_xcd * 8), dim3(64 * waves), (size_t)waves * 8 * 64 * sizeof(float), st_, tbl);
+        const size_t lds = klane_in_launch ? (size_t)kKlWaves * 14 * 65 * sizeof(float) : (size_t)waves * 8 * 64 * sizeof(float);
+        if (half) hipLaunchKernelGGL((direct_conv_many_kernel<__half, false>), dim3(per_xcd * 8), dim3(64 * waves), lds, st_, tbl);
+        else if (klane_in_launch) hipLaunchKernelGGL((direct_conv_many_kernel<float, true>), dim3(per_xcd * 8), dim3(64 * waves), lds, st_, tbl);
+        else hipLaunchKernelGGL((direct_conv_many_kernel<float, false>), dim3(per_xcd * 8), dim3(64 * waves), lds, st_, tbl);
     }
     return hipGetLastError();
 }

@@ -260,6 +260,33 @@ def test_direct_and_depthwise_layers_in_one_call(env, half):
         assert np.abs(a - b).max() <= (2e-3 if half else 2e-5) * np.abs(b).max(), c.layer.name
 
 
+# float32 3x3 stride-1 pad-1 layers with K a multiple of 64, C a multiple of 4 and rows of 7 or 14 n pixels
+# run with the lanes along the output channels: tiles of 2 rows x 7 or 14 columns
+KLANE = [
+    Ly("kl_w7", 8, 7, 7, 64, 3, 1, 1),                       # 7-wide tiles, last row pair half empty
+    Ly("kl_w14", 12, 14, 14, 64, 3, 1, 1),                   # one tile per row pair: both edges in it
+    Ly("kl_w28", 16, 6, 28, 128, 3, 1, 1),                   # a left and a right tile, two blocks of output channels
+    Ly("kl_w42", 4, 5, 42, 64, 3, 1, 1),                     # left, middle and right tiles; one channel group, odd H
+    Ly("kl_deep", 256, 7, 7, 64, 3, 1, 1),                   # eight wavefronts per tile
+    Ly("kl_c132", 132, 3, 14, 64, 3, 1, 1),                  # 33 channel groups over 8 wavefronts
+    Ly("kl_h1", 4, 1, 14, 64, 3, 1, 1),
+    Ly("kl_n2", 8, 7, 14, 128, 3, 1, 1, n=2),
+    Ly("kl_w56", 64, 4, 56, 64, 3, 1, 1),
+    Ly("other_s2_w28", 16, 10, 28, 128, 3, 2, 1),
+    Ly("other_s2_deep", 256, 14, 14, 64, 3, 2, 1),           # the deep ones of the others: 16-wavefront workgroups
+    Ly("other_s2", 16, 15, 15, 32, 3, 2, 1),                 # not covered: the pixel-lane kernel in the same call
+    Ly("other_w15", 8, 9, 15, 64, 3, 1, 1),
+    Ly("other_c6", 6, 14, 14, 64, 3, 1, 1),
+]
+
+
+def test_direct_output_channel_lanes(env):
+    nnv, torch = env
+    cases = [Case(nnv, torch, l, nnv.DIRECT, False, 1700 + i, bias=(i % 2 == 0)) for i, l in enumerate(KLANE)]
+    run_grouped(nnv, torch, cases)
+    run_grouped(nnv, torch, cases, relu=True)
+
+
 @pytest.mark.parametrize("name,kind", [("resnet18", 0), ("mobilenetv2", 0), ("mobilenetv2", 4), ("efficientnet_b0", 4)])
 def test_full_stacks_direct_and_depthwise(env, name, kind):
     nnv, torch = env
