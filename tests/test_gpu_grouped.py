@@ -302,7 +302,8 @@ def test_graph_replay(env):
     dev = torch.device("cuda:0")
     cases = [Case(nnv, torch, l, nnv.IM2COL_GEMM, False, 1200 + i) for i, l in enumerate(SMALL[:16])]
     cases += [Case(nnv, torch, l, nnv.WINO_F4, False, 1250 + i) for i, l in enumerate(WINO_SMALL[:8])]
-    cases += [Case(nnv, torch, l, nnv.DIRECT, False, 1270 + i) for i, l in enumerate(DIRECT_DW[:12])]
+    # direct layers of all three launch classes
+    cases += [Case(nnv, torch, l, nnv.DIRECT, False, 1270 + i) for i, l in enumerate(DIRECT_DW[:12] + KLANE[:6])]
     cases += [Case(nnv, torch, l, nnv.DEPTHWISE, False, 1290 + i) for i, l in enumerate(DIRECT_DW) if l.is_depthwise]
     descs, kinds = [c.desc for c in cases], [c.kind for c in cases]
     need = nnv.nnv_conv_forward_grouped_workspace_bytes(descs, kinds)
