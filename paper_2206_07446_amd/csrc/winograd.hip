@@ -362,14 +362,16 @@ __global__ __launch_bounds__(256) void wino_output_kernel(const WinoParams w) {
 // tile GEMMs, output transforms of all of them), for the same reason as the implicit GEMM's
 // work-item launch: a batch-1 layer fills neither the chip nor the time its launch takes.
 // A workgroup finds its layer by counting the entries of a prefix array it has reached.
+constexpr int kWinoItemWaves = 4;
 struct WinoTable {
     WinoParams layer[kMaxWinoLayers];
     int in0[kMaxWinoLayers];      // first workgroup of each layer: input transform,
-    int gemm0[kMaxWinoLayers];    //   tile GEMM (work items: frequency x tile),
+    int gemm0[kMaxWinoLayers];    //   tile GEMM (workgroups of work items: frequency x tile),
     int out0[kMaxWinoLayers];     //   output transform; INT_MAX beyond the last layer
     int in_by[kMaxWinoLayers], out_by[kMaxWinoLayers];     // channel groups per tile block (the "y" extent of the single launches)
     int tm[kMaxWinoLayers], tn[kMaxWinoLayers];            // tile of the GEMM items
     int n_in, n_gemm, n_out;
+    int gemm_waves;               // wavefronts per tile-GEMM workgroup: 1 or kWinoItemWaves
 };
 static_assert(sizeof(WinoTable) <= 4096, "the table is passed by value as the kernel argument");
 typedef const __attribute__((address_space(4))) WinoTable *WinoTablePtr;
@@ -411,29 +413,37 @@ __global__ __launch_bounds__(256) void wino_output_many_kernel(const WinoTable t
     wino_output_block<SET, HALF>(w, local / by_n, local % by_n, 256);
 }
 
-// Tile GEMM work items: one wavefront per (frequency, tile); no split of the channel steps (the
-// alpha^2 frequencies already give thousands of items).  Items of a layer are ordered frequency
-// slowest; groups of 8 consecutive items go to one XCD.
+// Tile GEMM work items (frequency x tile).  A launch of many items runs one item per one-wavefront
+// workgroup.  A launch of few items uses workgroups of kWinoItemWaves wavefronts, and a layer with
+// many channel steps gives each item to 2 or 4 of them that split the steps (summed through LDS in
+// a fixed order): a lone wavefront streams its U panel at the pace of the few loads it keeps in
+// flight, and the 128-step items of a 512-channel layer took 35 us each, as long as the rest of
+// the launch; the wavefronts of a workgroup otherwise take consecutive items.  Items of a layer
+// are ordered frequency slowest; groups of 8 consecutive workgroups go to one XCD.
 template <bool HALF>
-__global__ __launch_bounds__(64) void wino_gemm_many_kernel(const WinoTable tbl_arg) {
+__global__ __launch_bounds__(64 * kWinoItemWaves) void wino_gemm_many_kernel(const WinoTable tbl_arg) {
+    extern __shared__ __align__(16) float red[];      // kWinoItemWaves x 16 accumulator registers x 64 lanes
     const WinoTablePtr tbl = (WinoTablePtr)__builtin_amdgcn_kernarg_segment_ptr();
     constexpr int G = 8;
     const int i = blockIdx.x, xcd = i & 7, j = i >> 3;
-    const int item = ((j / G) * 8 + xcd) * G + j % G;
-    if (item >= tbl->n_gemm) return;
-    NNV_FIND_LAYER(gemm0, item, li, first)
+    const int wg = ((j / G) * 8 + xcd) * G + j % G;
+    if (wg >= tbl->n_gemm) return;
+    NNV_FIND_LAYER(gemm0, wg, li, first)
     WinoParams w;
     load_wino_layer(w, tbl, li);
-    const int local = item - first;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int KS = 1 << w.ks_shift, ks = wave & (KS - 1), nt = wave >> w.ks_shift;
+    const int local = (wg - first) * ((int)(blockDim.x >> 6) >> w.ks_shift) + nt;
     const int tm = tbl->tm[li], tn = tbl->tn[li];
     const int per_xi = w.gemm_wgs_per_xi;                 // tiles per frequency
-    const int xi = local / per_xi, tile = local - xi * per_xi;
-    const int kbt = tile / w.ntb, tbt = tile - kbt * w.ntb;
-    const int lane = threadIdx.x;
+    const bool surplus = local >= per_xi * w.alpha2;      // the last workgroup of a layer may hold fewer items
+    const int xi = surplus ? 0 : local / per_xi, tile = local - xi * per_xi;
+    const int kbt = surplus ? w.K16 : tile / w.ntb, tbt = surplus ? 0 : tile - kbt * w.ntb;   // kb0 >= K16: nothing loaded, nothing stored
     constexpr int D = HALF ? 2 : 8;
-    if (tm == 2 && tn == 2) wino_gemm_tile<HALF, 2, 2, D>(w, xi, kbt * 2, tbt * 2, 0, 1, 0, 0, lane, nullptr);
-    else if (tm == 2) wino_gemm_tile<HALF, 2, 1, D>(w, xi, kbt * 2, tbt, 0, 1, 0, 0, lane, nullptr);
-    else wino_gemm_tile<HALF, 1, 1, D>(w, xi, kbt, tbt, 0, 1, 0, 0, lane, nullptr);
+    if (tm == 2 && tn == 2) wino_gemm_tile<HALF, 2, 2, D>(w, xi, kbt * 2, tbt * 2, ks, KS, w.ks_shift, nt, lane, red);
+    else if (tm == 2) wino_gemm_tile<HALF, 2, 1, D>(w, xi, kbt * 2, tbt, ks, KS, w.ks_shift, nt, lane, red);
+    else wino_gemm_tile<HALF, 1, 1, D>(w, xi, kbt, tbt, ks, KS, w.ks_shift, nt, lane, red);
 }
 
 // ---- fused variant (float32, F(2x2) and F(4x4)): all three steps in one kernel, no workspace.
@@ -714,7 +724,8 @@ template <int SET, bool HALF>
 static void launch_wino_many_t(const WinoTable &tbl, hipStream_t st) {
     hipLaunchKernelGGL((wino_input_many_kernel<SET, HALF>), dim3(tbl.n_in), dim3(256), 0, st, tbl);
     const int per_xcd = ceil_div(ceil_div(tbl.n_gemm, 8), 8) * 8;
-    hipLaunchKernelGGL((wino_gemm_many_kernel<HALF>), dim3(per_xcd * 8), dim3(64), 0, st, tbl);
+    hipLaunchKernelGGL((wino_gemm_many_kernel<HALF>), dim3(per_xcd * 8), dim3(64 * tbl.gemm_waves),
+                       (size_t)tbl.gemm_waves * 16 * 64 * sizeof(float), st, tbl);
     hipLaunchKernelGGL((wino_output_many_kernel<SET, HALF>), dim3(tbl.n_out), dim3(256), 0, st, tbl);
 }
 
@@ -727,6 +738,16 @@ hipError_t launch_wino_many(int n, const Geo *geos, int kind, const void *const 
     const bool half = geos[0].dtype == NNV_F16;
     WinoTable tbl{};
     long n_in = 0, n_gemm = 0, n_out = 0;
+    // a launch of few items (less than two rounds of the chip's wavefront slots) ends with its longest
+    // items: there the items of layers with many channel steps are split over 2 or 4 wavefronts
+    long items = 0;
+    for (int i = 0; i < n; ++i) {
+        const WinoPlan p = plan_wino(geos[i], kind);
+        const int tm = p.K16 >= 2 ? 2 : 1, tn = (tm == 2 && p.T16 >= 2) ? 2 : 1;
+        items += (long)p.alpha * p.alpha * ceil_div(p.K16, tm) * ceil_div(p.T16, tn);
+    }
+    const bool split = items < 8192;
+    tbl.gemm_waves = split ? kWinoItemWaves : 1;
     for (int i = 0; i < n; ++i) {
         const Geo &g = geos[i];
         if ((g.dtype == NNV_F16) != half || !wino_many_supported(g, kind)) return hipErrorInvalidValue;
@@ -735,7 +756,8 @@ hipError_t launch_wino_many(int n, const Geo *geos, int kind, const void *const 
         w = wino_params(g, p, x[i], U[i], bias ? bias[i] : nullptr, y[i], ws[i]);
         // tile of a GEMM item: as large as the layer allows (the launch holds thousands of items)
         const int tm = p.K16 >= 2 ? 2 : 1, tn = (tm == 2 && p.T16 >= 2) ? 2 : 1;
-        w.ks_shift = 0;
+        // then at most about 32 channel steps per wavefront
+        w.ks_shift = !split ? 0 : p.csteps > 64 ? 2 : p.csteps > 32 ? 1 : 0;
         w.ntb = ceil_div(p.T16, tn);
         w.gemm_wgs_per_xi = ceil_div(p.K16, tm) * w.ntb;
         tbl.tm[i] = tm; tbl.tn[i] = tn;
@@ -743,7 +765,7 @@ hipError_t launch_wino_many(int n, const Geo *geos, int kind, const void *const 
         tbl.out_by[i] = p.K16;
         tbl.in0[i] = (int)n_in; tbl.gemm0[i] = (int)n_gemm; tbl.out0[i] = (int)n_out;
         n_in += (long)p.T16 * tbl.in_by[i];
-        n_gemm += (long)w.alpha2 * w.gemm_wgs_per_xi;
+        n_gemm += ceil_div(w.alpha2 * w.gemm_wgs_per_xi, tbl.gemm_waves >> w.ks_shift);
         n_out += (long)p.T16 * tbl.out_by[i];
         if (n_in >= (1L << 30) || n_gemm >= (1L << 30) || n_out >= (1L << 30)) return hipErrorInvalidValue;
     }
