@@ -272,6 +272,8 @@ KLANE = [
     Ly("kl_h1", 4, 1, 14, 64, 3, 1, 1),
     Ly("kl_n2", 8, 7, 14, 128, 3, 1, 1, n=2),
     Ly("kl_w56", 64, 4, 56, 64, 3, 1, 1),
+    Ly("other_stem28", 3, 28, 28, 64, 7, 2, 3),              # thin layers: a block per wavefront
+    Ly("other_stem42", 3, 12, 42, 128, 7, 2, 3, n=2),
     Ly("other_s2_w28", 16, 10, 28, 128, 3, 2, 1),
     Ly("other_s2_deep", 256, 14, 14, 64, 3, 2, 1),           # the deep ones of the others: 16-wavefront workgroups
     Ly("other_s2", 16, 15, 15, 32, 3, 2, 1),                 # not covered: the pixel-lane kernel in the same call
