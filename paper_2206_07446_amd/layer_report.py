@@ -139,6 +139,67 @@ def grouped_pass(stack_name: str, half: bool):
               f"activations {act / 1e6:.1f} MB + weights {wbytes / 1e6:.1f} MB", flush=True)
 
 
+def grouped_summary(half: bool):
+    """One line per workload: per kind the time of one nnv_conv_forward_grouped call over the layers
+    that kind can run (and how many).  Timed as the median of 10 replays of a HIP graph holding
+    5 calls back to back (the host side of a call with dozens of layers takes longer than the GPU)."""
+    import torch
+    from nnv_workloads import STACK_NAMES, stack, layer_tensors
+    from . import binding as nnv
+    dev = torch.device("cuda:0")
+    dtype = nnv.F16 if half else nnv.F32
+    kinds = [KIND_NAMES[k] for k in sorted(KIND_NAMES)]
+    print("| stack | layers | GMAC | " + " | ".join(f"{k} us (layers)" for k in kinds) + " |")
+    print("|---|---:|---:|" + "---:|" * len(kinds))
+    for name in STACK_NAMES:
+        per_kind = {}
+        layers = stack(name)
+        for i, layer in enumerate(layers):
+            desc = nnv.make_desc(layer, dtype)
+            w, x = layer_tensors(layer, 220607446 + i)
+            wd, xd = torch.from_numpy(w).to(dev), torch.from_numpy(x).to(dev)
+            if half:
+                xd = xd.half()
+            for kind in range(6):
+                if not nnv.nnv_kind_supported(desc, kind):
+                    continue
+                wt = wd if kind == nnv.DIRECT else torch.empty(nnv.nnv_transformed_bytes(desc, kind), dtype=torch.uint8, device=dev)
+                y = torch.empty(layer.n * layer.k * layer.p * layer.q, dtype=xd.dtype, device=dev)
+                per_kind.setdefault(kind, []).append((layer, desc, wd, wt, xd, y))
+        cells = {}
+        for kind, sel in per_kind.items():
+            descs, ks = [s[1] for s in sel], [kind] * len(sel)
+            nnv.nnv_transform_weights_grouped(descs, ks, [s[2] for s in sel], [s[3] for s in sel])
+            need = nnv.nnv_conv_forward_grouped_workspace_bytes(descs, ks)
+            ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+            args = (descs, ks, [s[4] for s in sel], [s[3] for s in sel], None, [s[5] for s in sel], ws, need)
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                for _ in range(2):
+                    nnv.nnv_conv_forward_grouped(*args)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                for _ in range(5):
+                    nnv.nnv_conv_forward_grouped(*args)
+            g.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ts = []
+            for _ in range(10):
+                e0.record()
+                g.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                ts.append(e0.elapsed_time(e1) * 1e3 / 5)
+            del g
+            cells[KIND_NAMES[kind]] = f"{sorted(ts)[len(ts) // 2]:.1f} ({len(sel)})"
+            del ws
+        print(f"| {name} | {len(layers)} | {sum(l.macs for l in layers) / 1e9:.3f} | " +
+              " | ".join(cells.get(k, "-") for k in kinds) + " |", flush=True)
+
+
 def summary(half: bool):
     """One line per workload: layers, GMAC, and per kind the summed forward time of the layers it
     can run (and how many), then the sum over layers of the fastest kind of each."""
@@ -163,11 +224,16 @@ def main():
     ap.add_argument("--stack", default="resnet18")
     ap.add_argument("--half", action="store_true")
     ap.add_argument("--summary", action="store_true", help="totals of every workload instead of one per-layer table")
+    ap.add_argument("--grouped-summary", action="store_true",
+                    help="per workload and kind the time of one nnv_conv_forward_grouped call")
     ap.add_argument("--grouped-pass", action="store_true",
                     help="run the stack through nnv_conv_forward_grouped, one call per kind, three times (for rocprofv3)")
     ap.add_argument("--counter-pass", action="store_true",
                     help="run every (layer, kind) three times eagerly, nothing timed (for rocprofv3 --pmc)")
     args = ap.parse_args()
+    if args.grouped_summary:
+        grouped_summary(args.half)
+        return
     if args.grouped_pass:
         grouped_pass(args.stack, args.half)
         return

@@ -1,9 +1,10 @@
 """Parity in the launch configuration that bench.py times: the ResNet-18-shaped stack at full
 size, every (layer, kind) pair of the step, the whole transformation as ONE grouped launch, the
 forward pass of each kind as ONE grouped call (nnv_conv_forward_grouped) with one shared
-workspace, each phase captured into a HIP graph on a side stream and replayed.  Every transformed buffer and every output of the second replay is
-compared with the oracle; between the replays all destinations are overwritten, so a replay
-that did no work cannot pass."""
+workspace, issued eagerly call after call as bench.py does.  Before that the five phases are also
+captured into HIP graphs and replayed twice.  All destinations are overwritten before every pass,
+so a pass that did no work cannot pass; every transformed buffer and every output of the last
+(eager) pass is compared with the oracle."""
 import numpy as np
 import pytest
 
@@ -71,6 +72,13 @@ def test_step_as_timed_matches_oracle():
         for g in graphs:
             g.replay()
         torch.cuda.synchronize()
+    assert all(torch.isfinite(p.y).all() for p in pairs), "a replayed phase left outputs unwritten"
+    scramble()
+    torch.cuda.synchronize()
+    transform_all()                      # the step as bench.py issues it
+    for kind in step_kinds:
+        forward_kind(kind)
+    torch.cuda.synchronize()
 
     refs = {}
     for p in pairs:
