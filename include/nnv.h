@@ -162,10 +162,13 @@ int nnv_conv_forward_relu(const nnv_conv_desc *desc, nnv_kind kind, const void *
  * launch of single-wavefront work items (output tile x range of the reduction) and one
  * reduction launch; Winograd layers of one kind and storage type share three launches (all
  * input transforms, all tile GEMMs, all output transforms), except those nnv_conv_forward
- * runs as one fused kernel; DEPTHWISE layers of one storage type share one launch, and so
- * do DIRECT layers with groups = 1 and a square 1x1, 3x3, 5x5 or 7x7 filter; the remaining
- * layers are executed one after the other as by nnv_conv_forward.  Results per layer are as nnv_conv_forward's up to the order of the
- * float32 summation over the channels (deterministic: fixed order).
+ * runs as one fused kernel; DEPTHWISE layers of one storage type share one launch; DIRECT
+ * layers with groups = 1 and a square 1x1, 3x3, 5x5 or 7x7 filter share up to three (one of
+ * them for float32 3x3 stride-1 layers with the lanes along the output channels).  The
+ * remaining layers, and the layers of a kind of which the call holds only one or two (three
+ * for IM2COL_GEMM: the shared launches are laid out to fill the GPU), are executed one after
+ * the other as by nnv_conv_forward.  Results per layer are as nnv_conv_forward's up to the
+ * order of the float32 summation over the channels (deterministic: fixed order).
  *   descs, kinds, x, w_tx, y : HOST arrays of length n_layers (descriptors, kinds, device
  *       pointers as for nnv_conv_forward); outputs must not overlap
  *   bias  : NULL, or a HOST array of n_layers device pointers (entries may be NULL)

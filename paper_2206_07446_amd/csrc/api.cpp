@@ -254,11 +254,16 @@ GroupedPlan plan_grouped(int n, const Geo *geos, const nnv_kind *kinds) {
     std::vector<char> taken(n, 0);
     // collect the layers that satisfy `pick` into batches of at most `cap`, each layer with a
     // workspace region of its own
-    auto collect = [&](int cls, int kind, int cap, auto pick, auto region_bytes) {
+    // A batch below `least` layers is given back (its layers then run by themselves): the many-layer
+    // kernels are laid out for launches that fill the chip - work items of 144 k-steps, tiles resident
+    // all at once - and one or two layers through them take 2-5 times as long as their own launches
+    // (measured: a 512-channel 7x7 layer 30 against 15 us through the item GEMM).
+    auto collect = [&](int cls, int kind, int cap, int least, auto pick, auto region_bytes) {
         GroupedPlan::Batch cur{cls, kind, {}, {}};
         size_t off = 0;
         auto close = [&]() {
-            if (!cur.layers.empty()) { gp.bytes = std::max(gp.bytes, off); gp.batches.push_back(cur); }
+            if ((int)cur.layers.size() >= least) { gp.bytes = std::max(gp.bytes, off); gp.batches.push_back(cur); }
+            else for (int i : cur.layers) taken[i] = 0;
             cur.layers.clear(); cur.offset.clear(); off = 0;
         };
         for (int i = 0; i < n; ++i) {
@@ -273,16 +278,16 @@ GroupedPlan plan_grouped(int n, const Geo *geos, const nnv_kind *kinds) {
     };
     for (int half = 0; half < 2; ++half) {
         auto same_type = [&](int i) { return (geos[i].dtype == NNV_F16) == (half == 1); };
-        collect(GroupedPlan::GEMM_ITEMS, NNV_IM2COL_GEMM, kMaxGemmLayers,
+        collect(GroupedPlan::GEMM_ITEMS, NNV_IM2COL_GEMM, kMaxGemmLayers, 4,
                 [&](int i) { return kinds[i] == NNV_IM2COL_GEMM && same_type(i); },
                 [&](int i) { return im2col_items_workspace_bytes(geos[i]); });
-        collect(GroupedPlan::DIRECT_MANY, NNV_DIRECT, kMaxDirectLayers,
+        collect(GroupedPlan::DIRECT_MANY, NNV_DIRECT, kMaxDirectLayers, 3,
                 [&](int i) { return kinds[i] == NNV_DIRECT && same_type(i) && direct_many_supported(geos[i]); },
                 [&](int) { return (size_t)0; });
-        collect(GroupedPlan::DW_MANY, NNV_DEPTHWISE, kMaxDwLayers,
+        collect(GroupedPlan::DW_MANY, NNV_DEPTHWISE, kMaxDwLayers, 2,
                 [&](int i) { return kinds[i] == NNV_DEPTHWISE && same_type(i); }, [&](int) { return (size_t)0; });
         for (int kind : {NNV_WINO_F2, NNV_WINO_F4, NNV_WINO_F6})
-            collect(GroupedPlan::WINO_MANY, kind, kMaxWinoLayers,
+            collect(GroupedPlan::WINO_MANY, kind, kMaxWinoLayers, 2,
                     [&](int i) { return kinds[i] == kind && same_type(i) && wino_many_supported(geos[i], kind); },
                     [&](int i) { return ws_bytes(geos[i], kind); });
     }

@@ -321,23 +321,22 @@ __global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__rest
 // ---- 3x3 stride-1 pad-1 float32 layers with the lanes along the output channels
 //
 // lane = output channel (64 per wavefront), tile = TR = 2 output rows x TW columns held as TR * TW
-// accumulators per lane (one-row tiles were measured: too few FMAs per scalar row load).  The two operands swap roles against the
-// kernel above: a lane's taps
-// (9 consecutive floats per input channel in OIHW, 36 for a group of four channels) come by
-// 16-byte vector loads that stream each filter from HBM once per tile, and the input pixels,
-// which every lane needs alike, come through the scalar cache as FMA scalar operands (4 rows x
-// (TW + 2) columns per channel).  Per channel that is 18 * TW FMAs for 9 vector dwords and 4
-// scalar row loads, against 72 FMAs for 9 vector and 16 scalar loads above, and a tap is used
-// 2 * TW times once it is in a register.  Zero padding: columns outside the row are left out
-// at compile time (the tile variants LE / RE know whether they touch the left / right edge),
-// rows outside the plane are read from a row of zeros.  A scalar load cannot be waited for
-// without waiting for every scalar load issued after it, so the order is pinned: the row two
-// stages ahead is requested right after the wait for the current row, and has the FMAs of two
-// rows to arrive.  Two other ways of feeding the pixels were measured and dropped: held once per
-// quad of lanes and broadcast by a DPP operand on the FMA (DPP FMAs run at about half rate),
-// and staged in LDS and read back as broadcasts (10 % slower at full occupancy, no faster at low).
-// The cs wavefronts of a tile split the channels; partial sums meet in LDS, one output row of
-// the tile per pass, in a fixed order.
+// accumulators per lane (one-row tiles were measured: too few FMAs per scalar row load).  The two
+// operands swap roles against the kernel above: a lane's taps (9 consecutive floats per input
+// channel in OIHW, 36 for a group of four channels) come by 16-byte vector loads that stream each
+// filter from HBM once per tile, and the input pixels, which every lane needs alike, come through
+// the scalar cache as FMA scalar operands (4 rows x (TW + 2) columns per channel).  Per channel
+// that is 18 * TW FMAs for 9 vector dwords and 4 scalar row loads, against 72 FMAs for 9 vector
+// and 16 scalar loads above, and a tap is used 2 * TW times once it is in a register.  Zero
+// padding: columns outside the row are left out at compile time (the tile variants LE / RE know
+// whether they touch the left / right edge), rows outside the plane are read from a row of zeros.
+// A scalar load cannot be waited for without waiting for every scalar load issued after it, so
+// the order is pinned: the row two stages ahead is requested right after the wait for the
+// current row, and has the FMAs of two rows to arrive.  Two other ways of feeding the pixels
+// were measured and dropped: held once per quad of lanes and broadcast by a DPP operand on the
+// FMA (DPP FMAs run at about half rate), and staged in LDS and read back as broadcasts (level at
+// full occupancy, slower at low).  The cs wavefronts of a tile split the channels; partial sums
+// meet in LDS, one output row of the tile per pass, in a fixed order.
 constexpr int kKlWaves = 8;                 // wavefronts per workgroup
 __device__ const float kl_zero_row[16] = {};
 

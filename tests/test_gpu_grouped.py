@@ -337,7 +337,8 @@ def test_graph_replay(env):
 def test_argument_errors(env):
     nnv, torch = env
     dev = torch.device("cuda:0")
-    cases = [Case(nnv, torch, l, nnv.IM2COL_GEMM, False, 1300 + i) for i, l in enumerate((SMALL[11], SMALL[1]))]
+    # four layers: enough for the work-item launch (fewer would run by themselves, without a workspace)
+    cases = [Case(nnv, torch, l, nnv.IM2COL_GEMM, False, 1300 + i) for i, l in enumerate((SMALL[11], SMALL[1], SMALL[2], SMALL[3]))]
     descs, kinds = [c.desc for c in cases], [c.kind for c in cases]
     xs, wts, ys = [c.xd for c in cases], [c.wt for c in cases], [c.y for c in cases]
     need = nnv.nnv_conv_forward_grouped_workspace_bytes(descs, kinds)
@@ -351,13 +352,13 @@ def test_argument_errors(env):
     assert e.value.status == -1
     ws = torch.empty(need, dtype=torch.uint8, device=dev)
     with pytest.raises(nnv.NnvError) as e:
-        nnv.nnv_conv_forward_grouped(descs, [nnv.DEPTHWISE, 1], xs, wts, None, ys, ws)
+        nnv.nnv_conv_forward_grouped(descs, [nnv.DEPTHWISE, 1, 1, 1], xs, wts, None, ys, ws)
     assert e.value.status == -3
     with pytest.raises(nnv.NnvError) as e:
         nnv.nnv_conv_forward_grouped(descs, kinds, xs, wts, None, ys, ws, flags=2)
     assert e.value.status == -7
     with pytest.raises(nnv.NnvError) as e:
-        nnv.nnv_conv_forward_grouped(descs, kinds, [xs[0], None], wts, None, ys, ws)
+        nnv.nnv_conv_forward_grouped(descs, kinds, [xs[0], None, xs[2], xs[3]], wts, None, ys, ws)
     assert e.value.status == -1
     torch.cuda.synchronize()
     for c in cases:                                     # nothing was launched by the refused calls
