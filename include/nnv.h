@@ -164,7 +164,8 @@ int nnv_conv_forward_relu(const nnv_conv_desc *desc, nnv_kind kind, const void *
  * input transforms, all tile GEMMs, all output transforms), except those nnv_conv_forward
  * runs as one fused kernel; DEPTHWISE layers of one storage type share one launch; DIRECT
  * layers with groups = 1 and a square 1x1, 3x3, 5x5 or 7x7 filter share up to three (one of
- * them for float32 3x3 stride-1 layers with the lanes along the output channels).  The
+ * them for the float32 layers that run with the lanes along the output channels: 3x3 at stride 1,
+ * 3x3 and 7x7 at stride 2).  The
  * remaining layers, and the layers of a kind of which the call holds only one or two (three
  * for IM2COL_GEMM: the shared launches are laid out to fill the GPU), are executed one after
  * the other as by nnv_conv_forward.  Results per layer are as nnv_conv_forward's up to the

@@ -496,6 +496,231 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
     }
 }
 
+// ---- 3x3 and 7x7 stride-2 float32 layers with the lanes along the output channels
+//
+// At stride 2 a loaded pixel feeds only 9/4 (3x3) or 49/4 (7x7) FMAs per output channel, so the
+// scalar cache cannot deliver the pixels fast enough (a scalar row load would pay for at most 36
+// FMAs), and with the lanes along the pixels the filters of a deep layer are a stream of scalar
+// cache misses, each used by one wavefront.  Here the taps are again per lane (3x3: 16-byte
+// vector loads of four channels' taps, as above; 7x7 with up to four input channels: the 64
+// filters of the workgroup staged once in LDS, row stride odd, and read back a channel at a
+// time) and the pixels come by vector loads with the lanes along the patch (NR rows of NPX
+// pixels, flattened over ceil(NR NPX / 64) loads per channel, zero outside the plane through the
+// range check of the buffer).  The wavefront writes the patch to an LDS slot of its own and reads
+// it back with uniform addresses, so that every lane receives the same pixels in vector
+// registers: the LDS pipe runs beside the vector ALU (16 such reads next to 48 FMAs cost nothing,
+// measured), and a wavefront's LDS operations complete in order, so there is no barrier in the
+// channel loop.  (Handing the pixels round with v_readlane was measured first: one v_readlane
+// costs the issue time of four FMAs, 83 against 88 us for the launch below.)  A tile is TR output
+// rows of TW pixels; cs wavefronts split the channels.  The same tile body instantiated for
+// stride 1 (TR = 2) runs as fast as the scalar-operand kernel above on a VGG-16-shaped stack and
+// 10 % slower on a ResNet-18-shaped one, so stride 1 stays with the kernel above.
+struct KStrideLayer {
+    const float *x, *w, *bias;
+    float *y;
+    int N, C, H, W, K, P, Q, ph, pw, fs, st;
+    int tw;       // tile width: 14, or 7 for a 3x3 layer whose Q is an odd multiple of 7 (the last tile of a row may be ragged)
+    int nseg;     // ceil(Q / tw)
+    int ntile;    // nseg * P
+    int cs;       // wavefronts per tile: 3x3: up to 8, each takes C / cs channels, a multiple of 4; 7x7: 1
+    int wgt;      // workgroups per (image, block of 64 output channels)
+    int ts;       // 7x7: row stride (floats) of the staged filters
+    int relu;
+};
+__host__ __device__ static inline void kstride_geometry(KStrideLayer &L) {
+    L.tw = (L.fs == 3 && L.Q % 7 == 0 && L.Q % 14 != 0) ? 7 : 14;
+    L.nseg = (L.Q + L.tw - 1) / L.tw;
+    L.ntile = L.nseg * (L.st == 1 ? (L.P + 1) / 2 : L.P);      // stride 1: two output rows per tile
+    int cs = 1;
+    if (L.fs == 3) {
+        cs = (L.st == 1 && L.C < 128) ? 4 : kKlWaves;
+        while (cs > 1 && L.C % (4 * cs) != 0) cs >>= 1;
+    }
+    L.cs = cs;
+    L.wgt = (L.ntile + kKlWaves / cs - 1) / (kKlWaves / cs);
+    L.ts = (L.C * 49) | 1;
+}
+__host__ __device__ static inline int kstride_blocks(const KStrideLayer &L) { return L.wgt * (L.K / 64) * L.N; }
+// LDS floats in front of the output staging area (the staged filters of a 7x7 layer)
+__host__ __device__ static inline int kstride_filter_floats(const KStrideLayer &L) { return L.fs == 7 ? 64 * L.ts : 0; }
+
+// One channel of a tile: the wavefront's patch (NR rows x NPX columns, flat index f = row * NPX +
+// column) lies in its LDS slot; it is read back 16 pixels at a time with uniform addresses (every
+// lane gets the same four pixels per 16-byte read) and each pixel feeds the FMAs of the outputs
+// it belongs to: acc[orow][q] += pixel(orow * ST + dr, q * ST + sx) * t[dr][sx].
+template <int FS, int ST, int TW, int TR>
+__device__ __forceinline__ void klds_channel(const float *slot, const float (&t)[FS * FS], float (&acc)[TR * TW]) {
+    constexpr int NR = (TR - 1) * ST + FS, NPX = (TW - 1) * ST + FS, NF = NR * NPX;
+    constexpr int CP = 8, NCH = (NF + CP - 1) / CP;      // pixels per chunk; the next chunk is read while this one is used
+    kl_f4 px[2][CP / 4];
+    auto read_chunk = [&](int ch) __attribute__((always_inline)) {
+#pragma unroll
+        for (int m = 0; m < CP / 4; ++m)
+            if (CP * ch + 4 * m < NF) px[ch & 1][m] = *reinterpret_cast<const kl_f4 *>(slot + CP * ch + 4 * m);
+    };
+    read_chunk(0);
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+        if (ch + 1 < NCH) read_chunk(ch + 1);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int e = 0; e < CP; ++e) {
+            const int f = CP * ch + e;
+            if (f >= NF) continue;
+            const int r = f / NPX, i = f - r * NPX;
+            const float v = px[ch & 1][e >> 2][e & 3];
+#pragma unroll
+            for (int dr = 0; dr < FS; ++dr) {
+                const int ro = r - dr;
+                if (ro < 0 || ro % ST != 0 || ro / ST >= TR) continue;
+#pragma unroll
+                for (int sx = 0; sx < FS; ++sx) {
+                    const int d = i - sx;
+                    if (d < 0 || d % ST != 0 || d / ST >= TW) continue;
+                    acc[(ro / ST) * TW + d / ST] = fmaf(v, t[dr * FS + sx], acc[(ro / ST) * TW + d / ST]);
+                }
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+template <int FS, int ST, int TW, int TR>
+__device__ __forceinline__ void klds_tile(const KStrideLayer &L, const int lblk, float *lds) {
+    constexpr int NR = (TR - 1) * ST + FS, NPX = (TW - 1) * ST + FS, NF = NR * NPX, NLD = (NF + 63) / 64;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int KB = L.K >> 6;
+    // (the divisions run on the vector unit: the results are uniform and go back to scalar registers)
+    const int tg = lblk % L.wgt, rest = lblk / L.wgt;
+    const int img = __builtin_amdgcn_readfirstlane(rest / KB), kb = rest - img * KB;
+    const int tile = __builtin_amdgcn_readfirstlane(tg * (kKlWaves / L.cs) + wave / L.cs);
+    const int cw = __builtin_amdgcn_readfirstlane(wave % L.cs), w0 = wave - cw;
+    const bool live = tile < L.ntile;
+    const int rp = __builtin_amdgcn_readfirstlane(tile / L.nseg), seg = tile - rp * L.nseg;
+    const int p0 = rp * TR, q0 = seg * TW;
+    const int HW = L.H * L.W;
+    float *out = lds + kstride_filter_floats(L);
+    float *slot = out + kKlWaves * 14 * 65 + wave * 256;
+    // the lane's pixels in the NLD loads of a channel
+    uint32_t voff[NLD];
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) {
+        const int f = j * 64 + lane;
+        const int r = f / NPX, i = f - r * NPX;
+        const int ih = ST * p0 - L.ph + r, iw = ST * q0 - L.pw + i;
+        const bool ok = live && f < NF && ih >= 0 && ih < L.H && iw >= 0 && iw < L.W;
+        voff[j] = ok ? (uint32_t)((ih * L.W + iw) * 4) : kOobOffset;
+    }
+    const __amdgpu_buffer_rsrc_t xres = make_rsrc(L.x + (size_t)img * L.C * HW, (uint32_t)((size_t)L.C * HW * 4));
+    const uint32_t plane = (uint32_t)HW * 4u;
+    float acc[TR * TW];
+#pragma unroll
+    for (int q = 0; q < TR * TW; ++q) acc[q] = 0.f;
+    if constexpr (FS == 3) {
+        if (live) {
+            const __amdgpu_buffer_rsrc_t wres = make_rsrc(L.w, (uint32_t)((size_t)L.K * L.C * 36));
+            const uint32_t wvoff = (uint32_t)(kb * 64 + lane) * (uint32_t)L.C * 36u;
+            const uint32_t per = (uint32_t)(L.C / L.cs), cbeg = (uint32_t)cw * per, cendx = cbeg + per;
+            // pixels of four channels in flight: slot j holds channel c4 + j, refilled with channel
+            // c4 + j + 4 once it has gone to LDS (channels past the end re-read the last one: unused).
+            // The order of the requests is pinned: the wait in front of a channel's first use then
+            // leaves the younger requests in flight.
+            kl_f4 cur[9], nxt[9];
+            klane_load_taps(wres, wvoff, cbeg, cur);
+            float R[4][NLD];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int l = 0; l < NLD; ++l) R[j][l] = buf_load<float>(xres, voff[l], (cbeg + j) * plane);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            for (uint32_t c4 = cbeg; c4 < cendx; c4 += 4) {
+                klane_load_taps(wres, wvoff, c4 + 4 < cendx ? c4 + 4 : c4, nxt);
+                float t[36];
+#pragma unroll
+                for (int i = 0; i < 9; ++i) {
+                    t[4 * i] = cur[i].x; t[4 * i + 1] = cur[i].y; t[4 * i + 2] = cur[i].z; t[4 * i + 3] = cur[i].w;
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+#pragma unroll
+                    for (int l = 0; l < NLD; ++l) slot[l * 64 + lane] = R[j][l];
+                    const uint32_t cn = min(c4 + j + 4, cendx - 1);
+#pragma unroll
+                    for (int l = 0; l < NLD; ++l) R[j][l] = buf_load<float>(xres, voff[l], cn * plane);
+                    float tj[9];
+#pragma unroll
+                    for (int i = 0; i < 9; ++i) tj[i] = t[j * 9 + i];
+                    klds_channel<3, ST, TW, TR>(slot, tj, acc);
+                }
+#pragma unroll
+                for (int i = 0; i < 9; ++i) cur[i] = nxt[i];
+            }
+        }
+    } else {
+        // the workgroup's 64 filters: read as they lie in memory, written with an odd row stride
+        // (six requests in flight per thread; filter and position within it advance without a division)
+        const int flen = L.C * FS * FS, total = 64 * flen;
+        const float *wb = L.w + (size_t)kb * total;
+        constexpr int NT = 64 * kKlWaves, UN = 6;
+        const int dk = NT / flen, dr = NT - dk * flen;
+        int k = threadIdx.x / flen, rem = threadIdx.x - k * flen;
+        for (int e0 = threadIdx.x; e0 < total; e0 += NT * UN) {
+            float v[UN];
+#pragma unroll
+            for (int u = 0; u < UN; ++u) v[u] = e0 + u * NT < total ? wb[e0 + u * NT] : 0.f;
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                if (e0 + u * NT < total) lds[k * L.ts + rem] = v[u];
+                k += dk;
+                rem += dr;
+                if (rem >= flen) { rem -= flen; ++k; }
+            }
+        }
+        __syncthreads();
+        if (live) {
+            const float *mine = lds + lane * L.ts;
+            float cur[NLD], nxt[NLD];
+#pragma unroll
+            for (int l = 0; l < NLD; ++l) nxt[l] = buf_load<float>(xres, voff[l], 0u);
+            for (int c = 0; c < L.C; ++c) {
+#pragma unroll
+                for (int l = 0; l < NLD; ++l) cur[l] = nxt[l];
+                const uint32_t cn = (uint32_t)min(c + 1, L.C - 1);
+#pragma unroll
+                for (int l = 0; l < NLD; ++l) nxt[l] = buf_load<float>(xres, voff[l], cn * plane);
+#pragma unroll
+                for (int l = 0; l < NLD; ++l) slot[l * 64 + lane] = cur[l];
+                float tc[FS * FS];
+#pragma unroll
+                for (int i = 0; i < FS * FS; ++i) tc[i] = mine[c * FS * FS + i];
+                klds_channel<FS, ST, TW, TR>(slot, tc, acc);
+            }
+        }
+    }
+    // sum over the tile's wavefronts and store with the columns fastest over the lanes (as above), one output row per pass
+    const size_t ybase = ((size_t)img * L.K + (size_t)kb * 64) * L.P * L.Q;
+#pragma unroll
+    for (int r = 0; r < TR; ++r) {
+#pragma unroll
+        for (int q = 0; q < TW; ++q) out[(wave * TW + q) * 65 + lane] = acc[r * TW + q];
+        __syncthreads();
+        if (live && p0 + r < L.P) {
+            for (int o = cw * 64 + lane; o < 64 * TW; o += L.cs * 64) {
+                const int k = o / TW, q = o - k * TW;
+                if (q0 + q >= L.Q) continue;
+                float v = 0.f;
+                for (int ws = 0; ws < L.cs; ++ws) v += out[((w0 + ws) * TW + q) * 65 + k];
+                const float b = L.bias ? L.bias[kb * 64 + k] : 0.f;
+                L.y[ybase + ((size_t)k * L.P + p0 + r) * L.Q + q0 + q] = act(v + b, L.relu);
+            }
+        }
+        if (TR > 1) __syncthreads();
+    }
+}
+
 // ---- many direct-convolution layers (groups 1, square 1x1 / 3x3 / 5x5 / 7x7 filter) in one launch
 // of four-wavefront workgroups: a workgroup finds its layer by counting the entries of a prefix
 // array it has reached and then runs that layer's block.
@@ -516,48 +741,47 @@ typedef const __attribute__((address_space(4))) DirectTable *DirectTablePtr;
 // A launch runs workgroups of 4 or 16 wavefronts (the wavefronts of a workgroup split the input
 // channels): deep layers have few blocks with long channel loops and need the wider split.
 
-// KL: the launch may hold output-channel-lane layers (float32 only; they need more registers)
-template <typename T, bool KL>
-__global__ __launch_bounds__(1024) void direct_conv_many_kernel(const DirectTable tbl_arg) {
-    extern __shared__ __align__(16) float lds[];      // waves x 8 outputs x 64 lanes; kKlWaves x 14 x 65 with output-channel-lane layers
-    const int waves = blockDim.x >> 6;
-    const DirectTablePtr tbl = (DirectTablePtr)__builtin_amdgcn_kernarg_segment_ptr();
-    // groups of 8 consecutive blocks (neighbouring pixel or channel groups of a layer) go to one XCD
-    const int i = blockIdx.x, xcd = i & 7, j = i >> 3;
-    const int b = ((j >> 3) * 8 + xcd) * 8 + (j & 7);
-    if (b >= tbl->nblocks) return;
+// Finds the layer of logical block b in the table and copies its record; returns the index of the block within the layer.
+__device__ __forceinline__ int direct_many_lookup(const DirectTablePtr tbl, const int b, DirectLayer &L) {
     int li = 0, first = 0;
 #pragma unroll
     for (int l = 1; l < kMaxDirectLayers; ++l) {
         const int p = tbl->block0[l];
         if (b >= p) { ++li; first = p; }
     }
-    DirectLayer L;
-    {
-        static_assert(sizeof(DirectLayer) % 4 == 0, "copied word by word");
-        const __attribute__((address_space(4))) uint32_t *src = (const __attribute__((address_space(4))) uint32_t *)&tbl->layer[li];
-        uint32_t *dst = reinterpret_cast<uint32_t *>(&L);
+    static_assert(sizeof(DirectLayer) % 4 == 0, "copied word by word");
+    const __attribute__((address_space(4))) uint32_t *src = (const __attribute__((address_space(4))) uint32_t *)&tbl->layer[li];
+    uint32_t *dst = reinterpret_cast<uint32_t *>(&L);
 #pragma unroll
-        for (int k = 0; k < (int)(sizeof(DirectLayer) / 4); ++k) dst[k] = src[k];
-    }
+    for (int k = 0; k < (int)(sizeof(DirectLayer) / 4); ++k) dst[k] = src[k];
+    return b - first;
+}
+// groups of 8 consecutive blocks (neighbouring pixel or channel groups of a layer) go to one XCD
+__device__ __forceinline__ int direct_many_block() {
+    const int i = blockIdx.x, xcd = i & 7, j = i >> 3;
+    return ((j >> 3) * 8 + xcd) * 8 + (j & 7);
+}
+
+// Layers with the lanes along the pixels.  (Held to 64 registers so that two workgroups of 16
+// wavefronts fit a CU, the launch takes as long: every wavefront then takes twice the time.  The
+// filters of the deep layers are a stream of scalar-cache misses, and that path is the limit.)
+template <typename T>
+__global__ __launch_bounds__(1024) void direct_conv_many_kernel(const DirectTable tbl_arg) {
+    extern __shared__ __align__(16) float lds[];      // waves x 8 outputs x 64 lanes
+    const int waves = blockDim.x >> 6;
+    const DirectTablePtr tbl = (DirectTablePtr)__builtin_amdgcn_kernarg_segment_ptr();
+    const int b = direct_many_block();
+    if (b >= tbl->nblocks) return;
+    DirectLayer L;
+    int lblk = direct_many_lookup(tbl, b, L);
     const T *x = static_cast<const T *>(L.x);
     T *y = static_cast<T *>(L.y);
-    int lblk = b - first;
     int cs = waves;
     if (L.variant & 32) {
         // a layer with fewer input channels than wavefronts: nothing to split, every wavefront takes a block of its own
         lblk = lblk * waves + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         cs = 1;
         if (lblk >= L.d.grid_nx * L.d.grid_ny * L.d.N) return;
-    }
-    if constexpr (KL) {
-        if (L.variant == 64) {       // launched with kKlWaves wavefronts per workgroup
-            KLaneLayer K{x, L.w, L.bias, y, L.d.N, L.d.C, L.d.H, L.d.W, L.d.K, 0, 0, 0, 0, 0, L.d.relu};
-            klane_geometry(K);
-            if (K.tw == 7) klane_tile<7, 2>(K, lblk, lds);
-            else klane_tile<14, 2>(K, lblk, lds);
-            return;
-        }
     }
     switch (L.variant & 31) {
         case 0: direct_slane_block<T, 4, 1>(x, L.w, L.bias, y, L.d, lblk, cs, lds); break;
@@ -568,6 +792,29 @@ __global__ __launch_bounds__(1024) void direct_conv_many_kernel(const DirectTabl
         case 14: direct_slane_block<T, 8, 3, true>(x, L.w, L.bias, y, L.d, lblk, cs, lds); break;
         case 16: direct_slane_block<T, 4, 5>(x, L.w, L.bias, y, L.d, lblk, cs, lds); break;
         default: direct_slane_block<T, 4, 7>(x, L.w, L.bias, y, L.d, lblk, cs, lds); break;
+    }
+}
+
+// Output-channel-lane layers (float32; variant 64: 3x3 stride 1, 65: stride 2), kKlWaves wavefronts per workgroup.
+__global__ __launch_bounds__(1024) void direct_conv_many_klane_kernel(const DirectTable tbl_arg) {
+    extern __shared__ __align__(16) float lds[];      // kKlWaves x 14 x 65
+    const DirectTablePtr tbl = (DirectTablePtr)__builtin_amdgcn_kernarg_segment_ptr();
+    const int b = direct_many_block();
+    if (b >= tbl->nblocks) return;
+    DirectLayer L;
+    const int lblk = direct_many_lookup(tbl, b, L);
+    if (L.variant == 64) {
+        KLaneLayer K{static_cast<const float *>(L.x), L.w, L.bias, static_cast<float *>(L.y), L.d.N, L.d.C, L.d.H, L.d.W, L.d.K, 0, 0, 0, 0, 0, L.d.relu};
+        klane_geometry(K);
+        if (K.tw == 7) klane_tile<7, 2>(K, lblk, lds);
+        else klane_tile<14, 2>(K, lblk, lds);
+    } else {
+        KStrideLayer S{static_cast<const float *>(L.x), L.w, L.bias, static_cast<float *>(L.y), L.d.N, L.d.C, L.d.H, L.d.W, L.d.K,
+                       L.d.P, L.d.Q, L.d.ph, L.d.pw, L.d.R, L.d.sh, 0, 0, 0, 0, 0, 0, L.d.relu};
+        kstride_geometry(S);
+        if (S.fs == 7) klds_tile<7, 2, 14, 1>(S, lblk, lds);      // (a 7-wide tile of a 7x7 filter would not pay: 19 pixels for 7 outputs)
+        else if (S.tw == 7) klds_tile<3, 2, 7, 1>(S, lblk, lds);
+        else klds_tile<3, 2, 14, 1>(S, lblk, lds);
     }
 }
 
@@ -694,10 +941,21 @@ static hipError_t launch_direct_t(const Geo &g, const T *x, const float *w, cons
 bool direct_many_supported(const Geo &g) { return slane_supported(g); }
 
 // float32, groups 1, 3x3, stride 1, pad 1, K a multiple of 64, C a multiple of 4, rows of 7 or a multiple of 14 pixels
-// (stride 2 with one-row tiles was measured too: 21 FMAs per scalar row load, such wavefronts mostly wait)
 static bool klane_supported(const Geo &g) {
     return g.dtype == NNV_F32 && g.groups == 1 && g.r == 3 && g.s == 3 && g.sh == 1 && g.sw == 1 && g.ph == 1 && g.pw == 1 &&
            g.k % 64 == 0 && g.c % 4 == 0 && (g.w == 7 || g.w % 14 == 0);
+}
+// float32, groups 1, 3x3 (C a multiple of 4) or 7x7 (at most 4 input channels), stride 2, K a multiple of 64
+static bool kstride_supported(const Geo &g) {
+    if (!(g.dtype == NNV_F32 && g.groups == 1 && g.r == g.s && g.sh == 2 && g.sw == 2 && g.k % 64 == 0)) return false;
+    if ((size_t)g.c * g.h * g.w * 4 >= (1u << 31) || (size_t)g.k * g.c * g.r * g.s * 4 >= (1ull << 32)) return false;
+    if (g.r == 3) return g.c % 4 == 0;
+    return g.r == 7 && g.c <= 4;
+}
+static KStrideLayer kstride_layer(const Geo &g) {
+    KStrideLayer S{nullptr, nullptr, nullptr, nullptr, g.n, g.c, g.h, g.w, g.k, g.p, g.q, g.ph, g.pw, g.r, g.sh, 0, 0, 0, 0, 0, 0, 0};
+    kstride_geometry(S);
+    return S;
 }
 static KLaneLayer klane_layer(const Geo &g) {
     KLaneLayer K{nullptr, nullptr, nullptr, nullptr, g.n, g.c, g.h, g.w, g.k, 0, 0, 0, 0, 0, 0};
@@ -706,11 +964,13 @@ static KLaneLayer klane_layer(const Geo &g) {
 }
 
 // Layers [0, n) (one storage type, n <= kMaxDirectLayers, each direct_many_supported): one launch of
-// 8-wavefront workgroups for the layers the output-channel-lane kernel covers, one of 16-wavefront
-// workgroups for the deep ones among the others (the wavefronts of a workgroup split the input
-// channels: a deep layer is a chain of scalar-load round trips per wavefront, the wide split
-// shortens it) and one of 4-wavefront workgroups for the rest.  Within a launch the longest
-// wavefronts come first.  (All three in one launch, dealt out alternately, was measured: slower.)
+// 8-wavefront workgroups for the layers the two output-channel-lane kernels cover (3x3 stride 1;
+// 3x3 and 7x7 stride 2) and, for the others, one launch of 16-wavefront workgroups (the wavefronts
+// of a workgroup split the input channels: a deep layer is a chain of scalar-load round trips per
+// wavefront, the wide split shortens it; layers with fewer channels than wavefronts run a block per
+// wavefront).  A call without output-channel-lane layers splits the others by depth into a launch of
+// 16- and one of 4-wavefront workgroups.  Within a launch the longest wavefronts come first.  (All
+// in one launch, dealt out alternately, was measured: slower.)
 hipError_t launch_direct_many(int n, const Geo *geos, const void *const *x, const void *const *w, const float *const *bias,
                               void *const *y, hipStream_t st_) {
     if (n <= 0) return hipSuccess;
@@ -719,26 +979,29 @@ hipError_t launch_direct_many(int n, const Geo *geos, const void *const *x, cons
     bool any_klane = false;
     for (int i = 0; i < n; ++i) {
         if ((geos[i].dtype == NNV_F16) != half || !slane_supported(geos[i])) return hipErrorInvalidValue;
-        any_klane = any_klane || klane_supported(geos[i]);
+        any_klane = any_klane || klane_supported(geos[i]) || kstride_supported(geos[i]);
     }
     // pass 0 / 1: workgroups of 16 / 4 wavefronts; pass 2: output-channel-lane layers, 8 wavefronts
     for (int pass = 0; pass < 3; ++pass) {
         const int waves = pass == 0 ? 16 : pass == 1 ? 4 : kKlWaves;
         int order[kMaxDirectLayers], m = 0;
-        long weight[kMaxDirectLayers];        // sort key: about the FMAs of one wavefront
+        long weight[kMaxDirectLayers];        // sort key: about the vector instructions of one wavefront
         for (int i = 0; i < n; ++i) {
             const Geo &g = geos[i];
             int p;
-            if (klane_supported(g)) p = 2;
-            else if (any_klane) p = g.c >= 64 ? 0 : 1;      // what is left are few layers of short work: the wide channel split shortens their chains
+            if (klane_supported(g) || kstride_supported(g)) p = 2;
+            else if (any_klane) p = 0;      // what is left are few layers of short work: one launch, and the wide channel split shortens their chains
             else p = g.c > 128 ? 0 : 1;
             if (p != pass) continue;
             order[m++] = i;
             if (klane_supported(g)) {
                 const KLaneLayer K = klane_layer(g);
                 weight[i] = (long)(g.c / K.cs) * K.tw * 18;
+            } else if (kstride_supported(g)) {
+                const KStrideLayer S = kstride_layer(g);
+                weight[i] = (long)(g.c / S.cs) * g.r * (2 * S.tw + g.r - 2 + g.r * S.tw);
             } else {
-                weight[i] = (long)ceil_div(g.c, waves) * g.r * g.s * 8;
+                weight[i] = (long)(g.c < waves ? g.c : ceil_div(g.c, waves)) * g.r * g.s * ((g.k % 8 == 0 && g.r <= 3) ? 8 : 4);
             }
         }
         if (m == 0) continue;
@@ -746,6 +1009,7 @@ hipError_t launch_direct_many(int n, const Geo *geos, const void *const *x, cons
         DirectTable tbl{};
         long blocks = 0;
         bool klane_in_launch = false;
+        int filter_floats = 0;      // staged filters of the 7x7 stride-2 layers of the launch
         for (int o = 0; o < m; ++o) {
             const Geo &g = geos[order[o]];
             const int i = order[o];
@@ -757,6 +1021,12 @@ hipError_t launch_direct_many(int n, const Geo *geos, const void *const *x, cons
                 const KLaneLayer K = klane_layer(g);
                 L.variant = 64;
                 blocks += klane_blocks(K);
+                klane_in_launch = true;
+            } else if (pass == 2) {
+                const KStrideLayer S = kstride_layer(g);
+                L.variant = 65;
+                blocks += kstride_blocks(S);
+                filter_floats = std::max(filter_floats, kstride_filter_floats(S));
                 klane_in_launch = true;
             } else {
                 const bool grid8 = g.r == 3 && g.sh == 1 && g.sw == 1 && g.h <= 7 && g.w <= 7 && g.ph <= 1 && g.pw <= 1;
@@ -779,10 +1049,14 @@ hipError_t launch_direct_many(int n, const Geo *geos, const void *const *x, cons
         for (int o = m; o < kMaxDirectLayers; ++o) tbl.block0[o] = INT_MAX;
         tbl.nblocks = (int)blocks;
         const int per_xcd = ceil_div(ceil_div((int)blocks, 8), 8) * 8;
-        const size_t lds = klane_in_launch ? (size_t)kKlWaves * 14 * 65 * sizeof(float) : (size_t)waves * 8 * 64 * sizeof(float);
-        if (half) hipLaunchKernelGGL((direct_conv_many_kernel<__half, false>), dim3(per_xcd * 8), dim3(64 * waves), lds, st_, tbl);
-        else if (klane_in_launch) hipLaunchKernelGGL((direct_conv_many_kernel<float, true>), dim3(per_xcd * 8), dim3(64 * waves), lds, st_, tbl);
-        else hipLaunchKernelGGL((direct_conv_many_kernel<float, false>), dim3(per_xcd * 8), dim3(64 * waves), lds, st_, tbl);
+        const size_t lds = klane_in_launch ? ((size_t)filter_floats + (size_t)kKlWaves * 14 * 65 + (size_t)kKlWaves * 256) * sizeof(float) : (size_t)waves * 8 * 64 * sizeof(float);
+        if (lds > 64 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(direct_conv_many_klane_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        if (klane_in_launch) hipLaunchKernelGGL(direct_conv_many_klane_kernel, dim3(per_xcd * 8), dim3(64 * waves), lds, st_, tbl);
+        else if (half) hipLaunchKernelGGL(direct_conv_many_kernel<__half>, dim3(per_xcd * 8), dim3(64 * waves), lds, st_, tbl);
+        else hipLaunchKernelGGL(direct_conv_many_kernel<float>, dim3(per_xcd * 8), dim3(64 * waves), lds, st_, tbl);
     }
     return hipGetLastError();
 }

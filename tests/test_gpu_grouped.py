@@ -272,11 +272,21 @@ KLANE = [
     Ly("kl_h1", 4, 1, 14, 64, 3, 1, 1),
     Ly("kl_n2", 8, 7, 14, 128, 3, 1, 1, n=2),
     Ly("kl_w56", 64, 4, 56, 64, 3, 1, 1),
-    Ly("other_stem28", 3, 28, 28, 64, 7, 2, 3),              # thin layers: a block per wavefront
-    Ly("other_stem42", 3, 12, 42, 128, 7, 2, 3, n=2),
-    Ly("other_s2_w28", 16, 10, 28, 128, 3, 2, 1),
-    Ly("other_s2_deep", 256, 14, 14, 64, 3, 2, 1),           # the deep ones of the others: 16-wavefront workgroups
-    Ly("other_s2", 16, 15, 15, 32, 3, 2, 1),                 # not covered: the pixel-lane kernel in the same call
+    # stride 2 (3x3 with C a multiple of 4, 7x7 with up to 4 channels; K a multiple of 64): lanes along the
+    # output channels too, one output row of 7 or 14 columns per tile, pixels handed round by v_readlane
+    Ly("ks_stem28", 3, 28, 28, 64, 7, 2, 3),                 # 7x7: filters staged in LDS; Q = 14
+    Ly("ks_stem42", 3, 12, 42, 128, 7, 2, 3, n=2),           # Q = 21: a full and a ragged tile, two blocks of output channels
+    Ly("ks_stem_c4", 4, 9, 30, 64, 7, 2, 2),                 # four channels (even filter length, odd LDS stride), pad 2, Q = 14
+    Ly("ks_stem_c1", 1, 20, 20, 64, 7, 2, 0),                # one channel, no padding, Q = 7
+    Ly("ks_w28", 16, 10, 28, 128, 3, 2, 1),                  # Q = 14, four wavefronts per tile
+    Ly("ks_deep", 256, 14, 14, 64, 3, 2, 1),                 # Q = 7: 7-wide tiles, eight wavefronts per tile
+    Ly("ks_w56", 64, 6, 56, 64, 3, 2, 1),                    # Q = 28: two tiles per row
+    Ly("ks_q13", 8, 7, 26, 64, 3, 2, 1, n=2),                # Q = 13: ragged tile; two wavefronts per tile
+    Ly("ks_q21", 4, 5, 42, 64, 3, 2, 1),                     # Q = 21: three 7-wide tiles, one wavefront per tile
+    Ly("ks_q17_p0", 12, 9, 35, 64, 3, 2, 0),                 # no padding, Q = 17: a full and a ragged tile
+    Ly("other_s2", 16, 15, 15, 32, 3, 2, 1),                 # not covered (K = 32): the pixel-lane kernel in the same call
+    Ly("other_s2_c6", 6, 14, 14, 64, 3, 2, 1),               # not covered (C = 6)
+    Ly("other_1x1_s2", 64, 14, 14, 128, 1, 2, 0),
     Ly("other_w15", 8, 9, 15, 64, 3, 1, 1),
     Ly("other_c6", 6, 14, 14, 64, 3, 1, 1),
 ]
