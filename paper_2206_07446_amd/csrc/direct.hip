@@ -318,240 +318,92 @@ __global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__rest
     direct_slane_block<T, TK, FS, GRID8>(x, w, bias, y, d, lblk, blockDim.x >> 6, lds);
 }
 
-// ---- 3x3 stride-1 pad-1 float32 layers with the lanes along the output channels
+// ---- float32 3x3 (stride 1 or 2) and 7x7 (stride 2) layers with the lanes along the output channels
 //
-// lane = output channel (64 per wavefront), tile = TR = 2 output rows x TW columns held as TR * TW
-// accumulators per lane (one-row tiles were measured: too few FMAs per scalar row load).  The two
-// operands swap roles against the kernel above: a lane's taps (9 consecutive floats per input
-// channel in OIHW, 36 for a group of four channels) come by 16-byte vector loads that stream each
-// filter from HBM once per tile, and the input pixels, which every lane needs alike, come through
-// the scalar cache as FMA scalar operands (4 rows x (TW + 2) columns per channel).  Per channel
-// that is 18 * TW FMAs for 9 vector dwords and 4 scalar row loads, against 72 FMAs for 9 vector
-// and 16 scalar loads above, and a tap is used 2 * TW times once it is in a register.  Zero
-// padding: columns outside the row are left out at compile time (the tile variants LE / RE know
-// whether they touch the left / right edge), rows outside the plane are read from a row of zeros.
-// A scalar load cannot be waited for without waiting for every scalar load issued after it, so
-// the order is pinned: the row two stages ahead is requested right after the wait for the
-// current row, and has the FMAs of two rows to arrive.  Two other ways of feeding the pixels
-// were measured and dropped: held once per quad of lanes and broadcast by a DPP operand on the
-// FMA (DPP FMAs run at about half rate), and staged in LDS and read back as broadcasts (level at
-// full occupancy, slower at low).  The cs wavefronts of a tile split the channels; partial sums
-// meet in LDS, one output row of the tile per pass, in a fixed order.
+// lane = output channel (64 per wavefront), tile = TR output rows x TW columns held as TR * TW
+// accumulators per lane.  The two operands swap roles against the kernel above.
+//
+// Pixels.  Every lane needs the same pixels, so they must arrive as uniform operands.  The patch of
+// a tile (NR rows x NPX columns of one channel) is fetched by vector loads with the lanes along
+// the patch (flattened over ceil(NR NPX / 64) loads, zero outside the plane through the range
+// check of the buffer), written to an LDS slot of the wavefront and read back with uniform
+// addresses, 16 bytes at a time: every lane then holds the same four pixels in vector registers.
+// The LDS pipe runs beside the vector ALU (sixteen such reads next to 48 FMAs cost nothing,
+// measured) and a wavefront's LDS operations complete in order, so there is no barrier in the
+// channel loop.  Ways of feeding the pixels that were measured and dropped: through the scalar
+// cache as FMA scalar operands (rows of 16 by scalar loads: fine for deep layers, but on planes
+// of 56 x 56 and more every row load misses the scalar cache and the wavefronts mostly wait;
+// 525 against 421 us on a VGG-16-shaped stack, 84 against 77 us on a ResNet-18-shaped one; at
+// stride 2 a scalar row load pays for at most 36 FMAs), held once per quad of lanes and
+// broadcast by a DPP operand on the FMA (DPP FMAs issue at about half rate), and v_readlane into
+// scalar registers (one v_readlane costs the issue time of four FMAs).
+//
+// Taps.  A lane needs the taps of its own output channel, and the 64 filters of a block lie
+// C * FS * FS * 4 bytes apart: fetched per lane, every load instruction touches 64 cache lines, and
+// with such loads the deep layers are bound by the address path of the CU.  3x3: the wavefront
+// fetches the taps of two channels (72 contiguous bytes per filter) as they lie in memory, 8 bytes
+// per lane and 7 filters per instruction, copies them to its LDS region as they come (filter k at
+// byte 72 k) and every lane reads its filter back: ten loads that touch some ten lines each
+// instead of five that touch 64.  The fetch for the next pair of channels is issued before this
+// pair is computed, the copy through LDS follows the computation.  7x7 layers with at most four
+// input channels (a stem): the 64 whole filters of the workgroup are staged once in LDS, row
+// stride odd, and read back a channel at a time.
+//
+// The cs wavefronts of a tile split the channels; partial sums meet in LDS, one output row of the
+// tile per pass, in a fixed order, and the store runs with the columns fastest over the lanes.
 constexpr int kKlWaves = 8;                 // wavefronts per workgroup
-__device__ const float kl_zero_row[16] = {};
+constexpr int kTapRegion = 64 * 18 + 112;   // LDS floats of a wavefront's tap staging area (64 filters x 2 channels x 9 taps, and the overrun of the last copy)
+constexpr int kKlStagedMaxC = 4;            // whole filters are staged in LDS up to this many input channels
+typedef float kl_f4 __attribute__((ext_vector_type(4)));
+typedef float kl_f2 __attribute__((ext_vector_type(2)));
 
 struct KLaneLayer {
     const float *x, *w, *bias;
     float *y;
-    int N, C, H, W, K;
-    int tw;       // tile width: 14, or 7 for 7-wide planes (W is a multiple of it)
-    int nseg;     // W / tw
-    int ntile;    // nseg * ceil(H / 2)
-    int cs;       // wavefronts per tile (1, 2, 4 or 8): each takes C / cs channels, a multiple of 4
-    int wgt;      // workgroups per (image, block of 64 output channels) = ceil(ntile / (8 / cs))
+    int N, C, H, W, K, P, Q, ph, pw, fs, st;
+    int staged;   // 1: whole filters in LDS (7x7, C <= kKlStagedMaxC), 0: taps of two channels at a time (3x3, C a multiple of 4)
+    int tw;       // tile width: 14, or 7 for a 3x3 layer whose Q is an odd multiple of 7 (the last tile of a row may be ragged)
+    int tr;       // tile rows: 2 at stride 1, 1 at stride 2
+    int nseg;     // ceil(Q / tw)
+    int ntile;    // nseg * ceil(P / tr)
+    int cs;       // wavefronts per tile (1, 2, 4 or 8): each takes C / cs channels, a multiple of 4; staged: 1
+    int wgt;      // workgroups per (image, block of 64 output channels) = ceil(ntile / (kKlWaves / cs))
+    int ts;       // staged: row stride (floats) of the filters in LDS, odd
     int relu;
 };
 // tile geometry of a layer (the same arithmetic sizes the launch on the host and places a workgroup on the device)
 __host__ __device__ static inline void klane_geometry(KLaneLayer &L) {
-    L.tw = L.W == 7 ? 7 : 14;
-    L.nseg = L.W / L.tw;
-    L.ntile = L.nseg * ((L.H + 1) / 2);
-    int cs = L.C >= 128 ? 8 : 4;
-    while (cs > 1 && L.C % (4 * cs) != 0) cs >>= 1;
-    L.cs = cs;
-    L.wgt = (L.ntile + kKlWaves / cs - 1) / (kKlWaves / cs);
-}
-__host__ __device__ static inline int klane_blocks(const KLaneLayer &L) { return L.wgt * (L.K / 64) * L.N; }
-typedef const __attribute__((address_space(4))) float *KlConstPtr;
-typedef float kl_f4 __attribute__((ext_vector_type(4)));
-
-// taps of the four channels c .. c + 3 (36 floats per lane)
-__device__ __forceinline__ void klane_load_taps(__amdgpu_buffer_rsrc_t wres, uint32_t voff, uint32_t c, kl_f4 (&t)[9]) {
-#pragma unroll
-    for (int i = 0; i < 9; ++i)
-        t[i] = __builtin_bit_cast(kl_f4, __builtin_amdgcn_raw_buffer_load_b128(wres, voff + i * 16, c * 36u, 0));
-}
-
-template <int TW, int TR, bool LE, bool RE>
-__device__ __forceinline__ void klane_accumulate(const KLaneLayer &L, const int img, const int kb, const int p0, const int q0,
-                                                 const int cw, const int lane, float (&acc)[TR * TW]) {
-    constexpr int NR = TR + 2;                                   // patch rows
-    constexpr int NCOL = TW + 2;                                 // patch columns, the first one left of the tile
-    constexpr int NL = NCOL - (LE ? 1 : 0) - (RE ? 1 : 0);       // pixels read per patch row
-    const int HW = L.H * L.W;
-    const __amdgpu_buffer_rsrc_t wres = make_rsrc(L.w, (uint32_t)((size_t)L.K * L.C * 36));
-    const uint32_t voff = (uint32_t)(kb * 64 + lane) * (uint32_t)L.C * 36u;
-    // the patch rows: first pixel read, and the step from one channel to the next (0 for the zero row)
-    KlConstPtr row[NR];
-    uint32_t step[NR];
-    const float *ximg = L.x + (size_t)img * L.C * HW;
-#pragma unroll
-    for (int pr = 0; pr < NR; ++pr) {
-        const int ih = p0 - 1 + pr;
-        const bool ok = ih >= 0 && ih < L.H;
-        row[pr] = ok ? (KlConstPtr)(uintptr_t)(ximg + (size_t)ih * L.W + q0 - (LE ? 0 : 1)) : (KlConstPtr)(uintptr_t)kl_zero_row;
-        step[pr] = ok ? (uint32_t)HW : 0u;
-    }
-    // this wavefront's channels: [cbeg, cbeg + per), per a multiple of 4
-    const uint32_t per = (uint32_t)(L.C / L.cs), cbeg = (uint32_t)cw * per, cendx = cbeg + per;
-    auto load_row = [&](float (&R)[NL], int pr, uint32_t c) __attribute__((always_inline)) {
-        const KlConstPtr xr = row[pr] + (size_t)c * step[pr];
-#pragma unroll
-        for (int i = 0; i < NL; ++i) R[i] = xr[i];
-    };
-    kl_f4 cur[9], nxt[9];
-    klane_load_taps(wres, voff, cbeg, cur);
-    float R[NR][NL];
-    load_row(R[0], 0, cbeg);
-    load_row(R[1], 1, cbeg);
-    for (uint32_t c4 = cbeg; c4 < cendx; c4 += 4) {
-        // the next group's taps travel while this group is computed (the last group re-reads
-        // itself: the scalar offset is not part of the buffer range check, so it must stay inside)
-        klane_load_taps(wres, voff, c4 + 4 < cendx ? c4 + 4 : c4, nxt);
-        float t[36];
-#pragma unroll
-        for (int i = 0; i < 9; ++i) {
-            t[4 * i] = cur[i].x; t[4 * i + 1] = cur[i].y; t[4 * i + 2] = cur[i].z; t[4 * i + 3] = cur[i].w;
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint32_t c = c4 + j;
-#pragma unroll
-            for (int pr = 0; pr < NR; ++pr) {
-                // stage: first use of row pr (the wait for it lands here), then the request for the
-                // row two stages ahead, then the rest of row pr
-                bool first = true;
-#pragma unroll
-                for (int r = 0; r < TR; ++r) {
-                    const int dr = pr - r;
-                    if (dr < 0 || dr > 2) continue;
-#pragma unroll
-                    for (int q = 0; q < TW; ++q)
-#pragma unroll
-                        for (int ds = 0; ds < 3; ++ds) {
-                            const int col = q + ds;          // patch column, 0 .. NCOL - 1
-                            if ((LE && col == 0) || (RE && col == NCOL - 1)) continue;
-                            acc[r * TW + q] = fmaf(R[pr][col - (LE ? 1 : 0)], t[j * 9 + dr * 3 + ds], acc[r * TW + q]);
-                            if (first) {
-                                first = false;
-                                __builtin_amdgcn_sched_barrier(0);
-                                // the row two stages on: of this channel, or of the next one (the last channel
-                                // of the wavefront requests its own rows again: in range, never used)
-                                if (pr + 2 < NR) load_row(R[pr + 2], pr + 2, c);
-                                else load_row(R[pr + 2 - NR], pr + 2 - NR, c + 1 < cendx ? c + 1 : c);
-                                __builtin_amdgcn_sched_barrier(0);
-                            }
-                        }
-                }
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < 9; ++i) cur[i] = nxt[i];
-    }
-}
-
-template <int TW, int TR>
-__device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, float *lds) {
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int KB = L.K >> 6;
-    const int tg = lblk % L.wgt, rest = lblk / L.wgt;
-    const int kb = rest % KB, img = rest / KB;
-    const int tile = tg * (kKlWaves / L.cs) + wave / L.cs;
-    const int cw = wave % L.cs, w0 = wave - cw;
-    const bool live = tile < L.ntile;
-    const int rp = tile / L.nseg, seg = tile - rp * L.nseg;
-    const int p0 = rp * TR, q0 = seg * TW;
-    float acc[TR * TW];
-#pragma unroll
-    for (int i = 0; i < TR * TW; ++i) acc[i] = 0.f;
-    if (live) {
-        const bool le = seg == 0, re = seg == L.nseg - 1;
-        if (TW == 7 || (le && re)) klane_accumulate<TW, TR, true, true>(L, img, kb, p0, q0, cw, lane, acc);
-        else if (le) klane_accumulate<TW, TR, true, false>(L, img, kb, p0, q0, cw, lane, acc);
-        else if (re) klane_accumulate<TW, TR, false, true>(L, img, kb, p0, q0, cw, lane, acc);
-        else klane_accumulate<TW, TR, false, false>(L, img, kb, p0, q0, cw, lane, acc);
-    }
-    // Sum over the cs wavefronts of the tile and store, one output row of the tile per pass.  Every
-    // wavefront leaves its row as lds[(wave * TW + q) * 65 + lane]; then the tile's wavefronts share its
-    // 64 x TW outputs with the columns running fastest over the lanes, so that a store covers runs of
-    // TW consecutive floats of y instead of 64 separate rows (row stride 65: the transposed reads
-    // spread over the banks).  Fixed summation order.
-    const size_t ybase = ((size_t)img * L.K + (size_t)kb * 64) * L.H * L.W;
-#pragma unroll
-    for (int r = 0; r < TR; ++r) {
-#pragma unroll
-        for (int q = 0; q < TW; ++q) lds[(wave * TW + q) * 65 + lane] = acc[r * TW + q];
-        __syncthreads();
-        if (live && p0 + r < L.H) {
-            for (int o = cw * 64 + lane; o < 64 * TW; o += L.cs * 64) {
-                const int k = o / TW, q = o - k * TW;
-                float v = 0.f;
-                for (int ws = 0; ws < L.cs; ++ws) v += lds[((w0 + ws) * TW + q) * 65 + k];
-                const float b = L.bias ? L.bias[kb * 64 + k] : 0.f;
-                L.y[ybase + ((size_t)k * L.H + p0 + r) * L.W + q0 + q] = act(v + b, L.relu);
-            }
-        }
-        __syncthreads();
-    }
-}
-
-// ---- 3x3 and 7x7 stride-2 float32 layers with the lanes along the output channels
-//
-// At stride 2 a loaded pixel feeds only 9/4 (3x3) or 49/4 (7x7) FMAs per output channel, so the
-// scalar cache cannot deliver the pixels fast enough (a scalar row load would pay for at most 36
-// FMAs), and with the lanes along the pixels the filters of a deep layer are a stream of scalar
-// cache misses, each used by one wavefront.  Here the taps are again per lane (3x3: 16-byte
-// vector loads of four channels' taps, as above; 7x7 with up to four input channels: the 64
-// filters of the workgroup staged once in LDS, row stride odd, and read back a channel at a
-// time) and the pixels come by vector loads with the lanes along the patch (NR rows of NPX
-// pixels, flattened over ceil(NR NPX / 64) loads per channel, zero outside the plane through the
-// range check of the buffer).  The wavefront writes the patch to an LDS slot of its own and reads
-// it back with uniform addresses, so that every lane receives the same pixels in vector
-// registers: the LDS pipe runs beside the vector ALU (16 such reads next to 48 FMAs cost nothing,
-// measured), and a wavefront's LDS operations complete in order, so there is no barrier in the
-// channel loop.  (Handing the pixels round with v_readlane was measured first: one v_readlane
-// costs the issue time of four FMAs, 83 against 88 us for the launch below.)  A tile is TR output
-// rows of TW pixels; cs wavefronts split the channels.  The same tile body instantiated for
-// stride 1 (TR = 2) runs as fast as the scalar-operand kernel above on a VGG-16-shaped stack and
-// 10 % slower on a ResNet-18-shaped one, so stride 1 stays with the kernel above.
-struct KStrideLayer {
-    const float *x, *w, *bias;
-    float *y;
-    int N, C, H, W, K, P, Q, ph, pw, fs, st;
-    int tw;       // tile width: 14, or 7 for a 3x3 layer whose Q is an odd multiple of 7 (the last tile of a row may be ragged)
-    int nseg;     // ceil(Q / tw)
-    int ntile;    // nseg * P
-    int cs;       // wavefronts per tile: 3x3: up to 8, each takes C / cs channels, a multiple of 4; 7x7: 1
-    int wgt;      // workgroups per (image, block of 64 output channels)
-    int ts;       // 7x7: row stride (floats) of the staged filters
-    int relu;
-};
-__host__ __device__ static inline void kstride_geometry(KStrideLayer &L) {
+    L.staged = L.fs == 7;
     L.tw = (L.fs == 3 && L.Q % 7 == 0 && L.Q % 14 != 0) ? 7 : 14;
+    L.tr = L.st == 1 ? 2 : 1;
     L.nseg = (L.Q + L.tw - 1) / L.tw;
-    L.ntile = L.nseg * (L.st == 1 ? (L.P + 1) / 2 : L.P);      // stride 1: two output rows per tile
+    L.ntile = L.nseg * ((L.P + L.tr - 1) / L.tr);
     int cs = 1;
-    if (L.fs == 3) {
+    if (!L.staged) {
         cs = (L.st == 1 && L.C < 128) ? 4 : kKlWaves;
         while (cs > 1 && L.C % (4 * cs) != 0) cs >>= 1;
     }
     L.cs = cs;
     L.wgt = (L.ntile + kKlWaves / cs - 1) / (kKlWaves / cs);
-    L.ts = (L.C * 49) | 1;
+    L.ts = (L.C * L.fs * L.fs) | 1;
 }
-__host__ __device__ static inline int kstride_blocks(const KStrideLayer &L) { return L.wgt * (L.K / 64) * L.N; }
-// LDS floats in front of the output staging area (the staged filters of a 7x7 layer)
-__host__ __device__ static inline int kstride_filter_floats(const KStrideLayer &L) { return L.fs == 7 ? 64 * L.ts : 0; }
+__host__ __device__ static inline int klane_blocks(const KLaneLayer &L) { return L.wgt * (L.K / 64) * L.N; }
+// LDS floats in front of the output rows (the staged filters)
+__host__ __device__ static inline int klane_filter_floats(const KLaneLayer &L) { return L.staged ? 64 * L.ts : 0; }
+// LDS floats of a workgroup: staged: [filters][output rows, 14 x 65 per wavefront][pixel slots]; else
+// [a region of kTapRegion floats per wavefront: its tap staging area in the channel loop, its output rows afterwards][pixel slots]
+__host__ __device__ static inline int klane_lds_floats(const KLaneLayer &L) {
+    return L.staged ? klane_filter_floats(L) + kKlWaves * (14 * 65 + 256) : kKlWaves * (kTapRegion + 256);
+}
 
 // One channel of a tile: the wavefront's patch (NR rows x NPX columns, flat index f = row * NPX +
-// column) lies in its LDS slot; it is read back 16 pixels at a time with uniform addresses (every
-// lane gets the same four pixels per 16-byte read) and each pixel feeds the FMAs of the outputs
-// it belongs to: acc[orow][q] += pixel(orow * ST + dr, q * ST + sx) * t[dr][sx].
+// column) lies in its LDS slot; it is read back 16 pixels at a time with uniform addresses and
+// each pixel feeds the FMAs of the outputs it belongs to:
+// acc[orow][q] += pixel(orow * ST + dr, q * ST + sx) * t[dr][sx].
 template <int FS, int ST, int TW, int TR>
-__device__ __forceinline__ void klds_channel(const float *slot, const float (&t)[FS * FS], float (&acc)[TR * TW]) {
+__device__ __forceinline__ void klane_channel(const float *slot, const float (&t)[FS * FS], float (&acc)[TR * TW]) {
     constexpr int NR = (TR - 1) * ST + FS, NPX = (TW - 1) * ST + FS, NF = NR * NPX;
-    constexpr int CP = 8, NCH = (NF + CP - 1) / CP;      // pixels per chunk; the next chunk is read while this one is used
+    constexpr int CP = 16, NCH = (NF + CP - 1) / CP;     // pixels per chunk; the next chunk is read while this one is used
     kl_f4 px[2][CP / 4];
     auto read_chunk = [&](int ch) __attribute__((always_inline)) {
 #pragma unroll
@@ -585,9 +437,11 @@ __device__ __forceinline__ void klds_channel(const float *slot, const float (&t)
     }
 }
 
-template <int FS, int ST, int TW, int TR>
-__device__ __forceinline__ void klds_tile(const KStrideLayer &L, const int lblk, float *lds) {
+template <int FS, int ST, int TW, int TR, bool STAGED>
+__device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, float *lds) {
+    static_assert(STAGED || FS == 3, "taps of two channels at a time: 3x3 only");
     constexpr int NR = (TR - 1) * ST + FS, NPX = (TW - 1) * ST + FS, NF = NR * NPX, NLD = (NF + 63) / 64;
+    static_assert(NLD * 64 <= 256, "pixel slot");
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int KB = L.K >> 6;
@@ -600,8 +454,9 @@ __device__ __forceinline__ void klds_tile(const KStrideLayer &L, const int lblk,
     const int rp = __builtin_amdgcn_readfirstlane(tile / L.nseg), seg = tile - rp * L.nseg;
     const int p0 = rp * TR, q0 = seg * TW;
     const int HW = L.H * L.W;
-    float *out = lds + kstride_filter_floats(L);
-    float *slot = out + kKlWaves * 14 * 65 + wave * 256;
+    constexpr int OWS = STAGED ? 14 * 65 : kTapRegion;       // floats from one wavefront's output rows to the next one's
+    float *out = lds + klane_filter_floats(L);
+    float *slot = out + kKlWaves * OWS + wave * 256;
     // the lane's pixels in the NLD loads of a channel
     uint32_t voff[NLD];
 #pragma unroll
@@ -617,17 +472,42 @@ __device__ __forceinline__ void klds_tile(const KStrideLayer &L, const int lblk,
     float acc[TR * TW];
 #pragma unroll
     for (int q = 0; q < TR * TW; ++q) acc[q] = 0.f;
-    if constexpr (FS == 3) {
+    if constexpr (!STAGED) {
         if (live) {
-            const __amdgpu_buffer_rsrc_t wres = make_rsrc(L.w, (uint32_t)((size_t)L.K * L.C * 36));
-            const uint32_t wvoff = (uint32_t)(kb * 64 + lane) * (uint32_t)L.C * 36u;
+            const uint32_t rowbytes = (uint32_t)L.C * 36u;
+            const __amdgpu_buffer_rsrc_t wres = make_rsrc(L.w, (uint32_t)((size_t)L.K * rowbytes));
+            const uint32_t fbase = (uint32_t)(kb * 64) * rowbytes;
+            // lane -> (filter lane / 9 of the seven an instruction fetches, 8-byte piece lane % 9); lane 63 idle
+            const uint32_t tvoff = lane < 63 ? fbase + (uint32_t)(lane / 9) * rowbytes + (uint32_t)(lane % 9) * 8u : kOobOffset;
+            const uint32_t tvoff_last = lane < 9 ? fbase + (uint32_t)lane * 8u : kOobOffset;     // filter 63
+            kl_f2 *stage = reinterpret_cast<kl_f2 *>(out + wave * OWS);
+            // (the scalar offset is not part of the range check of a buffer load: it stays inside the tensor)
+            auto tap_fetch = [&](kl_f2 (&tmp)[10], uint32_t c) __attribute__((always_inline)) {
+#pragma unroll
+                for (int it = 0; it < 9; ++it)
+                    tmp[it] = __builtin_bit_cast(kl_f2, __builtin_amdgcn_raw_buffer_load_b64(wres, tvoff, c * 36u + (uint32_t)(it * 7) * rowbytes, 0));
+                tmp[9] = __builtin_bit_cast(kl_f2, __builtin_amdgcn_raw_buffer_load_b64(wres, tvoff_last, c * 36u + 63u * rowbytes, 0));
+            };
+            // (no lane is masked: lane 63 of a copy writes what lane 0 of the next one overwrites, LDS
+            // operations of a wavefront complete in order, and the last copy runs 55 pairs past filter 63)
+            auto tap_stage = [&](const kl_f2 (&tmp)[10], float (&t)[18]) __attribute__((always_inline)) {
+#pragma unroll
+                for (int it = 0; it < 10; ++it) stage[it * 63 + lane] = tmp[it];
+#pragma unroll
+                for (int m = 0; m < 9; ++m) {
+                    const kl_f2 v = stage[lane * 9 + m];
+                    t[2 * m] = v.x;
+                    t[2 * m + 1] = v.y;
+                }
+            };
             const uint32_t per = (uint32_t)(L.C / L.cs), cbeg = (uint32_t)cw * per, cendx = cbeg + per;
             // pixels of four channels in flight: slot j holds channel c4 + j, refilled with channel
             // c4 + j + 4 once it has gone to LDS (channels past the end re-read the last one: unused).
             // The order of the requests is pinned: the wait in front of a channel's first use then
             // leaves the younger requests in flight.
-            kl_f4 cur[9], nxt[9];
-            klane_load_taps(wres, wvoff, cbeg, cur);
+            kl_f2 tmp[10];
+            float t[18];
+            tap_fetch(tmp, cbeg);
             float R[4][NLD];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -636,27 +516,27 @@ __device__ __forceinline__ void klds_tile(const KStrideLayer &L, const int lblk,
                 for (int l = 0; l < NLD; ++l) R[j][l] = buf_load<float>(xres, voff[l], (cbeg + j) * plane);
             }
             __builtin_amdgcn_sched_barrier(0);
+            tap_stage(tmp, t);
             for (uint32_t c4 = cbeg; c4 < cendx; c4 += 4) {
-                klane_load_taps(wres, wvoff, c4 + 4 < cendx ? c4 + 4 : c4, nxt);
-                float t[36];
 #pragma unroll
-                for (int i = 0; i < 9; ++i) {
-                    t[4 * i] = cur[i].x; t[4 * i + 1] = cur[i].y; t[4 * i + 2] = cur[i].z; t[4 * i + 3] = cur[i].w;
+                for (int h = 0; h < 2; ++h) {
+                    // (the last pair fetches itself again: in range, never used)
+                    tap_fetch(tmp, min(c4 + 2 * h + 2, cendx - 2));
+#pragma unroll
+                    for (int jj = 0; jj < 2; ++jj) {
+                        const int j = 2 * h + jj;
+#pragma unroll
+                        for (int l = 0; l < NLD; ++l) slot[l * 64 + lane] = R[j][l];
+                        const uint32_t cn = min(c4 + j + 4, cendx - 1);
+#pragma unroll
+                        for (int l = 0; l < NLD; ++l) R[j][l] = buf_load<float>(xres, voff[l], cn * plane);
+                        float tj[9];
+#pragma unroll
+                        for (int i = 0; i < 9; ++i) tj[i] = t[jj * 9 + i];
+                        klane_channel<3, ST, TW, TR>(slot, tj, acc);
+                    }
+                    tap_stage(tmp, t);
                 }
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-#pragma unroll
-                    for (int l = 0; l < NLD; ++l) slot[l * 64 + lane] = R[j][l];
-                    const uint32_t cn = min(c4 + j + 4, cendx - 1);
-#pragma unroll
-                    for (int l = 0; l < NLD; ++l) R[j][l] = buf_load<float>(xres, voff[l], cn * plane);
-                    float tj[9];
-#pragma unroll
-                    for (int i = 0; i < 9; ++i) tj[i] = t[j * 9 + i];
-                    klds_channel<3, ST, TW, TR>(slot, tj, acc);
-                }
-#pragma unroll
-                for (int i = 0; i < 9; ++i) cur[i] = nxt[i];
             }
         }
     } else {
@@ -696,23 +576,27 @@ __device__ __forceinline__ void klds_tile(const KStrideLayer &L, const int lblk,
                 float tc[FS * FS];
 #pragma unroll
                 for (int i = 0; i < FS * FS; ++i) tc[i] = mine[c * FS * FS + i];
-                klds_channel<FS, ST, TW, TR>(slot, tc, acc);
+                klane_channel<FS, ST, TW, TR>(slot, tc, acc);
             }
         }
     }
-    // sum over the tile's wavefronts and store with the columns fastest over the lanes (as above), one output row per pass
+    // Sum over the cs wavefronts of the tile and store, one output row of the tile per pass.  Every
+    // wavefront leaves its row as out[wave * OWS + q * 65 + lane]; then the tile's wavefronts share its
+    // 64 x TW outputs with the columns running fastest over the lanes, so that a store covers runs of
+    // TW consecutive floats of y instead of 64 separate rows (row stride 65: the transposed reads
+    // spread over the banks).  Fixed summation order.
     const size_t ybase = ((size_t)img * L.K + (size_t)kb * 64) * L.P * L.Q;
 #pragma unroll
     for (int r = 0; r < TR; ++r) {
 #pragma unroll
-        for (int q = 0; q < TW; ++q) out[(wave * TW + q) * 65 + lane] = acc[r * TW + q];
+        for (int q = 0; q < TW; ++q) out[wave * OWS + q * 65 + lane] = acc[r * TW + q];
         __syncthreads();
         if (live && p0 + r < L.P) {
             for (int o = cw * 64 + lane; o < 64 * TW; o += L.cs * 64) {
                 const int k = o / TW, q = o - k * TW;
                 if (q0 + q >= L.Q) continue;
                 float v = 0.f;
-                for (int ws = 0; ws < L.cs; ++ws) v += out[((w0 + ws) * TW + q) * 65 + k];
+                for (int ws = 0; ws < L.cs; ++ws) v += out[(w0 + ws) * OWS + q * 65 + k];
                 const float b = L.bias ? L.bias[kb * 64 + k] : 0.f;
                 L.y[ybase + ((size_t)k * L.P + p0 + r) * L.Q + q0 + q] = act(v + b, L.relu);
             }
@@ -795,27 +679,22 @@ __global__ __launch_bounds__(1024) void direct_conv_many_kernel(const DirectTabl
     }
 }
 
-// Output-channel-lane layers (float32; variant 64: 3x3 stride 1, 65: stride 2), kKlWaves wavefronts per workgroup.
+// Output-channel-lane layers (variant 64, float32), kKlWaves wavefronts per workgroup.
 __global__ __launch_bounds__(1024) void direct_conv_many_klane_kernel(const DirectTable tbl_arg) {
-    extern __shared__ __align__(16) float lds[];      // kKlWaves x 14 x 65
+    extern __shared__ __align__(16) float lds[];      // klane_lds_floats of the launch's largest layer
     const DirectTablePtr tbl = (DirectTablePtr)__builtin_amdgcn_kernarg_segment_ptr();
     const int b = direct_many_block();
     if (b >= tbl->nblocks) return;
     DirectLayer L;
     const int lblk = direct_many_lookup(tbl, b, L);
-    if (L.variant == 64) {
-        KLaneLayer K{static_cast<const float *>(L.x), L.w, L.bias, static_cast<float *>(L.y), L.d.N, L.d.C, L.d.H, L.d.W, L.d.K, 0, 0, 0, 0, 0, L.d.relu};
-        klane_geometry(K);
-        if (K.tw == 7) klane_tile<7, 2>(K, lblk, lds);
-        else klane_tile<14, 2>(K, lblk, lds);
-    } else {
-        KStrideLayer S{static_cast<const float *>(L.x), L.w, L.bias, static_cast<float *>(L.y), L.d.N, L.d.C, L.d.H, L.d.W, L.d.K,
-                       L.d.P, L.d.Q, L.d.ph, L.d.pw, L.d.R, L.d.sh, 0, 0, 0, 0, 0, 0, L.d.relu};
-        kstride_geometry(S);
-        if (S.fs == 7) klds_tile<7, 2, 14, 1>(S, lblk, lds);      // (a 7-wide tile of a 7x7 filter would not pay: 19 pixels for 7 outputs)
-        else if (S.tw == 7) klds_tile<3, 2, 7, 1>(S, lblk, lds);
-        else klds_tile<3, 2, 14, 1>(S, lblk, lds);
-    }
+    KLaneLayer K{static_cast<const float *>(L.x), L.w, L.bias, static_cast<float *>(L.y), L.d.N, L.d.C, L.d.H, L.d.W, L.d.K,
+                 L.d.P, L.d.Q, L.d.ph, L.d.pw, L.d.R, L.d.sh, 0, 0, 0, 0, 0, 0, 0, 0, L.d.relu};
+    klane_geometry(K);
+    if (K.fs == 7) klane_tile<7, 2, 14, 1, true>(K, lblk, lds);      // (a 7-wide tile of a 7x7 filter would not pay: 19 pixels for 7 outputs)
+    else if (K.st == 1 && K.tw == 7) klane_tile<3, 1, 7, 2, false>(K, lblk, lds);
+    else if (K.st == 1) klane_tile<3, 1, 14, 2, false>(K, lblk, lds);
+    else if (K.tw == 7) klane_tile<3, 2, 7, 1, false>(K, lblk, lds);
+    else klane_tile<3, 2, 14, 1, false>(K, lblk, lds);
 }
 
 struct DirectPlan {
@@ -940,37 +819,30 @@ static hipError_t launch_direct_t(const Geo &g, const T *x, const float *w, cons
 
 bool direct_many_supported(const Geo &g) { return slane_supported(g); }
 
-// float32, groups 1, 3x3, stride 1, pad 1, K a multiple of 64, C a multiple of 4, rows of 7 or a multiple of 14 pixels
+// float32, groups 1, K a multiple of 64; 3x3 at stride 1 or 2 with C a multiple of 4; 7x7 at stride 2
+// with at most kKlStagedMaxC channels.  (A 3x3 first layer with three channels through the staged
+// path was measured: its 1792 short tiles lengthen the launch of a VGG-16-shaped stack by more
+// than the 19 us the layer takes with the lanes along the pixels.)
 static bool klane_supported(const Geo &g) {
-    return g.dtype == NNV_F32 && g.groups == 1 && g.r == 3 && g.s == 3 && g.sh == 1 && g.sw == 1 && g.ph == 1 && g.pw == 1 &&
-           g.k % 64 == 0 && g.c % 4 == 0 && (g.w == 7 || g.w % 14 == 0);
-}
-// float32, groups 1, 3x3 (C a multiple of 4) or 7x7 (at most 4 input channels), stride 2, K a multiple of 64
-static bool kstride_supported(const Geo &g) {
-    if (!(g.dtype == NNV_F32 && g.groups == 1 && g.r == g.s && g.sh == 2 && g.sw == 2 && g.k % 64 == 0)) return false;
+    if (!(g.dtype == NNV_F32 && g.groups == 1 && g.r == g.s && g.sh == g.sw && g.k % 64 == 0)) return false;
     if ((size_t)g.c * g.h * g.w * 4 >= (1u << 31) || (size_t)g.k * g.c * g.r * g.s * 4 >= (1ull << 32)) return false;
-    if (g.r == 3) return g.c % 4 == 0;
-    return g.r == 7 && g.c <= 4;
-}
-static KStrideLayer kstride_layer(const Geo &g) {
-    KStrideLayer S{nullptr, nullptr, nullptr, nullptr, g.n, g.c, g.h, g.w, g.k, g.p, g.q, g.ph, g.pw, g.r, g.sh, 0, 0, 0, 0, 0, 0, 0};
-    kstride_geometry(S);
-    return S;
+    if (g.r == 3) return (g.sh == 1 || g.sh == 2) && g.c % 4 == 0;
+    return g.r == 7 && g.sh == 2 && g.c <= kKlStagedMaxC;
 }
 static KLaneLayer klane_layer(const Geo &g) {
-    KLaneLayer K{nullptr, nullptr, nullptr, nullptr, g.n, g.c, g.h, g.w, g.k, 0, 0, 0, 0, 0, 0};
+    KLaneLayer K{nullptr, nullptr, nullptr, nullptr, g.n, g.c, g.h, g.w, g.k, g.p, g.q, g.ph, g.pw, g.r, g.sh, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     klane_geometry(K);
     return K;
 }
 
 // Layers [0, n) (one storage type, n <= kMaxDirectLayers, each direct_many_supported): one launch of
-// 8-wavefront workgroups for the layers the two output-channel-lane kernels cover (3x3 stride 1;
-// 3x3 and 7x7 stride 2) and, for the others, one launch of 16-wavefront workgroups (the wavefronts
-// of a workgroup split the input channels: a deep layer is a chain of scalar-load round trips per
-// wavefront, the wide split shortens it; layers with fewer channels than wavefronts run a block per
-// wavefront).  A call without output-channel-lane layers splits the others by depth into a launch of
-// 16- and one of 4-wavefront workgroups.  Within a launch the longest wavefronts come first.  (All
-// in one launch, dealt out alternately, was measured: slower.)
+// 8-wavefront workgroups for the layers the output-channel-lane kernel covers and, for the others,
+// one launch of 16-wavefront workgroups (the wavefronts of a workgroup split the input channels: a
+// deep layer is a chain of scalar-load round trips per wavefront, the wide split shortens it; layers
+// with fewer channels than wavefronts run a block per wavefront).  A call without output-channel-lane
+// layers splits the others by depth into a launch of 16- and one of 4-wavefront workgroups.  Within
+// a launch the longest wavefronts come first.  (All in one launch, dealt out alternately, was
+// measured: slower.)
 hipError_t launch_direct_many(int n, const Geo *geos, const void *const *x, const void *const *w, const float *const *bias,
                               void *const *y, hipStream_t st_) {
     if (n <= 0) return hipSuccess;
@@ -979,27 +851,24 @@ hipError_t launch_direct_many(int n, const Geo *geos, const void *const *x, cons
     bool any_klane = false;
     for (int i = 0; i < n; ++i) {
         if ((geos[i].dtype == NNV_F16) != half || !slane_supported(geos[i])) return hipErrorInvalidValue;
-        any_klane = any_klane || klane_supported(geos[i]) || kstride_supported(geos[i]);
+        any_klane = any_klane || klane_supported(geos[i]);
     }
     // pass 0 / 1: workgroups of 16 / 4 wavefronts; pass 2: output-channel-lane layers, 8 wavefronts
     for (int pass = 0; pass < 3; ++pass) {
         const int waves = pass == 0 ? 16 : pass == 1 ? 4 : kKlWaves;
         int order[kMaxDirectLayers], m = 0;
-        long weight[kMaxDirectLayers];        // sort key: about the vector instructions of one wavefront
+        long weight[kMaxDirectLayers];        // sort key: about the FMAs of one wavefront
         for (int i = 0; i < n; ++i) {
             const Geo &g = geos[i];
             int p;
-            if (klane_supported(g) || kstride_supported(g)) p = 2;
+            if (klane_supported(g)) p = 2;
             else if (any_klane) p = 0;      // what is left are few layers of short work: one launch, and the wide channel split shortens their chains
             else p = g.c > 128 ? 0 : 1;
             if (p != pass) continue;
             order[m++] = i;
             if (klane_supported(g)) {
                 const KLaneLayer K = klane_layer(g);
-                weight[i] = (long)(g.c / K.cs) * K.tw * 18;
-            } else if (kstride_supported(g)) {
-                const KStrideLayer S = kstride_layer(g);
-                weight[i] = (long)(g.c / S.cs) * g.r * (2 * S.tw + g.r - 2 + g.r * S.tw);
+                weight[i] = (long)(g.c / K.cs) * g.r * g.r * K.tw * K.tr;
             } else {
                 weight[i] = (long)(g.c < waves ? g.c : ceil_div(g.c, waves)) * g.r * g.s * ((g.k % 8 == 0 && g.r <= 3) ? 8 : 4);
             }
@@ -1008,8 +877,7 @@ hipError_t launch_direct_many(int n, const Geo *geos, const void *const *x, cons
         std::stable_sort(order, order + m, [&](int a, int b) { return weight[a] > weight[b]; });
         DirectTable tbl{};
         long blocks = 0;
-        bool klane_in_launch = false;
-        int filter_floats = 0;      // staged filters of the 7x7 stride-2 layers of the launch
+        size_t klane_lds = 0;       // output-channel-lane launch: LDS floats of its largest layout
         for (int o = 0; o < m; ++o) {
             const Geo &g = geos[order[o]];
             const int i = order[o];
@@ -1017,17 +885,11 @@ hipError_t launch_direct_many(int n, const Geo *geos, const void *const *x, cons
             L.x = x[i]; L.w = static_cast<const float *>(w[i]); L.bias = bias ? bias[i] : nullptr; L.y = y[i];
             L.d = DirectParams{g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.sh, g.sw, g.ph, g.pw, g.p, g.q, g.cg, g.kg, 0, 0, 0, g.relu};
             tbl.block0[o] = (int)blocks;
-            if (pass == 2 && klane_supported(g)) {
+            if (pass == 2) {
                 const KLaneLayer K = klane_layer(g);
                 L.variant = 64;
                 blocks += klane_blocks(K);
-                klane_in_launch = true;
-            } else if (pass == 2) {
-                const KStrideLayer S = kstride_layer(g);
-                L.variant = 65;
-                blocks += kstride_blocks(S);
-                filter_floats = std::max(filter_floats, kstride_filter_floats(S));
-                klane_in_launch = true;
+                klane_lds = std::max<size_t>(klane_lds, (size_t)klane_lds_floats(K));
             } else {
                 const bool grid8 = g.r == 3 && g.sh == 1 && g.sw == 1 && g.h <= 7 && g.w <= 7 && g.ph <= 1 && g.pw <= 1;
                 const int tk = (g.k % 8 == 0 && g.r <= 3) ? 8 : 4;      // the launch holds plenty of blocks: 8 outputs per loaded pixel
@@ -1049,12 +911,12 @@ hipError_t launch_direct_many(int n, const Geo *geos, const void *const *x, cons
         for (int o = m; o < kMaxDirectLayers; ++o) tbl.block0[o] = INT_MAX;
         tbl.nblocks = (int)blocks;
         const int per_xcd = ceil_div(ceil_div((int)blocks, 8), 8) * 8;
-        const size_t lds = klane_in_launch ? ((size_t)filter_floats + (size_t)kKlWaves * 14 * 65 + (size_t)kKlWaves * 256) * sizeof(float) : (size_t)waves * 8 * 64 * sizeof(float);
+        const size_t lds = pass == 2 ? klane_lds * sizeof(float) : (size_t)waves * 8 * 64 * sizeof(float);
         if (lds > 64 * 1024) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(direct_conv_many_klane_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
         }
-        if (klane_in_launch) hipLaunchKernelGGL(direct_conv_many_klane_kernel, dim3(per_xcd * 8), dim3(64 * waves), lds, st_, tbl);
+        if (pass == 2) hipLaunchKernelGGL(direct_conv_many_klane_kernel, dim3(per_xcd * 8), dim3(64 * waves), lds, st_, tbl);
         else if (half) hipLaunchKernelGGL(direct_conv_many_kernel<__half>, dim3(per_xcd * 8), dim3(64 * waves), lds, st_, tbl);
         else hipLaunchKernelGGL(direct_conv_many_kernel<float>, dim3(per_xcd * 8), dim3(64 * waves), lds, st_, tbl);
     }

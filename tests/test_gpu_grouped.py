@@ -260,20 +260,23 @@ def test_direct_and_depthwise_layers_in_one_call(env, half):
         assert np.abs(a - b).max() <= (2e-3 if half else 2e-5) * np.abs(b).max(), c.layer.name
 
 
-# float32 3x3 stride-1 pad-1 layers with K a multiple of 64, C a multiple of 4 and rows of 7 or 14 n pixels
-# run with the lanes along the output channels: tiles of 2 rows x 7 or 14 columns
+# float32 layers with K a multiple of 64 that run with the lanes along the output channels: 3x3 at stride 1
+# (tiles of 2 rows x 7 or 14 columns) or 2 (one row), C a multiple of 4, taps of two channels at a time through
+# LDS; 7x7 (stride 2) with at most 4 channels, whole filters staged in LDS.  Pixels through LDS.
 KLANE = [
     Ly("kl_w7", 8, 7, 7, 64, 3, 1, 1),                       # 7-wide tiles, last row pair half empty
     Ly("kl_w14", 12, 14, 14, 64, 3, 1, 1),                   # one tile per row pair: both edges in it
-    Ly("kl_w28", 16, 6, 28, 128, 3, 1, 1),                   # a left and a right tile, two blocks of output channels
-    Ly("kl_w42", 4, 5, 42, 64, 3, 1, 1),                     # left, middle and right tiles; one channel group, odd H
+    Ly("kl_w28", 16, 6, 28, 128, 3, 1, 1),                   # two tiles per row pair, two blocks of output channels
+    Ly("kl_w42", 4, 5, 42, 64, 3, 1, 1),                     # three tiles; one pair of channel pairs, odd H
     Ly("kl_deep", 256, 7, 7, 64, 3, 1, 1),                   # eight wavefronts per tile
-    Ly("kl_c132", 132, 3, 14, 64, 3, 1, 1),                  # 33 channel groups over 8 wavefronts
+    Ly("kl_c132", 132, 3, 14, 64, 3, 1, 1),                  # 33 channel groups: one wavefront per tile
     Ly("kl_h1", 4, 1, 14, 64, 3, 1, 1),
     Ly("kl_n2", 8, 7, 14, 128, 3, 1, 1, n=2),
     Ly("kl_w56", 64, 4, 56, 64, 3, 1, 1),
-    # stride 2 (3x3 with C a multiple of 4, 7x7 with up to 4 channels; K a multiple of 64): lanes along the
-    # output channels too, one output row of 7 or 14 columns per tile, pixels handed round by v_readlane
+    Ly("kl_w15", 8, 9, 15, 64, 3, 1, 1),                     # Q = 15: a full tile and one column of a ragged one
+    Ly("kl_p0", 8, 9, 16, 64, 3, 1, 0),                      # no padding: Q = 14, P = 7
+    Ly("kl_p2", 4, 5, 10, 64, 3, 1, 2),                      # padding 2: Q = 12, P = 7
+    Ly("other_c3", 3, 10, 28, 64, 3, 1, 1),                  # three channels: not covered
     Ly("ks_stem28", 3, 28, 28, 64, 7, 2, 3),                 # 7x7: filters staged in LDS; Q = 14
     Ly("ks_stem42", 3, 12, 42, 128, 7, 2, 3, n=2),           # Q = 21: a full and a ragged tile, two blocks of output channels
     Ly("ks_stem_c4", 4, 9, 30, 64, 7, 2, 2),                 # four channels (even filter length, odd LDS stride), pad 2, Q = 14
@@ -286,9 +289,9 @@ KLANE = [
     Ly("ks_q17_p0", 12, 9, 35, 64, 3, 2, 0),                 # no padding, Q = 17: a full and a ragged tile
     Ly("other_s2", 16, 15, 15, 32, 3, 2, 1),                 # not covered (K = 32): the pixel-lane kernel in the same call
     Ly("other_s2_c6", 6, 14, 14, 64, 3, 2, 1),               # not covered (C = 6)
-    Ly("other_1x1_s2", 64, 14, 14, 128, 1, 2, 0),
-    Ly("other_w15", 8, 9, 15, 64, 3, 1, 1),
     Ly("other_c6", 6, 14, 14, 64, 3, 1, 1),
+    Ly("other_1x1_s2", 64, 14, 14, 128, 1, 2, 0),
+    Ly("other_5x5", 4, 12, 12, 64, 5, 1, 2),
 ]
 
 
