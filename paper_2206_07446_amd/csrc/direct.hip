@@ -345,7 +345,7 @@ __global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__rest
 // per lane and 7 filters per instruction, copies them to its LDS region as they come (filter k at
 // byte 72 k) and every lane reads its filter back: ten loads that touch some ten lines each
 // instead of five that touch 64.  The fetch for the next pair of channels is issued before this
-// pair is computed, the copy through LDS follows the computation.  7x7 layers with at most four
+// pair is computed, the copy to LDS sits between its two channels, the read after them.  7x7 layers with at most four
 // input channels (a stem): the 64 whole filters of the workgroup are staged once in LDS, row
 // stride odd, and read back a channel at a time.
 //
@@ -380,7 +380,9 @@ __host__ __device__ static inline void klane_geometry(KLaneLayer &L) {
     L.ntile = L.nseg * ((L.P + L.tr - 1) / L.tr);
     int cs = 1;
     if (!L.staged) {
-        cs = (L.st == 1 && L.C < 128) ? 4 : kKlWaves;
+        // about 32 channels per wavefront (measured against 16 and 64 at stride 1, 8 and 64 at stride 2)
+        cs = L.C / 32;
+        cs = cs >= 8 ? 8 : cs >= 4 ? 4 : cs >= 2 ? 2 : 1;
         while (cs > 1 && L.C % (4 * cs) != 0) cs >>= 1;
     }
     L.cs = cs;
@@ -490,9 +492,11 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
             };
             // (no lane is masked: lane 63 of a copy writes what lane 0 of the next one overwrites, LDS
             // operations of a wavefront complete in order, and the last copy runs 55 pairs past filter 63)
-            auto tap_stage = [&](const kl_f2 (&tmp)[10], float (&t)[18]) __attribute__((always_inline)) {
+            auto tap_copy = [&](const kl_f2 (&tmp)[10]) __attribute__((always_inline)) {
 #pragma unroll
                 for (int it = 0; it < 10; ++it) stage[it * 63 + lane] = tmp[it];
+            };
+            auto tap_take = [&](float (&t)[18]) __attribute__((always_inline)) {
 #pragma unroll
                 for (int m = 0; m < 9; ++m) {
                     const kl_f2 v = stage[lane * 9 + m];
@@ -516,7 +520,8 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
                 for (int l = 0; l < NLD; ++l) R[j][l] = buf_load<float>(xres, voff[l], (cbeg + j) * plane);
             }
             __builtin_amdgcn_sched_barrier(0);
-            tap_stage(tmp, t);
+            tap_copy(tmp);
+            tap_take(t);
             for (uint32_t c4 = cbeg; c4 < cendx; c4 += 4) {
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
@@ -534,8 +539,11 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
 #pragma unroll
                         for (int i = 0; i < 9; ++i) tj[i] = t[jj * 9 + i];
                         klane_channel<3, ST, TW, TR>(slot, tj, acc);
+                        // the next pair's taps go to LDS between the two channels (the staging area
+                        // holds nothing that is still needed: this pair's taps are in registers)
+                        if (jj == 0) tap_copy(tmp);
                     }
-                    tap_stage(tmp, t);
+                    tap_take(t);
                 }
             }
         }

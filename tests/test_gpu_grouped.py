@@ -268,11 +268,12 @@ KLANE = [
     Ly("kl_w14", 12, 14, 14, 64, 3, 1, 1),                   # one tile per row pair: both edges in it
     Ly("kl_w28", 16, 6, 28, 128, 3, 1, 1),                   # two tiles per row pair, two blocks of output channels
     Ly("kl_w42", 4, 5, 42, 64, 3, 1, 1),                     # three tiles; one pair of channel pairs, odd H
-    Ly("kl_deep", 256, 7, 7, 64, 3, 1, 1),                   # eight wavefronts per tile
+    Ly("kl_deep", 256, 7, 7, 64, 3, 1, 1),                   # eight wavefronts per tile (one per 32 channels)
+    Ly("kl_c128", 128, 4, 14, 64, 3, 1, 1),                  # four wavefronts per tile
     Ly("kl_c132", 132, 3, 14, 64, 3, 1, 1),                  # 33 channel groups: one wavefront per tile
     Ly("kl_h1", 4, 1, 14, 64, 3, 1, 1),
     Ly("kl_n2", 8, 7, 14, 128, 3, 1, 1, n=2),
-    Ly("kl_w56", 64, 4, 56, 64, 3, 1, 1),
+    Ly("kl_w56", 64, 4, 56, 64, 3, 1, 1),                    # two wavefronts per tile
     Ly("kl_w15", 8, 9, 15, 64, 3, 1, 1),                     # Q = 15: a full tile and one column of a ragged one
     Ly("kl_p0", 8, 9, 16, 64, 3, 1, 0),                      # no padding: Q = 14, P = 7
     Ly("kl_p2", 4, 5, 10, 64, 3, 1, 2),                      # padding 2: Q = 12, P = 7
@@ -281,11 +282,12 @@ KLANE = [
     Ly("ks_stem42", 3, 12, 42, 128, 7, 2, 3, n=2),           # Q = 21: a full and a ragged tile, two blocks of output channels
     Ly("ks_stem_c4", 4, 9, 30, 64, 7, 2, 2),                 # four channels (even filter length, odd LDS stride), pad 2, Q = 14
     Ly("ks_stem_c1", 1, 20, 20, 64, 7, 2, 0),                # one channel, no padding, Q = 7
-    Ly("ks_w28", 16, 10, 28, 128, 3, 2, 1),                  # Q = 14, four wavefronts per tile
+    Ly("ks_w28", 16, 10, 28, 128, 3, 2, 1),                  # Q = 14
+    Ly("ks_c128", 128, 6, 28, 64, 3, 2, 1),                  # four wavefronts per tile
     Ly("ks_deep", 256, 14, 14, 64, 3, 2, 1),                 # Q = 7: 7-wide tiles, eight wavefronts per tile
-    Ly("ks_w56", 64, 6, 56, 64, 3, 2, 1),                    # Q = 28: two tiles per row
-    Ly("ks_q13", 8, 7, 26, 64, 3, 2, 1, n=2),                # Q = 13: ragged tile; two wavefronts per tile
-    Ly("ks_q21", 4, 5, 42, 64, 3, 2, 1),                     # Q = 21: three 7-wide tiles, one wavefront per tile
+    Ly("ks_w56", 64, 6, 56, 64, 3, 2, 1),                    # Q = 28: two tiles per row, two wavefronts per tile
+    Ly("ks_q13", 8, 7, 26, 64, 3, 2, 1, n=2),                # Q = 13: ragged tile
+    Ly("ks_q21", 4, 5, 42, 64, 3, 2, 1),                     # Q = 21: three 7-wide tiles
     Ly("ks_q17_p0", 12, 9, 35, 64, 3, 2, 0),                 # no padding, Q = 17: a full and a ragged tile
     Ly("other_s2", 16, 15, 15, 32, 3, 2, 1),                 # not covered (K = 32): the pixel-lane kernel in the same call
     Ly("other_s2_c6", 6, 14, 14, 64, 3, 2, 1),               # not covered (C = 6)
