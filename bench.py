@@ -46,12 +46,12 @@ KIND_LABEL = {0: "direct", 1: "im2col_gemm", 2: "wino_f2", 3: "wino_f4", 4: "dep
 # kernels a grouped forward call of one kind launches for a stack (one launch group)
 PHASE_KERNELS = {
     "transform": "transform_kernel (grouped weight transformation, all kinds)",
-    "direct": "direct_conv_many_klane_kernel + direct_conv_many_kernel (direct convolution of all layers in two launches, vector ALU)",
+    "direct": "direct_conv_many_klane_kernel (direct convolution of all layers in one launch, lanes along the output channels, vector ALU)",
     "im2col_gemm": "gemm_items_kernel + gemm_reduce_kernel (implicit GEMM work items of all layers, float32 MFMA)",
     "wino_f2": "wino_f2: wino_input_many + wino_gemm_many (float32 MFMA) + wino_output_many",
     "wino_f4": "wino_f4: wino_input_many + wino_gemm_many (float32 MFMA) + wino_output_many",
 }
-PHASE_LAUNCHES = {"transform": 1, "direct": 2, "im2col_gemm": 2, "wino_f2": 3, "wino_f4": 3}
+PHASE_LAUNCHES = {"transform": 1, "direct": 1, "im2col_gemm": 2, "wino_f2": 3, "wino_f4": 3}
 
 
 def csrc_digest():
@@ -399,9 +399,9 @@ def main():
                           "transform_bytes_per_step": sum(p.transform_bytes for p in pairs)}))
         return
 
-    # A step is eleven kernel launches in five calls (the grouped transformation, then one grouped
+    # A step is ten kernel launches in five calls (the grouped transformation, then one grouped
     # forward call per kernel kind), issued eagerly on torch's current stream: the GPU needs about
-    # 0.36 ms for them, the host far less to enqueue them, so the queue never runs dry and the
+    # 0.35 ms for them, the host far less to enqueue them, so the queue never runs dry and the
     # events recorded between the calls split the step into its phases.
     phases = [("transform", transform_all)] + [(KIND_LABEL[k], (lambda k=k: forward_kind(k))) for k in step_kinds]
     for _ in range(max(args.warmup, 1)):

@@ -352,7 +352,7 @@ __global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__rest
 // The cs wavefronts of a tile split the channels; partial sums meet in LDS, one output row of the
 // tile per pass, in a fixed order, and the store runs with the columns fastest over the lanes.
 constexpr int kKlWaves = 8;                 // wavefronts per workgroup
-constexpr int kTapRegion = 64 * 18 + 112;   // LDS floats of a wavefront's tap staging area (64 filters x 2 channels x 9 taps, and the overrun of the last copy)
+constexpr int kTapRegion = 64 * 20;         // LDS floats of a wavefront's tap staging area: 3x3: 64 filters x 2 channels x 9 taps and the overrun of the last copy (1264); 1x1: 64 filters x 16 channels, row stride 20
 constexpr int kKlStagedMaxC = 4;            // whole filters are staged in LDS up to this many input channels
 typedef float kl_f4 __attribute__((ext_vector_type(4)));
 typedef float kl_f2 __attribute__((ext_vector_type(2)));
@@ -361,12 +361,12 @@ struct KLaneLayer {
     const float *x, *w, *bias;
     float *y;
     int N, C, H, W, K, P, Q, ph, pw, fs, st;
-    int staged;   // 1: whole filters in LDS (7x7, C <= kKlStagedMaxC), 0: taps of two channels at a time (3x3, C a multiple of 4)
+    int staged;   // 1: whole filters in LDS (7x7, C <= kKlStagedMaxC), 0: taps of two (3x3, C a multiple of 4) or sixteen (1x1, C a multiple of 16) channels at a time
     int tw;       // tile width: 14, or 7 for a 3x3 layer whose Q is an odd multiple of 7 (the last tile of a row may be ragged)
     int tr;       // tile rows: 2 at stride 1, 1 at stride 2
     int nseg;     // ceil(Q / tw)
     int ntile;    // nseg * ceil(P / tr)
-    int cs;       // wavefronts per tile (1, 2, 4 or 8): each takes C / cs channels, a multiple of 4; staged: 1
+    int cs;       // wavefronts per tile (1, 2, 4 or 8): each takes C / cs channels, a multiple of 4 (3x3) or 16 (1x1); staged: 1
     int wgt;      // workgroups per (image, block of 64 output channels) = ceil(ntile / (kKlWaves / cs))
     int ts;       // staged: row stride (floats) of the filters in LDS, odd
     int relu;
@@ -374,16 +374,16 @@ struct KLaneLayer {
 // tile geometry of a layer (the same arithmetic sizes the launch on the host and places a workgroup on the device)
 __host__ __device__ static inline void klane_geometry(KLaneLayer &L) {
     L.staged = L.fs == 7;
-    L.tw = (L.fs == 3 && L.Q % 7 == 0 && L.Q % 14 != 0) ? 7 : 14;
+    L.tw = (L.fs <= 3 && L.Q % 7 == 0 && L.Q % 14 != 0) ? 7 : 14;
     L.tr = L.st == 1 ? 2 : 1;
     L.nseg = (L.Q + L.tw - 1) / L.tw;
     L.ntile = L.nseg * ((L.P + L.tr - 1) / L.tr);
     int cs = 1;
     if (!L.staged) {
-        // about 32 channels per wavefront (measured against 16 and 64 at stride 1, 8 and 64 at stride 2)
-        cs = L.C / 32;
+        // 3x3: about 32 channels per wavefront (measured against 16 and 64 at stride 1, 8 and 64 at stride 2); 1x1: 128
+        cs = L.C / (L.fs == 3 ? 32 : 128);
         cs = cs >= 8 ? 8 : cs >= 4 ? 4 : cs >= 2 ? 2 : 1;
-        while (cs > 1 && L.C % (4 * cs) != 0) cs >>= 1;
+        while (cs > 1 && L.C % ((L.fs == 3 ? 4 : 16) * cs) != 0) cs >>= 1;
     }
     L.cs = cs;
     L.wgt = (L.ntile + kKlWaves / cs - 1) / (kKlWaves / cs);
@@ -441,7 +441,7 @@ __device__ __forceinline__ void klane_channel(const float *slot, const float (&t
 
 template <int FS, int ST, int TW, int TR, bool STAGED>
 __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, float *lds) {
-    static_assert(STAGED || FS == 3, "taps of two channels at a time: 3x3 only");
+    static_assert(STAGED || FS == 3 || FS == 1, "taps of a few channels at a time: 3x3 and 1x1");
     constexpr int NR = (TR - 1) * ST + FS, NPX = (TW - 1) * ST + FS, NF = NR * NPX, NLD = (NF + 63) / 64;
     static_assert(NLD * 64 <= 256, "pixel slot");
     const int lane = threadIdx.x & 63;
@@ -459,22 +459,85 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
     constexpr int OWS = STAGED ? 14 * 65 : kTapRegion;       // floats from one wavefront's output rows to the next one's
     float *out = lds + klane_filter_floats(L);
     float *slot = out + kKlWaves * OWS + wave * 256;
-    // the lane's pixels in the NLD loads of a channel
+    // the lane's pixels in the NLD loads of a channel (1x1: a load holds two channels, 32 lanes each)
+    constexpr int LPC = FS == 1 ? 32 : 64;
+    static_assert(FS != 1 || NF <= 32, "two channels per pixel load");
     uint32_t voff[NLD];
 #pragma unroll
     for (int j = 0; j < NLD; ++j) {
-        const int f = j * 64 + lane;
+        const int f = j * 64 + (lane & (LPC - 1));
         const int r = f / NPX, i = f - r * NPX;
         const int ih = ST * p0 - L.ph + r, iw = ST * q0 - L.pw + i;
         const bool ok = live && f < NF && ih >= 0 && ih < L.H && iw >= 0 && iw < L.W;
-        voff[j] = ok ? (uint32_t)((ih * L.W + iw) * 4) : kOobOffset;
+        voff[j] = ok ? (uint32_t)(((lane / LPC) * HW + ih * L.W + iw) * 4) : kOobOffset;
     }
     const __amdgpu_buffer_rsrc_t xres = make_rsrc(L.x + (size_t)img * L.C * HW, (uint32_t)((size_t)L.C * HW * 4));
     const uint32_t plane = (uint32_t)HW * 4u;
     float acc[TR * TW];
 #pragma unroll
     for (int q = 0; q < TR * TW; ++q) acc[q] = 0.f;
-    if constexpr (!STAGED) {
+    if constexpr (!STAGED && FS == 1) {
+        if (live) {
+            // taps of 16 channels (64 contiguous bytes per filter) at a time: 16 bytes per lane, 16 filters
+            // per instruction, copied to LDS with a row stride of 20 floats (the 16-byte reads of
+            // eight neighbouring lanes then cover all banks), read back by the filter's lane
+            const uint32_t rowbytes = (uint32_t)L.C * 4u;
+            const __amdgpu_buffer_rsrc_t wres = make_rsrc(L.w, (uint32_t)((size_t)L.K * rowbytes));
+            const uint32_t tvoff = (uint32_t)(kb * 64 + (lane >> 2)) * rowbytes + (uint32_t)(lane & 3) * 16u;
+            float *stage = out + wave * OWS;
+            auto tap_fetch = [&](kl_f4 (&tmp)[4], uint32_t c) __attribute__((always_inline)) {
+#pragma unroll
+                for (int it = 0; it < 4; ++it)
+                    tmp[it] = __builtin_bit_cast(kl_f4, __builtin_amdgcn_raw_buffer_load_b128(wres, tvoff, c * 4u + (uint32_t)(it * 16) * rowbytes, 0));
+            };
+            auto tap_copy = [&](const kl_f4 (&tmp)[4]) __attribute__((always_inline)) {
+#pragma unroll
+                for (int it = 0; it < 4; ++it) *reinterpret_cast<kl_f4 *>(stage + (it * 16 + (lane >> 2)) * 20 + (lane & 3) * 4) = tmp[it];
+            };
+            auto tap_take = [&](float (&t)[16]) __attribute__((always_inline)) {
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    const kl_f4 v = *reinterpret_cast<const kl_f4 *>(stage + lane * 20 + 4 * m);
+                    t[4 * m] = v.x; t[4 * m + 1] = v.y; t[4 * m + 2] = v.z; t[4 * m + 3] = v.w;
+                }
+            };
+            const uint32_t per = (uint32_t)(L.C / L.cs), cbeg = (uint32_t)cw * per, cendx = cbeg + per;
+            // pixels of four channel pairs in flight (slot j: channels c16 + 2 j and + 1 of the eight pairs
+            // of a group alternate over the slots); requests in a pinned order as below
+            kl_f4 tmp[4];
+            float t[16];
+            tap_fetch(tmp, cbeg);
+            float R[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                __builtin_amdgcn_sched_barrier(0);
+                R[j] = buf_load<float>(xres, voff[0], (cbeg + 2 * j) * plane);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            tap_copy(tmp);
+            tap_take(t);
+            for (uint32_t c16 = cbeg; c16 < cendx; c16 += 16) {
+                // (the last group fetches itself again: in range, never used)
+                tap_fetch(tmp, min(c16 + 16, cendx - 16));
+#pragma unroll
+                for (int jp = 0; jp < 8; ++jp) {
+                    const int j = jp & 3;
+                    slot[lane] = R[j];
+                    const uint32_t cn = min(c16 + 2 * jp + 8, cendx - 2);
+                    R[j] = buf_load<float>(xres, voff[0], cn * plane);
+                    const float t0[1] = {t[2 * jp]}, t1[1] = {t[2 * jp + 1]};
+                    klane_channel<1, ST, TW, TR>(slot, t0, acc);
+                    klane_channel<1, ST, TW, TR>(slot + 32, t1, acc);
+                    // (the accumulators are pinned here: left alone, the compiler sinks the FMAs of many
+                    // channels below their LDS reads and parks the pixels in scratch memory meanwhile)
+#pragma unroll
+                    for (int q = 0; q < TR * TW; ++q) asm volatile("" : "+v"(acc[q]));
+                    if (jp == 3) tap_copy(tmp);
+                }
+                tap_take(t);
+            }
+        }
+    } else if constexpr (!STAGED) {
         if (live) {
             const uint32_t rowbytes = (uint32_t)L.C * 36u;
             const __amdgpu_buffer_rsrc_t wres = make_rsrc(L.w, (uint32_t)((size_t)L.K * rowbytes));
@@ -699,6 +762,10 @@ __global__ __launch_bounds__(1024) void direct_conv_many_klane_kernel(const Dire
                  L.d.P, L.d.Q, L.d.ph, L.d.pw, L.d.R, L.d.sh, 0, 0, 0, 0, 0, 0, 0, 0, L.d.relu};
     klane_geometry(K);
     if (K.fs == 7) klane_tile<7, 2, 14, 1, true>(K, lblk, lds);      // (a 7-wide tile of a 7x7 filter would not pay: 19 pixels for 7 outputs)
+    else if (K.fs == 1 && K.st == 1 && K.tw == 7) klane_tile<1, 1, 7, 2, false>(K, lblk, lds);
+    else if (K.fs == 1 && K.st == 1) klane_tile<1, 1, 14, 2, false>(K, lblk, lds);
+    else if (K.fs == 1 && K.tw == 7) klane_tile<1, 2, 7, 1, false>(K, lblk, lds);
+    else if (K.fs == 1) klane_tile<1, 2, 14, 1, false>(K, lblk, lds);
     else if (K.st == 1 && K.tw == 7) klane_tile<3, 1, 7, 2, false>(K, lblk, lds);
     else if (K.st == 1) klane_tile<3, 1, 14, 2, false>(K, lblk, lds);
     else if (K.tw == 7) klane_tile<3, 2, 7, 1, false>(K, lblk, lds);
@@ -835,6 +902,7 @@ static bool klane_supported(const Geo &g) {
     if (!(g.dtype == NNV_F32 && g.groups == 1 && g.r == g.s && g.sh == g.sw && g.k % 64 == 0)) return false;
     if ((size_t)g.c * g.h * g.w * 4 >= (1u << 31) || (size_t)g.k * g.c * g.r * g.s * 4 >= (1ull << 32)) return false;
     if (g.r == 3) return (g.sh == 1 || g.sh == 2) && g.c % 4 == 0;
+    if (g.r == 1) return (g.sh == 1 || g.sh == 2) && g.c % 16 == 0;
     return g.r == 7 && g.sh == 2 && g.c <= kKlStagedMaxC;
 }
 static KLaneLayer klane_layer(const Geo &g) {

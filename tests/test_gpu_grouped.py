@@ -262,7 +262,8 @@ def test_direct_and_depthwise_layers_in_one_call(env, half):
 
 # float32 layers with K a multiple of 64 that run with the lanes along the output channels: 3x3 at stride 1
 # (tiles of 2 rows x 7 or 14 columns) or 2 (one row), C a multiple of 4, taps of two channels at a time through
-# LDS; 7x7 (stride 2) with at most 4 channels, whole filters staged in LDS.  Pixels through LDS.
+# LDS; 1x1 at stride 1 or 2, C a multiple of 16, taps of sixteen channels at a time; 7x7 (stride 2) with at
+# most 4 channels, whole filters staged in LDS.  Pixels through LDS.
 KLANE = [
     Ly("kl_w7", 8, 7, 7, 64, 3, 1, 1),                       # 7-wide tiles, last row pair half empty
     Ly("kl_w14", 12, 14, 14, 64, 3, 1, 1),                   # one tile per row pair: both edges in it
@@ -292,7 +293,13 @@ KLANE = [
     Ly("other_s2", 16, 15, 15, 32, 3, 2, 1),                 # not covered (K = 32): the pixel-lane kernel in the same call
     Ly("other_s2_c6", 6, 14, 14, 64, 3, 2, 1),               # not covered (C = 6)
     Ly("other_c6", 6, 14, 14, 64, 3, 1, 1),
-    Ly("other_1x1_s2", 64, 14, 14, 128, 1, 2, 0),
+    Ly("k1_s2", 64, 14, 14, 128, 1, 2, 0),                   # 1x1 (C a multiple of 16): Q = 7, 7-wide one-row tiles
+    Ly("k1_s2_w28", 48, 9, 55, 64, 1, 2, 0),                 # Q = 28, P = 5; three groups of 16 channels
+    Ly("k1_w7", 256, 7, 7, 64, 1, 1, 0),                     # stride 1: two-row tiles, two wavefronts per tile
+    Ly("k1_w28", 32, 5, 28, 128, 1, 1, 0, n=2),              # two tiles per row pair, odd P
+    Ly("k1_w15", 16, 4, 15, 64, 1, 1, 0),                    # ragged tile
+    Ly("k1_deep", 1024, 7, 7, 64, 1, 1, 0),                  # eight wavefronts per tile
+    Ly("other_1x1_c24", 24, 14, 14, 64, 1, 1, 0),            # not covered (C = 24)
     Ly("other_5x5", 4, 12, 12, 64, 5, 1, 2),
 ]
 
