@@ -351,7 +351,7 @@ __global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__rest
 //
 // The cs wavefronts of a tile split the channels; partial sums meet in LDS, one output row of the
 // tile per pass, in a fixed order, and the store runs with the columns fastest over the lanes.
-constexpr int kKlWaves = 8;                 // wavefronts per workgroup
+constexpr int kKlWaves = 8;                 // wavefronts per workgroup (16, with a 16-way channel split for the deepest layers, was measured: slower on every stack)
 constexpr int kTapRegion = 64 * 20;         // LDS floats of a wavefront's tap staging area: 3x3: 64 filters x 2 channels x 9 taps and the overrun of the last copy (1264); 1x1: 64 filters x 16 channels, row stride 20
 constexpr int kKlStagedMaxC = 4;            // whole filters are staged in LDS up to this many input channels
 typedef float kl_f4 __attribute__((ext_vector_type(4)));
@@ -375,6 +375,9 @@ struct KLaneLayer {
 __host__ __device__ static inline void klane_geometry(KLaneLayer &L) {
     L.staged = L.fs == 7;
     L.tw = (L.fs <= 3 && L.Q % 7 == 0 && L.Q % 14 != 0) ? 7 : 14;
+    // two output rows per tile at stride 1: a tap then feeds twice the FMAs.  (One-row tiles for the
+    // 512-channel layers on 7 x 7 planes, whose 256 long wavefronts end a launch of small layers, were
+    // measured: 82 against 76 us; two pairs of taps in flight instead of one changed nothing.)
     L.tr = L.st == 1 ? 2 : 1;
     L.nseg = (L.Q + L.tw - 1) / L.tw;
     L.ntile = L.nseg * ((L.P + L.tr - 1) / L.tr);
