@@ -32,17 +32,15 @@ VALU_F32_PEAK_TFLOPS = 157.3  # float32 vector peak (packed FMA; plain FMA, as c
 # the digest below; once a source file changes, `traffic` is reported as null until the counters
 # are taken again.
 MEASURED_TRAFFIC = {
-    "csrc_sha256_16": "ec31e47dafbd4b95",
+    "csrc_sha256_16": "f03163c899327123",
     "MB_per_step": {
         "transform": (45.0, 262.9),
-        "direct": (107.2, 10.0),
+        "direct": (77.8, 10.2),
         "im2col_gemm": (97.5, 23.0),
         "wino_f2": (137.8, 50.7),
         "wino_f4": (198.3, 38.4),
     },
 }
-
-KIND_LABEL = {0: "direct", 1: "im2col_gemm", 2: "wino_f2", 3: "wino_f4", 4: "depthwise", 5: "wino_f6"}
 # kernels a grouped forward call of one kind launches for a stack (one launch group)
 PHASE_KERNELS = {
     "transform": "transform_kernel (grouped weight transformation, all kinds)",
