@@ -44,7 +44,7 @@ MEASURED_TRAFFIC = {
 # kernels a grouped forward call of one kind launches for a stack (one launch group)
 PHASE_KERNELS = {
     "transform": "transform_kernel (grouped weight transformation, all kinds)",
-    "direct": "direct_conv_many_klane_kernel (direct convolution of all layers in one launch, lanes along the output channels, vector ALU)",
+    "direct": "direct_conv_many_klane_kernel<float> (direct convolution of all layers in one launch, lanes along the output channels, vector ALU)",
     "im2col_gemm": "gemm_items_kernel + gemm_reduce_kernel (implicit GEMM work items of all layers, float32 MFMA)",
     "wino_f2": "wino_f2: wino_input_many + wino_gemm_many (float32 MFMA) + wino_output_many",
     "wino_f4": "wino_f4: wino_input_many + wino_gemm_many (float32 MFMA) + wino_output_many",

@@ -318,7 +318,8 @@ __global__ __launch_bounds__(1024) void direct_conv_slane_kernel(const T *__rest
     direct_slane_block<T, TK, FS, GRID8>(x, w, bias, y, d, lblk, blockDim.x >> 6, lds);
 }
 
-// ---- float32 3x3 (stride 1 or 2) and 7x7 (stride 2) layers with the lanes along the output channels
+// ---- 3x3 and 1x1 (stride 1 or 2) and 7x7 (stride 2) layers with the lanes along the output channels
+// (float32 arithmetic; x and y in float32 or float16, the weights are the raw float32 tensor)
 //
 // lane = output channel (64 per wavefront), tile = TR output rows x TW columns held as TR * TW
 // accumulators per lane.  The two operands swap roles against the kernel above.
@@ -358,8 +359,9 @@ typedef float kl_f4 __attribute__((ext_vector_type(4)));
 typedef float kl_f2 __attribute__((ext_vector_type(2)));
 
 struct KLaneLayer {
-    const float *x, *w, *bias;
-    float *y;
+    const void *x;      // float32 or float16 activations (the kernel's storage type T)
+    const float *w, *bias;
+    void *y;
     int N, C, H, W, K, P, Q, ph, pw, fs, st;
     int staged;   // 1: whole filters in LDS (7x7, C <= kKlStagedMaxC), 0: taps of two (3x3, C a multiple of 4) or sixteen (1x1, C a multiple of 16) channels at a time
     int tw;       // tile width: 14, or 7 for a 3x3 layer whose Q is an odd multiple of 7 (the last tile of a row may be ragged)
@@ -442,8 +444,9 @@ __device__ __forceinline__ void klane_channel(const float *slot, const float (&t
     }
 }
 
-template <int FS, int ST, int TW, int TR, bool STAGED>
+template <typename T, int FS, int ST, int TW, int TR, bool STAGED>
 __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, float *lds) {
+    constexpr int ESZ = sizeof(T);
     static_assert(STAGED || FS == 3 || FS == 1, "taps of a few channels at a time: 3x3 and 1x1");
     constexpr int NR = (TR - 1) * ST + FS, NPX = (TW - 1) * ST + FS, NF = NR * NPX, NLD = (NF + 63) / 64;
     static_assert(NLD * 64 <= 256, "pixel slot");
@@ -472,10 +475,10 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
         const int r = f / NPX, i = f - r * NPX;
         const int ih = ST * p0 - L.ph + r, iw = ST * q0 - L.pw + i;
         const bool ok = live && f < NF && ih >= 0 && ih < L.H && iw >= 0 && iw < L.W;
-        voff[j] = ok ? (uint32_t)(((lane / LPC) * HW + ih * L.W + iw) * 4) : kOobOffset;
+        voff[j] = ok ? (uint32_t)(((lane / LPC) * HW + ih * L.W + iw) * ESZ) : kOobOffset;
     }
-    const __amdgpu_buffer_rsrc_t xres = make_rsrc(L.x + (size_t)img * L.C * HW, (uint32_t)((size_t)L.C * HW * 4));
-    const uint32_t plane = (uint32_t)HW * 4u;
+    const __amdgpu_buffer_rsrc_t xres = make_rsrc(static_cast<const T *>(L.x) + (size_t)img * L.C * HW, (uint32_t)((size_t)L.C * HW * ESZ));
+    const uint32_t plane = (uint32_t)(HW * ESZ);
     float acc[TR * TW];
 #pragma unroll
     for (int q = 0; q < TR * TW; ++q) acc[q] = 0.f;
@@ -514,7 +517,7 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 __builtin_amdgcn_sched_barrier(0);
-                R[j] = buf_load<float>(xres, voff[0], (cbeg + 2 * j) * plane);
+                R[j] = buf_load_x<T>(xres, voff[0], (cbeg + 2 * j) * plane);
             }
             __builtin_amdgcn_sched_barrier(0);
             tap_copy(tmp);
@@ -527,7 +530,7 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
                     const int j = jp & 3;
                     slot[lane] = R[j];
                     const uint32_t cn = min(c16 + 2 * jp + 8, cendx - 2);
-                    R[j] = buf_load<float>(xres, voff[0], cn * plane);
+                    R[j] = buf_load_x<T>(xres, voff[0], cn * plane);
                     const float t0[1] = {t[2 * jp]}, t1[1] = {t[2 * jp + 1]};
                     klane_channel<1, ST, TW, TR>(slot, t0, acc);
                     klane_channel<1, ST, TW, TR>(slot + 32, t1, acc);
@@ -583,7 +586,7 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
             for (int j = 0; j < 4; ++j) {
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int l = 0; l < NLD; ++l) R[j][l] = buf_load<float>(xres, voff[l], (cbeg + j) * plane);
+                for (int l = 0; l < NLD; ++l) R[j][l] = buf_load_x<T>(xres, voff[l], (cbeg + j) * plane);
             }
             __builtin_amdgcn_sched_barrier(0);
             tap_copy(tmp);
@@ -600,7 +603,7 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
                         for (int l = 0; l < NLD; ++l) slot[l * 64 + lane] = R[j][l];
                         const uint32_t cn = min(c4 + j + 4, cendx - 1);
 #pragma unroll
-                        for (int l = 0; l < NLD; ++l) R[j][l] = buf_load<float>(xres, voff[l], cn * plane);
+                        for (int l = 0; l < NLD; ++l) R[j][l] = buf_load_x<T>(xres, voff[l], cn * plane);
                         float tj[9];
 #pragma unroll
                         for (int i = 0; i < 9; ++i) tj[i] = t[jj * 9 + i];
@@ -638,13 +641,13 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
             const float *mine = lds + lane * L.ts;
             float cur[NLD], nxt[NLD];
 #pragma unroll
-            for (int l = 0; l < NLD; ++l) nxt[l] = buf_load<float>(xres, voff[l], 0u);
+            for (int l = 0; l < NLD; ++l) nxt[l] = buf_load_x<T>(xres, voff[l], 0u);
             for (int c = 0; c < L.C; ++c) {
 #pragma unroll
                 for (int l = 0; l < NLD; ++l) cur[l] = nxt[l];
                 const uint32_t cn = (uint32_t)min(c + 1, L.C - 1);
 #pragma unroll
-                for (int l = 0; l < NLD; ++l) nxt[l] = buf_load<float>(xres, voff[l], cn * plane);
+                for (int l = 0; l < NLD; ++l) nxt[l] = buf_load_x<T>(xres, voff[l], cn * plane);
 #pragma unroll
                 for (int l = 0; l < NLD; ++l) slot[l * 64 + lane] = cur[l];
                 float tc[FS * FS];
@@ -672,7 +675,7 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
                 float v = 0.f;
                 for (int ws = 0; ws < L.cs; ++ws) v += out[(w0 + ws) * OWS + q * 65 + k];
                 const float b = L.bias ? L.bias[kb * 64 + k] : 0.f;
-                L.y[ybase + ((size_t)k * L.P + p0 + r) * L.Q + q0 + q] = act(v + b, L.relu);
+                st<T>(static_cast<T *>(L.y), ybase + ((size_t)k * L.P + p0 + r) * L.Q + q0 + q, act(v + b, L.relu));
             }
         }
         if (TR > 1) __syncthreads();
@@ -753,7 +756,8 @@ __global__ __launch_bounds__(1024) void direct_conv_many_kernel(const DirectTabl
     }
 }
 
-// Output-channel-lane layers (variant 64, float32), kKlWaves wavefronts per workgroup.
+// Output-channel-lane layers (variant 64), kKlWaves wavefronts per workgroup; T: storage type of x and y.
+template <typename T>
 __global__ __launch_bounds__(1024) void direct_conv_many_klane_kernel(const DirectTable tbl_arg) {
     extern __shared__ __align__(16) float lds[];      // klane_lds_floats of the launch's largest layer
     const DirectTablePtr tbl = (DirectTablePtr)__builtin_amdgcn_kernarg_segment_ptr();
@@ -761,18 +765,18 @@ __global__ __launch_bounds__(1024) void direct_conv_many_klane_kernel(const Dire
     if (b >= tbl->nblocks) return;
     DirectLayer L;
     const int lblk = direct_many_lookup(tbl, b, L);
-    KLaneLayer K{static_cast<const float *>(L.x), L.w, L.bias, static_cast<float *>(L.y), L.d.N, L.d.C, L.d.H, L.d.W, L.d.K,
+    KLaneLayer K{L.x, L.w, L.bias, L.y, L.d.N, L.d.C, L.d.H, L.d.W, L.d.K,
                  L.d.P, L.d.Q, L.d.ph, L.d.pw, L.d.R, L.d.sh, 0, 0, 0, 0, 0, 0, 0, 0, L.d.relu};
     klane_geometry(K);
-    if (K.fs == 7) klane_tile<7, 2, 14, 1, true>(K, lblk, lds);      // (a 7-wide tile of a 7x7 filter would not pay: 19 pixels for 7 outputs)
-    else if (K.fs == 1 && K.st == 1 && K.tw == 7) klane_tile<1, 1, 7, 2, false>(K, lblk, lds);
-    else if (K.fs == 1 && K.st == 1) klane_tile<1, 1, 14, 2, false>(K, lblk, lds);
-    else if (K.fs == 1 && K.tw == 7) klane_tile<1, 2, 7, 1, false>(K, lblk, lds);
-    else if (K.fs == 1) klane_tile<1, 2, 14, 1, false>(K, lblk, lds);
-    else if (K.st == 1 && K.tw == 7) klane_tile<3, 1, 7, 2, false>(K, lblk, lds);
-    else if (K.st == 1) klane_tile<3, 1, 14, 2, false>(K, lblk, lds);
-    else if (K.tw == 7) klane_tile<3, 2, 7, 1, false>(K, lblk, lds);
-    else klane_tile<3, 2, 14, 1, false>(K, lblk, lds);
+    if (K.fs == 7) klane_tile<T, 7, 2, 14, 1, true>(K, lblk, lds);      // (a 7-wide tile of a 7x7 filter would not pay: 19 pixels for 7 outputs)
+    else if (K.fs == 1 && K.st == 1 && K.tw == 7) klane_tile<T, 1, 1, 7, 2, false>(K, lblk, lds);
+    else if (K.fs == 1 && K.st == 1) klane_tile<T, 1, 1, 14, 2, false>(K, lblk, lds);
+    else if (K.fs == 1 && K.tw == 7) klane_tile<T, 1, 2, 7, 1, false>(K, lblk, lds);
+    else if (K.fs == 1) klane_tile<T, 1, 2, 14, 1, false>(K, lblk, lds);
+    else if (K.st == 1 && K.tw == 7) klane_tile<T, 3, 1, 7, 2, false>(K, lblk, lds);
+    else if (K.st == 1) klane_tile<T, 3, 1, 14, 2, false>(K, lblk, lds);
+    else if (K.tw == 7) klane_tile<T, 3, 2, 7, 1, false>(K, lblk, lds);
+    else klane_tile<T, 3, 2, 14, 1, false>(K, lblk, lds);
 }
 
 struct DirectPlan {
@@ -897,12 +901,12 @@ static hipError_t launch_direct_t(const Geo &g, const T *x, const float *w, cons
 
 bool direct_many_supported(const Geo &g) { return slane_supported(g); }
 
-// float32, groups 1, K a multiple of 64; 3x3 at stride 1 or 2 with C a multiple of 4; 7x7 at stride 2
+// groups 1, K a multiple of 64; 3x3 at stride 1 or 2 with C a multiple of 4; 1x1 with C a multiple of 16; 7x7 at stride 2
 // with at most kKlStagedMaxC channels.  (A 3x3 first layer with three channels through the staged
 // path was measured: its 1792 short tiles lengthen the launch of a VGG-16-shaped stack by more
 // than the 19 us the layer takes with the lanes along the pixels.)
 static bool klane_supported(const Geo &g) {
-    if (!(g.dtype == NNV_F32 && g.groups == 1 && g.r == g.s && g.sh == g.sw && g.k % 64 == 0)) return false;
+    if (!(g.groups == 1 && g.r == g.s && g.sh == g.sw && g.k % 64 == 0)) return false;
     if ((size_t)g.c * g.h * g.w * 4 >= (1u << 31) || (size_t)g.k * g.c * g.r * g.s * 4 >= (1ull << 32)) return false;
     if (g.r == 3) return (g.sh == 1 || g.sh == 2) && g.c % 4 == 0;
     if (g.r == 1) return (g.sh == 1 || g.sh == 2) && g.c % 16 == 0;
@@ -992,10 +996,12 @@ hipError_t launch_direct_many(int n, const Geo *geos, const void *const *x, cons
         const int per_xcd = ceil_div(ceil_div((int)blocks, 8), 8) * 8;
         const size_t lds = pass == 2 ? klane_lds * sizeof(float) : (size_t)waves * 8 * 64 * sizeof(float);
         if (lds > 64 * 1024) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(direct_conv_many_klane_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            const void *fn = half ? reinterpret_cast<const void *>(direct_conv_many_klane_kernel<__half>) : reinterpret_cast<const void *>(direct_conv_many_klane_kernel<float>);
+            hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
         }
-        if (pass == 2) hipLaunchKernelGGL(direct_conv_many_klane_kernel, dim3(per_xcd * 8), dim3(64 * waves), lds, st_, tbl);
+        if (pass == 2 && half) hipLaunchKernelGGL(direct_conv_many_klane_kernel<__half>, dim3(per_xcd * 8), dim3(64 * waves), lds, st_, tbl);
+        else if (pass == 2) hipLaunchKernelGGL(direct_conv_many_klane_kernel<float>, dim3(per_xcd * 8), dim3(64 * waves), lds, st_, tbl);
         else if (half) hipLaunchKernelGGL(direct_conv_many_kernel<__half>, dim3(per_xcd * 8), dim3(64 * waves), lds, st_, tbl);
         else hipLaunchKernelGGL(direct_conv_many_kernel<float>, dim3(per_xcd * 8), dim3(64 * waves), lds, st_, tbl);
     }

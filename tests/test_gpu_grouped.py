@@ -304,9 +304,10 @@ KLANE = [
 ]
 
 
-def test_direct_output_channel_lanes(env):
+@pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
+def test_direct_output_channel_lanes(env, half):
     nnv, torch = env
-    cases = [Case(nnv, torch, l, nnv.DIRECT, False, 1700 + i, bias=(i % 2 == 0)) for i, l in enumerate(KLANE)]
+    cases = [Case(nnv, torch, l, nnv.DIRECT, half, 1700 + i, bias=(i % 2 == 0)) for i, l in enumerate(KLANE)]
     run_grouped(nnv, torch, cases)
     run_grouped(nnv, torch, cases, relu=True)
 
