@@ -41,6 +41,8 @@ MEASURED_TRAFFIC = {
         "wino_f4": (198.3, 38.4),
     },
 }
+
+KIND_LABEL = {0: "direct", 1: "im2col_gemm", 2: "wino_f2", 3: "wino_f4", 4: "depthwise", 5: "wino_f6"}
 # kernels a grouped forward call of one kind launches for a stack (one launch group)
 PHASE_KERNELS = {
     "transform": "transform_kernel (grouped weight transformation, all kinds)",

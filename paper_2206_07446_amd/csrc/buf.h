@@ -50,4 +50,21 @@ __device__ static inline int xcd_logical_tile(int total) {
 }
 static inline unsigned xcd_grid(int total) { return (unsigned)(((total + 7) / 8) * 8); }
 
+// Many-layer launches: a workgroup (or wavefront) finds its layer in an ascending table of first
+// block numbers that lies in the kernel-argument segment (at most 64 entries, INT_MAX beyond the used
+// ones, entry 0 is 0).  Lane l looks at entry l; the entries that b has reached are a prefix of the
+// lanes, so one vector load and a ballot give the index.  (A chain of scalar comparisons over the
+// table, the first version, took a wavefront 2 us on a busy chip: half the life of a depthwise
+// wavefront.)  b must be uniform over the wavefront.  Returns the index; first = that entry.
+template <int N>
+__device__ static inline int table_find(const __attribute__((address_space(4))) int *table, const int b, int &first) {
+    static_assert(N <= 64, "one table entry per lane");
+    const int lane = threadIdx.x & 63;
+    const int *t = reinterpret_cast<const int *>(reinterpret_cast<uintptr_t>(table));
+    const int mine = lane < N ? t[lane] : 0x7fffffff;
+    const int li = __builtin_popcountll(__ballot(b >= mine)) - 1;
+    first = __builtin_amdgcn_readlane(mine, li);
+    return li;
+}
+
 }  // namespace nnv

@@ -704,12 +704,8 @@ typedef const __attribute__((address_space(4))) DirectTable *DirectTablePtr;
 
 // Finds the layer of logical block b in the table and copies its record; returns the index of the block within the layer.
 __device__ __forceinline__ int direct_many_lookup(const DirectTablePtr tbl, const int b, DirectLayer &L) {
-    int li = 0, first = 0;
-#pragma unroll
-    for (int l = 1; l < kMaxDirectLayers; ++l) {
-        const int p = tbl->block0[l];
-        if (b >= p) { ++li; first = p; }
-    }
+    int first;
+    const int li = table_find<kMaxDirectLayers>(&tbl->block0[0], b, first);
     static_assert(sizeof(DirectLayer) % 4 == 0, "copied word by word");
     const __attribute__((address_space(4))) uint32_t *src = (const __attribute__((address_space(4))) uint32_t *)&tbl->layer[li];
     uint32_t *dst = reinterpret_cast<uint32_t *>(&L);
@@ -1140,12 +1136,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void depthwise_many_kernel(const DwTable tbl_arg) {
     const DwTablePtr tbl = (DwTablePtr)__builtin_amdgcn_kernarg_segment_ptr();
     const int b = blockIdx.x;
-    int li = 0, first = 0;
-#pragma unroll
-    for (int l = 1; l < kMaxDwLayers; ++l) {
-        const int p = tbl->block0[l];
-        if (b >= p) { ++li; first = p; }
-    }
+    int first;
+    const int li = table_find<kMaxDwLayers>(&tbl->block0[0], b, first);
     DwLayer L;
     {
         static_assert(sizeof(DwLayer) % 4 == 0, "copied word by word");

@@ -605,8 +605,7 @@ struct GemmItemLayer {
 struct GemmItemTable {
     GemmItemLayer layer[kMaxGemmLayers];
     // first item / first reduction workgroup of each layer, INT_MAX beyond the last layer: a
-    // workgroup finds its layer by counting the entries it has reached (one load of the array,
-    // no chain of dependent loads)
+    // workgroup finds its layer by counting the entries it has reached (table_find)
     int item0[kMaxGemmLayers], red0[kMaxGemmLayers];
     int nlayers, nitems;
     int group;          // consecutive items handed to one XCD
@@ -689,12 +688,8 @@ __global__ __launch_bounds__(64 * kItemWaves, 3) void gemm_items_kernel(const Ge
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int item = (((j / G) * 8 + xcd) * G + j % G) * kItemWaves + wave;
     if (item >= tbl->nitems) return;
-    int li = 0, first = 0;
-#pragma unroll
-    for (int l = 1; l < kMaxGemmLayers; ++l) {
-        const int i0 = tbl->item0[l];
-        if (item >= i0) { ++li; first = i0; }
-    }
+    int first;
+    const int li = table_find<kMaxGemmLayers>(&tbl->item0[0], item, first);
     GemmItemLayer L;
     load_item_layer(L, tbl, li);                     // one batch of scalar loads
     const int local = item - first;
@@ -731,12 +726,8 @@ __device__ static inline int ceil_div_dev(int a, int b) { return (a + b - 1) / b
 __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmItemTable tbl_arg) {
     const GemmItemTablePtr tbl = (GemmItemTablePtr)__builtin_amdgcn_kernarg_segment_ptr();
     const int b = blockIdx.x;
-    int li = 0, first = 0;
-#pragma unroll
-    for (int l = 1; l < kMaxGemmLayers; ++l) {      // the last layer that starts at or before b
-        const int r0 = tbl->red0[l];
-        if (b >= r0) { ++li; first = r0; }
-    }
+    int first;
+    const int li = table_find<kMaxGemmLayers>(&tbl->red0[0], b, first);      // the last layer that starts at or before b
     GemmItemLayer L;
     load_item_layer(L, tbl, li);
     const int nreg = L.tm * 8;                                   // accumulator registers per lane: TM x 2 blocks x 4

@@ -13,6 +13,7 @@
 #include <climits>
 #include "nnv_internal.h"
 #include "wino_consts.h"
+#include "buf.h"
 
 namespace nnv {
 
@@ -237,9 +238,8 @@ __global__ __launch_bounds__(256) void transform_kernel(const JobTable tbl_arg) 
     extern __shared__ __align__(16) float lds[];
     const JobTablePtr tbl = (JobTablePtr)__builtin_amdgcn_kernarg_segment_ptr();
     const int b = blockIdx.x;
-    int j = 0;
-#pragma unroll
-    for (int l = 1; l < kMaxJobs; ++l) j += b >= tbl->first_block[l] ? 1 : 0;
+    int first_unused;
+    const int j = table_find<kMaxJobs>(&tbl->first_block[0], b, first_unused);
     TransformJob job;
     {
         static_assert(sizeof(TransformJob) % 4 == 0, "copied word by word");

@@ -384,12 +384,9 @@ __device__ __forceinline__ void load_wino_layer(WinoParams &dst, const WinoTable
     for (int i = 0; i < (int)(sizeof(WinoParams) / 4); ++i) d[i] = src[i];
 }
 
-#define NNV_FIND_LAYER(prefix, b, li, first)                                      \
-    int li = 0, first = 0;                                                        \
-    _Pragma("unroll") for (int l_ = 1; l_ < kMaxWinoLayers; ++l_) {               \
-        const int p_ = tbl->prefix[l_];                                           \
-        if ((b) >= p_) { ++li; first = p_; }                                      \
-    }
+#define NNV_FIND_LAYER(prefix, b, li, first) \
+    int first;                               \
+    const int li = table_find<kMaxWinoLayers>(&tbl->prefix[0], (b), first);
 
 template <int SET, bool HALF>
 __global__ __launch_bounds__(256) void wino_input_many_kernel(const WinoTable tbl_arg) {
