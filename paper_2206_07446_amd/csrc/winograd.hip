@@ -437,7 +437,7 @@ __global__ __launch_bounds__(64 * kWinoItemWaves) void wino_gemm_many_kernel(con
     const bool surplus = local >= per_xi * w.alpha2;      // the last workgroup of a layer may hold fewer items
     const int xi = surplus ? 0 : local / per_xi, tile = local - xi * per_xi;
     const int kbt = surplus ? w.K16 : tile / w.ntb, tbt = surplus ? 0 : tile - kbt * w.ntb;   // kb0 >= K16: nothing loaded, nothing stored
-    constexpr int D = HALF ? 2 : 8;
+    constexpr int D = HALF ? 2 : 4;     // float32: a ring of 4 steps keeps the kernel at 71 registers (7 wavefronts per SIMD); 8 steps and 4 wavefronts were measured: 8-11 % slower on small stacks
     if (tm == 2 && tn == 2) wino_gemm_tile<HALF, 2, 2, D>(w, xi, kbt * 2, tbt * 2, ks, KS, w.ks_shift, nt, lane, red);
     else if (tm == 2) wino_gemm_tile<HALF, 2, 1, D>(w, xi, kbt * 2, tbt, ks, KS, w.ks_shift, nt, lane, red);
     else wino_gemm_tile<HALF, 1, 1, D>(w, xi, kbt, tbt, ks, KS, w.ks_shift, nt, lane, red);
