@@ -164,8 +164,9 @@ int nnv_conv_forward_relu(const nnv_conv_desc *desc, nnv_kind kind, const void *
  * input transforms, all tile GEMMs, all output transforms), except those nnv_conv_forward
  * runs as one fused kernel; DEPTHWISE layers of one storage type share one launch; DIRECT
  * layers with groups = 1 and a square 1x1, 3x3, 5x5 or 7x7 filter share up to three (one of
- * them for the float32 layers that run with the lanes along the output channels: 3x3 at stride 1,
- * 3x3 and 7x7 at stride 2).  The
+ * them for the layers that run with the lanes along the output channels: K a multiple of 64 and
+ * a 3x3 filter with C a multiple of 4, a 1x1 filter with C a multiple of 16, each at stride 1 or
+ * 2, or a 7x7 stride-2 filter with at most 4 channels).  The
  * remaining layers, and the layers of a kind of which the call holds only one or two (three
  * for IM2COL_GEMM: the shared launches are laid out to fill the GPU), are executed one after
  * the other as by nnv_conv_forward.  Results per layer are as nnv_conv_forward's up to the
