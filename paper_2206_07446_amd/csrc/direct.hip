@@ -398,36 +398,46 @@ __host__ __device__ static inline int klane_blocks(const KLaneLayer &L) { return
 // LDS floats in front of the output rows (the staged filters)
 __host__ __device__ static inline int klane_filter_floats(const KLaneLayer &L) { return L.staged ? 64 * L.ts : 0; }
 // LDS floats of a workgroup: staged: [filters][output rows, 14 x 65 per wavefront][pixel slots]; else
-// [a region of kTapRegion floats per wavefront: its tap staging area in the channel loop, its output rows afterwards][pixel slots]
+// [a region of kTapRegion floats per wavefront: its tap staging area in the channel loop, its output rows afterwards][pixel slots];
+// two pixel slots of 256 floats per wavefront
 __host__ __device__ static inline int klane_lds_floats(const KLaneLayer &L) {
-    return L.staged ? klane_filter_floats(L) + kKlWaves * (14 * 65 + 256) : kKlWaves * (kTapRegion + 256);
+    return L.staged ? klane_filter_floats(L) + kKlWaves * (14 * 65 + 256) : kKlWaves * (kTapRegion + 512);
 }
 
 // One channel of a tile: the wavefront's patch (NR rows x NPX columns, flat index f = row * NPX +
 // column) lies in its LDS slot; it is read back 16 pixels at a time with uniform addresses and
 // each pixel feeds the FMAs of the outputs it belongs to:
 // acc[orow][q] += pixel(orow * ST + dr, q * ST + sx) * t[dr][sx].
-template <int FS, int ST, int TW, int TR>
-__device__ __forceinline__ void klane_channel(const float *slot, const float (&t)[FS * FS], float (&acc)[TR * TW]) {
+// The chunks alternate between two register sets, the next one being read while this one is used.
+// PAR: the set of this channel's first chunk (a constant once the caller's loop is unrolled).  PRE: that chunk is in its registers already (the
+// previous channel fetched it from `slot`); next: where the next channel's patch lies, or null --
+// its first chunk is then fetched beside the FMAs of this channel's last one, so that a channel
+// does not begin with an LDS round trip.  kKlChunk pixels per chunk.
+constexpr int kKlChunk = 16;
+template <int FS, int ST, int TW, int TR> constexpr int klane_chunks() { return (((TR - 1) * ST + FS) * ((TW - 1) * ST + FS) + kKlChunk - 1) / kKlChunk; }
+template <int FS, int ST, int TW, int TR, bool PRE>
+__device__ __forceinline__ void klane_channel(const float *slot, const float *next, const float (&t)[FS * FS], float (&acc)[TR * TW],
+                                              kl_f4 (&px)[2][kKlChunk / 4], const int PAR) {
     constexpr int NR = (TR - 1) * ST + FS, NPX = (TW - 1) * ST + FS, NF = NR * NPX;
-    constexpr int CP = 16, NCH = (NF + CP - 1) / CP;     // pixels per chunk; the next chunk is read while this one is used
-    kl_f4 px[2][CP / 4];
-    auto read_chunk = [&](int ch) __attribute__((always_inline)) {
+    constexpr int CP = kKlChunk, NCH = klane_chunks<FS, ST, TW, TR>();
+    auto read_chunk = [&](const float *from, int ch, int set) __attribute__((always_inline)) {
 #pragma unroll
         for (int m = 0; m < CP / 4; ++m)
-            if (CP * ch + 4 * m < NF) px[ch & 1][m] = *reinterpret_cast<const kl_f4 *>(slot + CP * ch + 4 * m);
+            if (CP * ch + 4 * m < NF) px[set][m] = *reinterpret_cast<const kl_f4 *>(from + CP * ch + 4 * m);
     };
-    read_chunk(0);
+    if (!PRE) read_chunk(slot, 0, PAR);
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch) {
-        if (ch + 1 < NCH) read_chunk(ch + 1);
+        const int cur = (PAR + ch) & 1;
+        if (ch + 1 < NCH) read_chunk(slot, ch + 1, cur ^ 1);
+        else if (next) read_chunk(next, 0, cur ^ 1);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int e = 0; e < CP; ++e) {
             const int f = CP * ch + e;
             if (f >= NF) continue;
             const int r = f / NPX, i = f - r * NPX;
-            const float v = px[ch & 1][e >> 2][e & 3];
+            const float v = px[cur][e >> 2][e & 3];
 #pragma unroll
             for (int dr = 0; dr < FS; ++dr) {
                 const int ro = r - dr;
@@ -450,6 +460,7 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
     static_assert(STAGED || FS == 3 || FS == 1, "taps of a few channels at a time: 3x3 and 1x1");
     constexpr int NR = (TR - 1) * ST + FS, NPX = (TW - 1) * ST + FS, NF = NR * NPX, NLD = (NF + 63) / 64;
     static_assert(NLD * 64 <= 256, "pixel slot");
+    kl_f4 px[2][kKlChunk / 4];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int KB = L.K >> 6;
@@ -464,7 +475,7 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
     const int HW = L.H * L.W;
     constexpr int OWS = STAGED ? 14 * 65 : kTapRegion;       // floats from one wavefront's output rows to the next one's
     float *out = lds + klane_filter_floats(L);
-    float *slot = out + kKlWaves * OWS + wave * 256;
+    float *slot = out + kKlWaves * OWS + wave * (STAGED ? 256 : 512);      // two pixel slots of 256 floats: this channel's patch and the next one's
     // the lane's pixels in the NLD loads of a channel (1x1: a load holds two channels, 32 lanes each)
     constexpr int LPC = FS == 1 ? 32 : 64;
     static_assert(FS != 1 || NF <= 32, "two channels per pixel load");
@@ -532,8 +543,8 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
                     const uint32_t cn = min(c16 + 2 * jp + 8, cendx - 2);
                     R[j] = buf_load_x<T>(xres, voff[0], cn * plane);
                     const float t0[1] = {t[2 * jp]}, t1[1] = {t[2 * jp + 1]};
-                    klane_channel<1, ST, TW, TR>(slot, t0, acc);
-                    klane_channel<1, ST, TW, TR>(slot + 32, t1, acc);
+                    klane_channel<1, ST, TW, TR, false>(slot, nullptr, t0, acc, px, 0);
+                    klane_channel<1, ST, TW, TR, false>(slot + 32, nullptr, t1, acc, px, 0);
                     // (the accumulators are pinned here: left alone, the compiler sinks the FMAs of many
                     // channels below their LDS reads and parks the pixels in scratch memory meanwhile)
 #pragma unroll
@@ -591,6 +602,16 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
             __builtin_amdgcn_sched_barrier(0);
             tap_copy(tmp);
             tap_take(t);
+            // The patch of a channel goes to LDS one channel ahead (the two slots alternate) and its first
+            // chunk is read beside the last FMAs of the channel before it.  Slot j & 1 holds channel c4 + j.
+            constexpr int NCH = klane_chunks<3, ST, TW, TR>();
+#pragma unroll
+            for (int l = 0; l < NLD; ++l) slot[l * 64 + lane] = R[0][l];
+#pragma unroll
+            for (int l = 0; l < NLD; ++l) R[0][l] = buf_load_x<T>(xres, voff[l], min(cbeg + 4, cendx - 1) * plane);
+#pragma unroll
+            for (int m = 0; m < kKlChunk / 4; ++m)
+                if (4 * m < NF) px[0][m] = *reinterpret_cast<const kl_f4 *>(slot + 4 * m);
             for (uint32_t c4 = cbeg; c4 < cendx; c4 += 4) {
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
@@ -598,16 +619,18 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
                     tap_fetch(tmp, min(c4 + 2 * h + 2, cendx - 2));
 #pragma unroll
                     for (int jj = 0; jj < 2; ++jj) {
-                        const int j = 2 * h + jj;
+                        const int j = 2 * h + jj, jn = (j + 1) & 3;
+                        // the next channel's patch (slot jn holds channel c4 + j + 1; past the end: the last channel again)
+                        float *nslot = slot + ((j + 1) & 1) * 256;
 #pragma unroll
-                        for (int l = 0; l < NLD; ++l) slot[l * 64 + lane] = R[j][l];
-                        const uint32_t cn = min(c4 + j + 4, cendx - 1);
+                        for (int l = 0; l < NLD; ++l) nslot[l * 64 + lane] = R[jn][l];
+                        const uint32_t cn = min(c4 + j + 5, cendx - 1);
 #pragma unroll
-                        for (int l = 0; l < NLD; ++l) R[j][l] = buf_load_x<T>(xres, voff[l], cn * plane);
+                        for (int l = 0; l < NLD; ++l) R[jn][l] = buf_load_x<T>(xres, voff[l], cn * plane);
                         float tj[9];
 #pragma unroll
                         for (int i = 0; i < 9; ++i) tj[i] = t[jj * 9 + i];
-                        klane_channel<3, ST, TW, TR>(slot, tj, acc);
+                        klane_channel<3, ST, TW, TR, true>(slot + (j & 1) * 256, nslot, tj, acc, px, (j * NCH) & 1);
                         // the next pair's taps go to LDS between the two channels (the staging area
                         // holds nothing that is still needed: this pair's taps are in registers)
                         if (jj == 0) tap_copy(tmp);
@@ -653,7 +676,7 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
                 float tc[FS * FS];
 #pragma unroll
                 for (int i = 0; i < FS * FS; ++i) tc[i] = mine[c * FS * FS + i];
-                klane_channel<FS, ST, TW, TR>(slot, tc, acc);
+                klane_channel<FS, ST, TW, TR, false>(slot, nullptr, tc, acc, px, 0);
             }
         }
     }

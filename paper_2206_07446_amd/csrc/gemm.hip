@@ -791,6 +791,41 @@ __global__ __launch_bounds__(256) void to_channels_last_kernel(const __half *__r
     *reinterpret_cast<uint4 *>(xt + ((size_t)img * HW + pix) * cpad + oct * 8) = *reinterpret_cast<uint4 *>(v);
 }
 
+// The same conversion for several layers in one launch: a workgroup finds its layer by its index,
+// as the item kernel does, then converts 256 pixels of 8 channels of one image.
+struct ChannelsLastTable {
+    const __half *x[kMaxGemmLayers];
+    __half *xt[kMaxGemmLayers];
+    int C[kMaxGemmLayers], HW[kMaxGemmLayers], cpad[kMaxGemmLayers];
+    int block0[kMaxGemmLayers];      // first workgroup of each layer, INT_MAX beyond the last one
+    int nblocks;
+};
+typedef const __attribute__((address_space(4))) ChannelsLastTable *ChannelsLastTablePtr;
+
+__global__ __launch_bounds__(256) void to_channels_last_many_kernel(const ChannelsLastTable tbl_arg) {
+    const ChannelsLastTablePtr tbl = (ChannelsLastTablePtr)__builtin_amdgcn_kernarg_segment_ptr();
+    const int b = blockIdx.x;
+    if (b >= tbl->nblocks) return;
+    int first;
+    const int li = table_find<kMaxGemmLayers>(&tbl->block0[0], b, first);
+    const int C = tbl->C[li], HW = tbl->HW[li], cpad = tbl->cpad[li];
+    const __half *x = tbl->x[li];
+    __half *xt = tbl->xt[li];
+    const int npb = (HW + 255) / 256, noct = cpad / 8;
+    const int local = b - first;
+    const int pb = local % npb, rest = local / npb;
+    const int oct = rest % noct, img = rest / noct;
+    const int pix = pb * 256 + threadIdx.x;
+    if (pix >= HW) return;
+    __half v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int c = oct * 8 + j;
+        v[j] = (c < C) ? x[((size_t)img * C + c) * HW + pix] : __float2half(0.f);
+    }
+    *reinterpret_cast<uint4 *>(xt + ((size_t)img * HW + pix) * cpad + oct * 8) = *reinterpret_cast<uint4 *>(v);
+}
+
 // ---------------------------------------------------------------- host side
 
 struct GemmPlan {
@@ -1005,7 +1040,8 @@ hipError_t launch_im2col_items(int n, const Geo *geos, const void *const *x, con
     auto item_len = [&](int i) { return ceil_div(plans[i].steps, plans[i].nsplit) * plans[i].tm; };
     std::stable_sort(order, order + n, [&](int a, int b) { return item_len(a) > item_len(b); });
     GemmItemTable tbl{};
-    int items = 0, red = 0;
+    ChannelsLastTable cl{};
+    int items = 0, red = 0, ncl = 0, clblocks = 0;
     for (int o = 0; o < n; ++o) {
         const int i = order[o];
         const Geo &g = geos[i];
@@ -1014,8 +1050,16 @@ hipError_t launch_im2col_items(int n, const Geo *geos, const void *const *x, con
         L.g = gemm_params(g, ip.mode, x[i], w[i], bias ? bias[i] : nullptr, y[i]);
         char *region = static_cast<char *>(ws[i]);
         if (ip.xt_bytes) {
+            // all channel-last copies of the call are made by one launch in front of the item launch
             void *xt = region + align_up(ip.part_bytes, 256);
-            launch_channels_last(g, L.g, x[i], xt, st);
+            cl.x[ncl] = static_cast<const __half *>(x[i]);
+            cl.xt[ncl] = static_cast<__half *>(xt);
+            cl.C[ncl] = g.c;
+            cl.HW[ncl] = g.h * g.w;
+            cl.cpad[ncl] = L.g.cpad;
+            cl.block0[ncl] = clblocks;
+            clblocks += ceil_div(g.h * g.w, 256) * (L.g.cpad / 8) * g.n;
+            ++ncl;
             L.g.x = xt;
         }
         L.part = ip.nsplit > 1 ? reinterpret_cast<float *>(region) : nullptr;
@@ -1033,6 +1077,11 @@ hipError_t launch_im2col_items(int n, const Geo *geos, const void *const *x, con
     tbl.nitems = items;
     tbl.group = 2;       // workgroups (of kItemWaves items) handed to one XCD in a row
     tbl.nred = red;
+    if (ncl > 0) {
+        for (int i = ncl; i < kMaxGemmLayers; ++i) cl.block0[i] = INT_MAX;
+        cl.nblocks = clblocks;
+        hipLaunchKernelGGL(to_channels_last_many_kernel, dim3(clblocks), dim3(256), 0, st, cl);
+    }
     const int wgs = ceil_div(items, kItemWaves);
     const int per_xcd = ceil_div(ceil_div(wgs, tbl.group), 8) * tbl.group;
     if (half) hipLaunchKernelGGL(gemm_items_kernel<true>, dim3(per_xcd * 8), dim3(64 * kItemWaves), 0, st, tbl);
