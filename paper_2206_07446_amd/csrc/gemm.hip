@@ -792,7 +792,7 @@ __global__ __launch_bounds__(256) void to_channels_last_kernel(const __half *__r
 }
 
 // The same conversion for several layers in one launch: a workgroup finds its layer by its index,
-// as the item kernel does, then converts 256 pixels of 8 channels of one image.
+// as the item kernel does, then converts 256 pixels of 32 channels of one image.
 struct ChannelsLastTable {
     const __half *x[kMaxGemmLayers];
     __half *xt[kMaxGemmLayers];
@@ -811,19 +811,23 @@ __global__ __launch_bounds__(256) void to_channels_last_many_kernel(const Channe
     const int C = tbl->C[li], HW = tbl->HW[li], cpad = tbl->cpad[li];
     const __half *x = tbl->x[li];
     __half *xt = tbl->xt[li];
-    const int npb = (HW + 255) / 256, noct = cpad / 8;
+    const int npb = (HW + 255) / 256, nblk = cpad / 32;
     const int local = b - first;
     const int pb = local % npb, rest = local / npb;
-    const int oct = rest % noct, img = rest / noct;
+    const int cb = rest % nblk, img = rest / nblk;
     const int pix = pb * 256 + threadIdx.x;
     if (pix >= HW) return;
-    __half v[8];
+    // (a thread writes the 64 contiguous bytes of its pixel's 32 channels; 8 channels per thread, or
+    // two pixels per thread with 4-byte loads, took the same 10-11 us on the ResNet-18-shaped stack)
+    __half v[32];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int c = oct * 8 + j;
+    for (int j = 0; j < 32; ++j) {
+        const int c = cb * 32 + j;
         v[j] = (c < C) ? x[((size_t)img * C + c) * HW + pix] : __float2half(0.f);
     }
-    *reinterpret_cast<uint4 *>(xt + ((size_t)img * HW + pix) * cpad + oct * 8) = *reinterpret_cast<uint4 *>(v);
+    uint4 *dst = reinterpret_cast<uint4 *>(xt + ((size_t)img * HW + pix) * cpad + cb * 32);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) dst[q] = reinterpret_cast<const uint4 *>(v)[q];
 }
 
 // ---------------------------------------------------------------- host side
@@ -1073,7 +1077,7 @@ hipError_t launch_im2col_items(int n, const Geo *geos, const void *const *x, con
             cl.HW[ncl] = g.h * g.w;
             cl.cpad[ncl] = L.g.cpad;
             cl.block0[ncl] = clblocks;
-            clblocks += ceil_div(g.h * g.w, 256) * (L.g.cpad / 8) * g.n;
+            clblocks += ceil_div(g.h * g.w, 256) * (L.g.cpad / 32) * g.n;
             ++ncl;
             L.g.x = xt;
         }
