@@ -238,7 +238,7 @@ int static_scratch(void **out) {
 // Layers of one launch run concurrently, so each needs a workspace region of its own; launches
 // follow one another on the stream, so the regions of different launches overlap.
 struct GroupedPlan {
-    enum Class { SINGLE = 0, GEMM_ITEMS = 1, WINO_MANY = 2, DIRECT_MANY = 3, DW_MANY = 4 };
+    enum Class { SINGLE = 0, GEMM_ITEMS = 1, WINO_MANY = 2, DIRECT_MANY = 3, DW_MANY = 4, DW_RAW_MANY = 5 };
     struct Batch {
         int cls;
         int kind;                   // WINO_MANY: the Winograd kind of the batch
@@ -286,6 +286,10 @@ GroupedPlan plan_grouped(int n, const Geo *geos, const nnv_kind *kinds) {
                 [&](int) { return (size_t)0; });
         collect(GroupedPlan::DW_MANY, NNV_DEPTHWISE, kMaxDwLayers, 2,
                 [&](int i) { return kinds[i] == NNV_DEPTHWISE && same_type(i); }, [&](int) { return (size_t)0; });
+        // depthwise layers given to the direct kind: the depthwise launch, reading the untransformed filters
+        collect(GroupedPlan::DW_RAW_MANY, NNV_DIRECT, kMaxDwLayers, 2,
+                [&](int i) { return kinds[i] == NNV_DIRECT && same_type(i) && supported(geos[i], NNV_DEPTHWISE); },
+                [&](int) { return (size_t)0; });
         for (int kind : {NNV_WINO_F2, NNV_WINO_F4, NNV_WINO_F6})
             collect(GroupedPlan::WINO_MANY, kind, kMaxWinoLayers, 2,
                     [&](int i) { return kinds[i] == kind && same_type(i) && wino_many_supported(geos[i], kind); },
@@ -447,7 +451,8 @@ int nnv_conv_forward_grouped(int n_layers, const nnv_conv_desc *descs, const nnv
                 e = launch_direct_many(m, bg.data(), bx.data(), bw.data(), bb.data(), by.data(), st);
                 break;
             default:
-                e = launch_depthwise_many(m, bg.data(), bx.data(), bw.data(), bb.data(), by.data(), st);
+                e = launch_depthwise_many(m, bg.data(), bx.data(), bw.data(), bb.data(), by.data(),
+                                          b.cls == GroupedPlan::DW_RAW_MANY, st);
                 break;
         }
         if (e != hipSuccess) return hip_fail(e);

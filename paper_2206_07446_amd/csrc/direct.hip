@@ -1105,6 +1105,7 @@ struct DwLayer {
     void *y;
     DwParams d;
     int fs;
+    int raw;        // w holds the untransformed float32 filters [c][fs * fs] (a depthwise layer run by the direct kind)
 };
 struct DwTable {
     DwLayer layer[kMaxDwLayers];
@@ -1114,8 +1115,8 @@ struct DwTable {
 static_assert(sizeof(DwTable) <= 4096, "the table is passed by value as the kernel argument");
 typedef const __attribute__((address_space(4))) DwTable *DwTablePtr;
 
-template <typename T, int FS>
-__device__ __forceinline__ void depthwise_flat_block(const T *__restrict__ x, const T *__restrict__ wp,
+template <typename T, int FS, bool RAW>
+__device__ __forceinline__ void depthwise_flat_block(const T *__restrict__ x, const void *__restrict__ wv,
                                                      const float *__restrict__ bias, T *__restrict__ y,
                                                      const DwParams &d, const int blk) {
     constexpr int kDwPerThread = dw_per_thread(FS);
@@ -1134,7 +1135,8 @@ __device__ __forceinline__ void depthwise_flat_block(const T *__restrict__ x, co
 #pragma unroll
     for (int i = 0; i < kDwPerThread; ++i) {
         const int p = pq[i] / d.Q, q = pq[i] - p * d.Q;
-        const T *wc = wp + (size_t)(c[i] >> 5) * (FS * FS * 32) + (c[i] & 31);
+        const T *wc = static_cast<const T *>(wv) + (size_t)(c[i] >> 5) * (FS * FS * 32) + (c[i] & 31);
+        const float *wr = static_cast<const float *>(wv) + (size_t)c[i] * (FS * FS);
         const T *xc = x + (size_t)plane[i] * d.H * d.W;
         const int ih0 = p * d.st - d.ph, iw0 = q * d.st - d.pw;
 #pragma unroll
@@ -1146,7 +1148,7 @@ __device__ __forceinline__ void depthwise_flat_block(const T *__restrict__ x, co
                 const int iw = iw0 + s2;
                 const bool ok = rok && iw >= 0 && iw < d.W;
                 const float xv = ok ? ld<T>(xc, (size_t)ih * d.W + iw) : 0.f;
-                acc[i] = fmaf(xv, ld<T>(wc, (r * FS + s2) * 32), acc[i]);
+                acc[i] = fmaf(xv, RAW ? wr[r * FS + s2] : ld<T>(wc, (r * FS + s2) * 32), acc[i]);
             }
         }
     }
@@ -1169,14 +1171,19 @@ __global__ __launch_bounds__(256) void depthwise_many_kernel(const DwTable tbl_a
 #pragma unroll
         for (int k = 0; k < (int)(sizeof(DwLayer) / 4); ++k) dst[k] = src[k];
     }
-    const T *x = static_cast<const T *>(L.x), *w = static_cast<const T *>(L.w);
+    const T *x = static_cast<const T *>(L.x);
     T *y = static_cast<T *>(L.y);
-    if (L.fs == 5) depthwise_flat_block<T, 5>(x, w, L.bias, y, L.d, b - first);
-    else depthwise_flat_block<T, 3>(x, w, L.bias, y, L.d, b - first);
+    if (L.raw) {
+        if (L.fs == 5) depthwise_flat_block<T, 5, true>(x, L.w, L.bias, y, L.d, b - first);
+        else depthwise_flat_block<T, 3, true>(x, L.w, L.bias, y, L.d, b - first);
+    } else {
+        if (L.fs == 5) depthwise_flat_block<T, 5, false>(x, L.w, L.bias, y, L.d, b - first);
+        else depthwise_flat_block<T, 3, false>(x, L.w, L.bias, y, L.d, b - first);
+    }
 }
 
 hipError_t launch_depthwise_many(int n, const Geo *geos, const void *const *x, const void *const *w, const float *const *bias,
-                                 void *const *y, hipStream_t st_) {
+                                 void *const *y, bool raw, hipStream_t st_) {
     if (n <= 0) return hipSuccess;
     if (n > kMaxDwLayers) return hipErrorInvalidValue;
     const bool half = geos[0].dtype == NNV_F16;
@@ -1189,6 +1196,7 @@ hipError_t launch_depthwise_many(int n, const Geo *geos, const void *const *x, c
         L.x = x[i]; L.w = w[i]; L.bias = bias ? bias[i] : nullptr; L.y = y[i];
         L.d = DwParams{g.n, g.c, g.h, g.w, g.sh, g.ph, g.pw, g.p, g.q, g.relu};
         L.fs = g.r;
+        L.raw = raw ? 1 : 0;
         tbl.block0[i] = (int)blocks;
         blocks += ((long)g.n * g.c * g.p * g.q + 256 * dw_per_thread(g.r) - 1) / (256 * dw_per_thread(g.r));
         if (blocks >= (1L << 30)) return hipErrorInvalidValue;

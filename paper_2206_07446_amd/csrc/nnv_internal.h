@@ -74,8 +74,10 @@ constexpr int kMaxDwLayers = 40;
 bool direct_many_supported(const Geo &g);
 hipError_t launch_direct_many(int n, const Geo *geos, const void *const *x, const void *const *w, const float *const *bias,
                               void *const *y, hipStream_t st);
+// raw: w[i] are the untransformed float32 filters (depthwise layers run by the direct kind), else the
+// channel-blocked tap-major ones of the depthwise kind.
 hipError_t launch_depthwise_many(int n, const Geo *geos, const void *const *x, const void *const *w,
-                                 const float *const *bias, void *const *y, hipStream_t st);
+                                 const float *const *bias, void *const *y, bool raw, hipStream_t st);
 
 size_t im2col_workspace_bytes(const Geo &g);
 hipError_t launch_im2col(const Geo &g, const void *x, const void *w, const float *bias, void *y, void *ws, hipStream_t st);
