@@ -519,8 +519,8 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
                 }
             };
             const uint32_t per = (uint32_t)(L.C / L.cs), cbeg = (uint32_t)cw * per, cendx = cbeg + per;
-            // pixels of four channel pairs in flight (slot j: channels c16 + 2 j and + 1 of the eight pairs
-            // of a group alternate over the slots); requests in a pinned order as below
+            // pixels of four channel pairs in flight (register j: channels c16 + 2 j and + 1; the eight pairs
+            // of a group alternate over the registers); requests in a pinned order as below
             kl_f4 tmp[4];
             float t[16];
             tap_fetch(tmp, cbeg);
@@ -533,18 +533,27 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
             __builtin_amdgcn_sched_barrier(0);
             tap_copy(tmp);
             tap_take(t);
+            // A pair's pixels go to LDS one pair ahead (two slots of 64 floats alternate) and a channel's
+            // first chunk is read beside the last FMAs of the channel before it.
+            constexpr int NCH = klane_chunks<1, ST, TW, TR>();
+            slot[lane] = R[0];
+            R[0] = buf_load_x<T>(xres, voff[0], min(cbeg + 8, cendx - 2) * plane);
+#pragma unroll
+            for (int m = 0; m < kKlChunk / 4; ++m)
+                if (4 * m < NF) px[0][m] = *reinterpret_cast<const kl_f4 *>(slot + 4 * m);
             for (uint32_t c16 = cbeg; c16 < cendx; c16 += 16) {
                 // (the last group fetches itself again: in range, never used)
                 tap_fetch(tmp, min(c16 + 16, cendx - 16));
 #pragma unroll
                 for (int jp = 0; jp < 8; ++jp) {
-                    const int j = jp & 3;
-                    slot[lane] = R[j];
-                    const uint32_t cn = min(c16 + 2 * jp + 8, cendx - 2);
-                    R[j] = buf_load_x<T>(xres, voff[0], cn * plane);
+                    const int jn = (jp + 1) & 3;
+                    float *cur = slot + (jp & 1) * 64, *nslot = slot + ((jp + 1) & 1) * 64;
+                    nslot[lane] = R[jn];                     // the next pair (past the end: the last pair again)
+                    const uint32_t cn = min(c16 + 2 * jp + 10, cendx - 2);
+                    R[jn] = buf_load_x<T>(xres, voff[0], cn * plane);
                     const float t0[1] = {t[2 * jp]}, t1[1] = {t[2 * jp + 1]};
-                    klane_channel<1, ST, TW, TR, false>(slot, nullptr, t0, acc, px, 0);
-                    klane_channel<1, ST, TW, TR, false>(slot + 32, nullptr, t1, acc, px, 0);
+                    klane_channel<1, ST, TW, TR, true>(cur, cur + 32, t0, acc, px, 0);
+                    klane_channel<1, ST, TW, TR, true>(cur + 32, nslot, t1, acc, px, NCH & 1);
                     // (the accumulators are pinned here: left alone, the compiler sinks the FMAs of many
                     // channels below their LDS reads and parks the pixels in scratch memory meanwhile)
 #pragma unroll
@@ -970,7 +979,7 @@ hipError_t launch_direct_many(int n, const Geo *geos, const void *const *x, cons
             order[m++] = i;
             if (klane_supported(g)) {
                 const KLaneLayer K = klane_layer(g);
-                weight[i] = (long)(g.c / K.cs) * g.r * g.r * K.tw * K.tr;
+                weight[i] = K.staged ? 0 : (long)(g.c / K.cs) * g.r * g.r * K.tw * K.tr;
             } else {
                 weight[i] = (long)(g.c < waves ? g.c : ceil_div(g.c, waves)) * g.r * g.s * ((g.k % 8 == 0 && g.r <= 3) ? 8 : 4);
             }
