@@ -405,32 +405,48 @@ __host__ __device__ static inline int klane_lds_floats(const KLaneLayer &L) {
 }
 
 // One channel of a tile: the wavefront's patch (NR rows x NPX columns, flat index f = row * NPX +
-// column) lies in its LDS slot; it is read back 16 pixels at a time with uniform addresses and
+// column) lies in its LDS slot; it is read back kKlChunk pixels at a time with uniform addresses and
 // each pixel feeds the FMAs of the outputs it belongs to:
 // acc[orow][q] += pixel(orow * ST + dr, q * ST + sx) * t[dr][sx].
-// The chunks alternate between two register sets, the next one being read while this one is used.
-// PAR: the set of this channel's first chunk (a constant once the caller's loop is unrolled).  PRE: that chunk is in its registers already (the
-// previous channel fetched it from `slot`); next: where the next channel's patch lies, or null --
-// its first chunk is then fetched beside the FMAs of this channel's last one, so that a channel
-// does not begin with an LDS round trip.  kKlChunk pixels per chunk.
-constexpr int kKlChunk = 16;
+// The chunks rotate over kKlSets register sets and the reads run up to kKlDepth chunks ahead of the
+// FMAs: a wavefront alternates between few FMAs and an LDS round trip, and with one chunk in flight
+// a chunk took as long as the round trip whatever its FMAs.
+// PAR: the set of this channel's first chunk (a constant once the caller's loop is unrolled).  PRE:
+// the first klane_depth chunks are in their registers already (the previous channel fetched them
+// from `slot`); next: where the next channel's patch lies, or null -- its first chunks are then
+// fetched beside the last FMAs of this channel.
+constexpr int kKlChunk = 8, kKlSets = 4, kKlDepth = 3;
 template <int FS, int ST, int TW, int TR> constexpr int klane_chunks() { return (((TR - 1) * ST + FS) * ((TW - 1) * ST + FS) + kKlChunk - 1) / kKlChunk; }
+template <int FS, int ST, int TW, int TR> constexpr int klane_depth() { return klane_chunks<FS, ST, TW, TR>() < kKlDepth ? klane_chunks<FS, ST, TW, TR>() : kKlDepth; }
+typedef kl_f4 KlPixels[kKlSets][kKlChunk / 4];
+template <int FS, int ST, int TW, int TR>
+__device__ __forceinline__ void klane_read_chunk(const float *from, const int ch, const int set, KlPixels &px) {
+    constexpr int NF = ((TR - 1) * ST + FS) * ((TW - 1) * ST + FS);
+#pragma unroll
+    for (int m = 0; m < kKlChunk / 4; ++m)
+        if (kKlChunk * ch + 4 * m < NF) px[set][m] = *reinterpret_cast<const kl_f4 *>(from + kKlChunk * ch + 4 * m);
+}
+// the first chunks of the first channel of a loop (sets 0 ..)
+template <int FS, int ST, int TW, int TR>
+__device__ __forceinline__ void klane_preload(const float *slot, KlPixels &px) {
+#pragma unroll
+    for (int d = 0; d < klane_depth<FS, ST, TW, TR>(); ++d) klane_read_chunk<FS, ST, TW, TR>(slot, d, d, px);
+}
 template <int FS, int ST, int TW, int TR, bool PRE>
 __device__ __forceinline__ void klane_channel(const float *slot, const float *next, const float (&t)[FS * FS], float (&acc)[TR * TW],
-                                              kl_f4 (&px)[2][kKlChunk / 4], const int PAR) {
+                                              KlPixels &px, const int PAR) {
     constexpr int NR = (TR - 1) * ST + FS, NPX = (TW - 1) * ST + FS, NF = NR * NPX;
-    constexpr int CP = kKlChunk, NCH = klane_chunks<FS, ST, TW, TR>();
-    auto read_chunk = [&](const float *from, int ch, int set) __attribute__((always_inline)) {
+    constexpr int CP = kKlChunk, NCH = klane_chunks<FS, ST, TW, TR>(), D = klane_depth<FS, ST, TW, TR>();
+    static_assert(D + 1 <= kKlSets, "the chunk in use and the chunks in flight have a register set each");
+    if (!PRE) {
 #pragma unroll
-        for (int m = 0; m < CP / 4; ++m)
-            if (CP * ch + 4 * m < NF) px[set][m] = *reinterpret_cast<const kl_f4 *>(from + CP * ch + 4 * m);
-    };
-    if (!PRE) read_chunk(slot, 0, PAR);
+        for (int d = 0; d < D; ++d) klane_read_chunk<FS, ST, TW, TR>(slot, d, (PAR + d) % kKlSets, px);
+    }
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch) {
-        const int cur = (PAR + ch) & 1;
-        if (ch + 1 < NCH) read_chunk(slot, ch + 1, cur ^ 1);
-        else if (next) read_chunk(next, 0, cur ^ 1);
+        const int cur = (PAR + ch) % kKlSets, nx = ch + D;
+        if (nx < NCH) klane_read_chunk<FS, ST, TW, TR>(slot, nx, (PAR + nx) % kKlSets, px);
+        else if (next) klane_read_chunk<FS, ST, TW, TR>(next, nx - NCH, (PAR + nx) % kKlSets, px);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int e = 0; e < CP; ++e) {
@@ -460,7 +476,7 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
     static_assert(STAGED || FS == 3 || FS == 1, "taps of a few channels at a time: 3x3 and 1x1");
     constexpr int NR = (TR - 1) * ST + FS, NPX = (TW - 1) * ST + FS, NF = NR * NPX, NLD = (NF + 63) / 64;
     static_assert(NLD * 64 <= 256, "pixel slot");
-    kl_f4 px[2][kKlChunk / 4];
+    KlPixels px;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int KB = L.K >> 6;
@@ -536,11 +552,10 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
             // A pair's pixels go to LDS one pair ahead (two slots of 64 floats alternate) and a channel's
             // first chunk is read beside the last FMAs of the channel before it.
             constexpr int NCH = klane_chunks<1, ST, TW, TR>();
+            static_assert((2 * NCH) % kKlSets == 0, "every pair starts with register set 0");
             slot[lane] = R[0];
             R[0] = buf_load_x<T>(xres, voff[0], min(cbeg + 8, cendx - 2) * plane);
-#pragma unroll
-            for (int m = 0; m < kKlChunk / 4; ++m)
-                if (4 * m < NF) px[0][m] = *reinterpret_cast<const kl_f4 *>(slot + 4 * m);
+            klane_preload<1, ST, TW, TR>(slot, px);
             for (uint32_t c16 = cbeg; c16 < cendx; c16 += 16) {
                 // (the last group fetches itself again: in range, never used)
                 tap_fetch(tmp, min(c16 + 16, cendx - 16));
@@ -553,7 +568,7 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
                     R[jn] = buf_load_x<T>(xres, voff[0], cn * plane);
                     const float t0[1] = {t[2 * jp]}, t1[1] = {t[2 * jp + 1]};
                     klane_channel<1, ST, TW, TR, true>(cur, cur + 32, t0, acc, px, 0);
-                    klane_channel<1, ST, TW, TR, true>(cur + 32, nslot, t1, acc, px, NCH & 1);
+                    klane_channel<1, ST, TW, TR, true>(cur + 32, nslot, t1, acc, px, NCH % kKlSets);
                     // (the accumulators are pinned here: left alone, the compiler sinks the FMAs of many
                     // channels below their LDS reads and parks the pixels in scratch memory meanwhile)
 #pragma unroll
@@ -618,9 +633,7 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
             for (int l = 0; l < NLD; ++l) slot[l * 64 + lane] = R[0][l];
 #pragma unroll
             for (int l = 0; l < NLD; ++l) R[0][l] = buf_load_x<T>(xres, voff[l], min(cbeg + 4, cendx - 1) * plane);
-#pragma unroll
-            for (int m = 0; m < kKlChunk / 4; ++m)
-                if (4 * m < NF) px[0][m] = *reinterpret_cast<const kl_f4 *>(slot + 4 * m);
+            klane_preload<3, ST, TW, TR>(slot, px);
             for (uint32_t c4 = cbeg; c4 < cendx; c4 += 4) {
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
@@ -639,7 +652,7 @@ __device__ __forceinline__ void klane_tile(const KLaneLayer &L, const int lblk, 
                         float tj[9];
 #pragma unroll
                         for (int i = 0; i < 9; ++i) tj[i] = t[jj * 9 + i];
-                        klane_channel<3, ST, TW, TR, true>(slot + (j & 1) * 256, nslot, tj, acc, px, (j * NCH) & 1);
+                        klane_channel<3, ST, TW, TR, true>(slot + (j & 1) * 256, nslot, tj, acc, px, (j * NCH) % kKlSets);
                         // the next pair's taps go to LDS between the two channels (the staging area
                         // holds nothing that is still needed: this pair's taps are in registers)
                         if (jj == 0) tap_copy(tmp);
