@@ -722,7 +722,7 @@ __device__ static inline int ceil_div_dev(int a, int b) { return (a + b - 1) / b
 
 // Adds the nsplit partial tiles of every split layer in the order of the ranges and stores y.
 // A thread owns four consecutive lanes of one accumulator register (16-byte loads); the loads of
-// four ranges are in flight at once, the additions keep the order of the ranges.
+// twelve ranges are in flight at once, the additions keep the order of the ranges.
 __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmItemTable tbl_arg) {
     const GemmItemTablePtr tbl = (GemmItemTablePtr)__builtin_amdgcn_kernarg_segment_ptr();
     const int b = blockIdx.x;
@@ -739,17 +739,15 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmItemTable tb
     const float4 *src = reinterpret_cast<const float4 *>(L.part + (size_t)tile * L.nsplit * per_tile + rl);
     const size_t zs = (size_t)per_tile / 4;
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    int z = 0;
-    for (; z + 4 <= L.nsplit; z += 4) {
-        const float4 p0 = src[(z + 0) * zs], p1 = src[(z + 1) * zs], p2 = src[(z + 2) * zs], p3 = src[(z + 3) * zs];
-        v.x += p0.x; v.y += p0.y; v.z += p0.z; v.w += p0.w;
-        v.x += p1.x; v.y += p1.y; v.z += p1.z; v.w += p1.w;
-        v.x += p2.x; v.y += p2.y; v.z += p2.z; v.w += p2.w;
-        v.x += p3.x; v.y += p3.y; v.z += p3.z; v.w += p3.w;
-    }
-    for (; z < L.nsplit; ++z) {
-        const float4 p = src[z * zs];
-        v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+    constexpr int kInFlight = 12;
+    for (int z = 0; z < L.nsplit; z += kInFlight) {
+        // (ranges past the last one load the last one again and are not added)
+        float4 p[kInFlight];
+#pragma unroll
+        for (int i = 0; i < kInFlight; ++i) p[i] = src[(size_t)min(z + i, L.nsplit - 1) * zs];
+#pragma unroll
+        for (int i = 0; i < kInFlight; ++i)
+            if (z + i < L.nsplit) { v.x += p[i].x; v.y += p[i].y; v.z += p[i].z; v.w += p[i].w; }
     }
     // the four values are rows (lane0 / 16) * 4 + jj of panel m, pixels (lane0 % 16) .. + 3 of block t
     const int mt = tile / L.ntn, nb = tile - mt * L.ntn;
