@@ -32,10 +32,10 @@ VALU_F32_PEAK_TFLOPS = 157.3  # float32 vector peak (packed FMA; plain FMA, as c
 # the digest below; once a source file changes, `traffic` is reported as null until the counters
 # are taken again.
 MEASURED_TRAFFIC = {
-    "csrc_sha256_16": "f1b73b56ddc44763",
+    "csrc_sha256_16": "7181c3c5739f8eb5",
     "MB_per_step": {
         "transform": (44.9, 262.9),
-        "direct": (77.7, 10.2),
+        "direct": (77.6, 10.2),
         "im2col_gemm": (97.4, 23.0),
         "wino_f2": (137.8, 50.7),
         "wino_f4": (198.3, 38.4),
@@ -135,15 +135,18 @@ def cpu_baseline(layers, nnv, budget_s=12.0):
                       f"convolution uses all cores, the numpy transforms and reference Winograd one"}
 
 
-def graph_ms(torch, np, side, fn, reps=10, before=None):
-    """Median time of fn's launches, captured once on `side` into a HIP graph and replayed;
-    `before` (if given) runs ahead of every timed replay, outside the event pair."""
+def graph_ms(torch, np, side, fn, reps=10, before=None, calls=1):
+    """Median time of fn's launches, captured on `side` into a HIP graph and replayed; `before`
+    (if given) runs ahead of every timed replay, outside the event pair.  With calls > 1 the graph
+    holds that many calls of fn back to back and the time is per call: a replay has a fixed cost
+    of 20-25 us between its two events, which would otherwise be most of a small workload's time."""
     with torch.cuda.stream(side):
         fn()
     torch.cuda.synchronize()
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g, stream=side):
-        fn()
+        for _ in range(calls):
+            fn()
     g.replay()
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -156,7 +159,7 @@ def graph_ms(torch, np, side, fn, reps=10, before=None):
         e1.record()
         torch.cuda.synchronize()
         ts.append(e0.elapsed_time(e1))
-    return float(np.median(ts))
+    return float(np.median(ts)) / calls
 
 
 def grouped_forward(nnv, sel, ws):
@@ -164,10 +167,14 @@ def grouped_forward(nnv, sel, ws):
                                  None, [p.y for p in sel], ws, ws.numel())
 
 
+CONFIG_CALLS = 5     # calls per replayed graph for the other configurations (time reported per call)
+
+
 def stack_report(nnv, torch, np, side, name, dtype, kinds, per_layer=False):
-    """One of the other workload configurations, measured beside the step with the same method:
-    the grouped transformation of every (layer, kind) pair, the grouped forward pass per kind,
-    and the sum over layers of each layer's fastest kind (per-layer times from nnv_time_layer)."""
+    """One of the other workload configurations, measured beside the step by graph replay
+    (CONFIG_CALLS calls per graph, time per call): the grouped transformation of every (layer, kind)
+    pair, the grouped forward pass per kind, and the sum over layers of each layer's fastest kind
+    (per-layer times from nnv_time_layer)."""
     from nnv_workloads import stack, layer_tensors, STACK_NAMES
     dev = torch.device("cuda:0")
     half = dtype == nnv.F16
@@ -189,13 +196,13 @@ def stack_report(nnv, torch, np, side, name, dtype, kinds, per_layer=False):
     tx = [p for p in pairs if p.kind != nnv.DIRECT]
     if tx:
         t = graph_ms(torch, np, side, lambda: nnv.nnv_transform_weights_grouped(
-            [p.desc for p in tx], [p.kind for p in tx], [p.w_raw for p in tx], [p.w_tx for p in tx]))
+            [p.desc for p in tx], [p.kind for p in tx], [p.w_raw for p in tx], [p.w_tx for p in tx]), calls=CONFIG_CALLS)
         by_kind = {}
         for kind in kinds:
             sel = [p for p in tx if p.kind == kind]
             if sel:
                 tk = graph_ms(torch, np, side, lambda sel=sel: nnv.nnv_transform_weights_grouped(
-                    [p.desc for p in sel], [p.kind for p in sel], [p.w_raw for p in sel], [p.w_tx for p in sel]))
+                    [p.desc for p in sel], [p.kind for p in sel], [p.w_raw for p in sel], [p.w_tx for p in sel]), calls=CONFIG_CALLS)
                 by_kind[KIND_LABEL[kind]] = {"layers": len(sel), "ms": round(tk, 4), "MB": round(sum(p.transform_bytes for p in sel) / 1e6, 1),
                                              "GBps": round(sum(p.transform_bytes for p in sel) / (tk * 1e-3) / 1e9, 1)}
         unique = sum({id(p.w_raw): p.raw_bytes for p in tx}.values()) + sum(p.tx_bytes for p in tx)
@@ -209,7 +216,7 @@ def stack_report(nnv, torch, np, side, name, dtype, kinds, per_layer=False):
             continue
         need = nnv.nnv_conv_forward_grouped_workspace_bytes([p.desc for p in sel], [p.kind for p in sel])
         ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
-        t = graph_ms(torch, np, side, lambda sel=sel, ws=ws: grouped_forward(nnv, sel, ws))
+        t = graph_ms(torch, np, side, lambda sel=sel, ws=ws: grouped_forward(nnv, sel, ws), calls=CONFIG_CALLS)
         fw[KIND_LABEL[kind]] = {"layers": len(sel), "ms": round(t, 4),
                                 "TFLOPs_executed": round(sum(p.flops for p in sel) / (t * 1e-3) / 1e12, 2),
                                 "TFLOPs_direct_equivalent": round(sum(p.direct_flops for p in sel) / (t * 1e-3) / 1e12, 2),
