@@ -160,13 +160,16 @@ int nnv_conv_forward_relu(const nnv_conv_desc *desc, nnv_kind kind, const void *
  * layer (Algorithm 1's input, Section 3.3, Table 2), and a batch-1 layer alone neither fills
  * the GPU nor outlasts its own launch: IM2COL_GEMM layers of one storage type share one
  * launch of single-wavefront work items (output tile x range of the reduction) and one
- * reduction launch; Winograd layers of one kind and storage type share three launches (all
+ * reduction launch (float16 layers with filters larger than 1x1: one more, which makes the
+ * channels-last copies of all their inputs); Winograd layers of one kind and storage type share three launches (all
  * input transforms, all tile GEMMs, all output transforms), except those nnv_conv_forward
  * runs as one fused kernel; DEPTHWISE layers of one storage type share one launch; DIRECT
  * layers with groups = 1 and a square 1x1, 3x3, 5x5 or 7x7 filter share up to three (one of
  * them for the layers that run with the lanes along the output channels: K a multiple of 64 and
  * a 3x3 filter with C a multiple of 4, a 1x1 filter with C a multiple of 16, each at stride 1 or
- * 2, or a 7x7 stride-2 filter with at most 4 channels).  The
+ * 2, or a 7x7 stride-2 filter with at most 4 channels); DIRECT layers of depthwise shape
+ * (as the DEPTHWISE kind accepts) share one launch of the depthwise kernel, which reads the
+ * untransformed filters.  The
  * remaining layers, and the layers of a kind of which the call holds only one or two (three
  * for IM2COL_GEMM: the shared launches are laid out to fill the GPU), are executed one after
  * the other as by nnv_conv_forward.  Results per layer are as nnv_conv_forward's up to the
