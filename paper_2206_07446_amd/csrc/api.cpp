@@ -278,9 +278,9 @@ GroupedPlan plan_grouped(int n, const Geo *geos, const nnv_kind *kinds) {
     };
     for (int half = 0; half < 2; ++half) {
         auto same_type = [&](int i) { return (geos[i].dtype == NNV_F16) == (half == 1); };
+        // (the regions of an item launch depend on the item length, which depends on the whole batch: laid out below)
         collect(GroupedPlan::GEMM_ITEMS, NNV_IM2COL_GEMM, kMaxGemmLayers, 4,
-                [&](int i) { return kinds[i] == NNV_IM2COL_GEMM && same_type(i); },
-                [&](int i) { return im2col_items_workspace_bytes(geos[i]); });
+                [&](int i) { return kinds[i] == NNV_IM2COL_GEMM && same_type(i); }, [&](int) { return (size_t)0; });
         collect(GroupedPlan::DIRECT_MANY, NNV_DIRECT, kMaxDirectLayers, 3,
                 [&](int i) { return kinds[i] == NNV_DIRECT && same_type(i) && direct_many_supported(geos[i]); },
                 [&](int) { return (size_t)0; });
@@ -294,6 +294,18 @@ GroupedPlan plan_grouped(int n, const Geo *geos, const nnv_kind *kinds) {
             collect(GroupedPlan::WINO_MANY, kind, kMaxWinoLayers, 2,
                     [&](int i) { return kinds[i] == kind && same_type(i) && wino_many_supported(geos[i], kind); },
                     [&](int i) { return ws_bytes(geos[i], kind); });
+    }
+    for (GroupedPlan::Batch &b : gp.batches) {
+        if (b.cls != GroupedPlan::GEMM_ITEMS) continue;
+        std::vector<Geo> bg;
+        for (int i : b.layers) bg.push_back(geos[i]);
+        const int target = im2col_items_target((int)bg.size(), bg.data());
+        size_t off = 0;
+        for (size_t j = 0; j < b.layers.size(); ++j) {
+            b.offset[j] = off;
+            off += align_up(im2col_items_workspace_bytes(bg[j], target), 256);
+        }
+        gp.bytes = std::max(gp.bytes, off);
     }
     for (int i = 0; i < n; ++i) {
         if (taken[i]) continue;

@@ -1017,25 +1017,50 @@ static ItemPlan plan_items(const Geo &g, const int item_steps) {
     return ip;
 }
 
+// Item length of a launch of these layers.
 // float16 items of a call that fills the chip fewer than three times over are a quarter as long:
 // such a launch ends with its longest items (a 512-channel 3x3 layer is one item of 144 steps per tile
 // otherwise), and a float16 step moves eight times the channels of a float32 one.  Measured on
 // the ResNet-18-, ResNet-50- and VGG-16-shaped stacks: 75 -> 61, 129 -> 123 and (the long items
 // kept) 184 us against 201 us with the short ones.
-constexpr int kItemStepsShortHalf = 36;
+// float32: a launch whose items all fit the chip at once (kItemsResident, less a sixteenth: a launch
+// that fills every slot was measured slower than one that leaves a few free) takes the shortest
+// item length, in steps of 12 down to kItemStepsMin, with which they still do: the launch lasts as
+// long as an item, and the free slots would stay idle.  Measured (us, one call): SqueezeNet-shaped
+// stack 84 -> 64, GoogLeNet 131 -> 101, AlexNet 80 -> 51, MobileNetV2 66 -> 55, ResNet-50 170 -> 159;
+// the ResNet-18-shaped stack (2882 items of 144 steps) keeps its items.
+constexpr int kItemStepsShortHalf = 36, kItemStepsMin = 48;
 constexpr int kItemsResident = 256 * 3 * kItemWaves;
 
-size_t im2col_items_workspace_bytes(const Geo &g) {
-    const ItemPlan ip = plan_items(g, kItemSteps);
-    size_t part = ip.part_bytes;
-    // (which item length a call uses depends on its other layers: room for either)
-    if (g.dtype == NNV_F16) part = std::max(part, plan_items(g, kItemStepsShortHalf).part_bytes);
-    return align_up(part, 256) + align_up(ip.xt_bytes, 256);
+int im2col_items_target(int n, const Geo *geos) {
+    auto total_at = [&](int t) {
+        long tot = 0;
+        for (int i = 0; i < n; ++i) {
+            const ItemPlan p = plan_items(geos[i], t);
+            tot += (long)p.nmt * p.ntn * p.nsplit;
+        }
+        return tot;
+    };
+    const long total = total_at(kItemSteps);
+    if (geos[0].dtype == NNV_F16) return total < 3L * kItemsResident ? kItemStepsShortHalf : kItemSteps;
+    constexpr long fit = (long)kItemsResident * 15 / 16;
+    int best = kItemSteps;
+    if (total <= fit)
+        for (int t = kItemSteps - 12; t >= kItemStepsMin; t -= 12) {
+            if (total_at(t) > fit) break;
+            best = t;
+        }
+    return best;
+}
+
+size_t im2col_items_workspace_bytes(const Geo &g, int target) {
+    const ItemPlan ip = plan_items(g, target);
+    return align_up(ip.part_bytes, 256) + align_up(ip.xt_bytes, 256);
 }
 
 // Launches layers [0, n) (all of one storage type, n <= kMaxGemmLayers) as one item launch plus,
 // if any layer is split, one reduction launch.  ws[i] is layer i's own workspace region of
-// im2col_items_workspace_bytes.
+// im2col_items_workspace_bytes(geos[i], im2col_items_target(n, geos)).
 hipError_t launch_im2col_items(int n, const Geo *geos, const void *const *x, const void *const *w, const float *const *bias,
                                void *const *y, void *const *ws, hipStream_t st) {
     if (n <= 0) return hipSuccess;
@@ -1045,15 +1070,13 @@ hipError_t launch_im2col_items(int n, const Geo *geos, const void *const *x, con
     // of the short ones.
     ItemPlan plans[kMaxGemmLayers];
     int order[kMaxGemmLayers];
-    long total = 0;
-    for (int i = 0; i < n; ++i) {
+    for (int i = 0; i < n; ++i)
         if ((geos[i].dtype == NNV_F16) != half) return hipErrorInvalidValue;
-        plans[i] = plan_items(geos[i], kItemSteps);
-        total += (long)plans[i].nmt * plans[i].ntn * plans[i].nsplit;
+    const int target = im2col_items_target(n, geos);
+    for (int i = 0; i < n; ++i) {
+        plans[i] = plan_items(geos[i], target);
         order[i] = i;
     }
-    if (half && total < 3L * kItemsResident)
-        for (int i = 0; i < n; ++i) plans[i] = plan_items(geos[i], kItemStepsShortHalf);
     auto item_len = [&](int i) { return ceil_div(plans[i].steps, plans[i].nsplit) * plans[i].tm; };
     std::stable_sort(order, order + n, [&](int a, int b) { return item_len(a) > item_len(b); });
     GemmItemTable tbl{};

@@ -84,9 +84,10 @@ hipError_t launch_im2col(const Geo &g, const void *x, const void *w, const float
 
 // Many independent IM2COL_GEMM layers (one storage type, at most kMaxGemmLayers) in one launch of
 // single-wavefront work items, plus one reduction launch if a layer's channels are split; ws[i] is
-// layer i's own region of im2col_items_workspace_bytes bytes.
+// layer i's own region of im2col_items_workspace_bytes(geos[i], im2col_items_target(n, geos)) bytes.
 constexpr int kMaxGemmLayers = 20;
-size_t im2col_items_workspace_bytes(const Geo &g);
+int im2col_items_target(int n, const Geo *geos);             // item length (k-steps) a launch of these layers uses
+size_t im2col_items_workspace_bytes(const Geo &g, int target);
 hipError_t launch_im2col_items(int n, const Geo *geos, const void *const *x, const void *const *w,
                                const float *const *bias, void *const *y, void *const *ws, hipStream_t st);
 
